@@ -1,0 +1,190 @@
+/*
+ * CPU oracle for arbitrary-precision bipolar-INT matrix multiplication.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * GPU library is checked against.  It shares no code, header, table or helper
+ * with the HIP path, and nothing in the product path may call it.
+ *
+ * What is defined here (paper sections in brackets):
+ *   - oracle_bipolar_value      : value of an n-bit bipolar-INT code   [Sec. 3.1, Eq. 1]
+ *   - oracle_gemm_i64           : C = A * W^T on the decoded values,
+ *                                 int64 triple loop                    [Sec. 3.2, Y = WX]
+ *   - oracle_gemm_planes_i64    : the method's own three steps:
+ *                                 decomposition into 1-bit planes,
+ *                                 pairwise 1-bit products, shift-and-add
+ *                                 recovery                             [Sec. 3.2, steps 1-3]
+ *   - oracle_scale_f64          : per-token x per-channel scaling of
+ *                                 the integer result in double
+ *                                 (epilogue; not in the paper, defined
+ *                                 by the build's problem statement)
+ *
+ * Orientation: activations A are M x K codes of p bits, weights W are N x K
+ * codes of q bits, both K-contiguous; C is M x N row-major.  The paper writes
+ * the same contraction as Y = W X with the weights on the left.
+ *
+ * Parity pins: every function here is pinned by tests/test_oracle_pins.py
+ * (closed forms, brute force over all codes, library matmul, invariants).
+ * The paper's worked 2-bit example (Fig. 2) did not survive as numbers, so no
+ * paper-printed value is used: "worked-example parity unpinned"; the n=2 value
+ * table (-3,-1,+1,+3) that Eq. 1 fixes is stored in tests/golden/.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Eq. 1: (x)_D = sum_{i=0}^{n-1} (2 x^(i) - 1) * 2^i, x^(i) the i-th bit of the code. */
+int64_t oracle_bipolar_value(uint32_t code, int nbits)
+{
+    int64_t v = 0;
+    for (int i = 0; i < nbits; ++i) {
+        int64_t bit = (code >> i) & 1u;
+        v += (2 * bit - 1) * ((int64_t)1 << i);
+    }
+    return v;
+}
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Decode a rows x K matrix of codes (one uint8 per element, low nbits bits used)
+ * into int64 values with Eq. 1, element by element. */
+static int64_t *decode_matrix(const uint8_t *codes, int64_t rows, int64_t K, int nbits)
+{
+    int64_t *v = (int64_t *)malloc((size_t)rows * (size_t)K * sizeof(int64_t));
+    if (!v) return NULL;
+    uint32_t mask = (nbits >= 32) ? 0xffffffffu : ((1u << nbits) - 1u);
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t k = 0; k < K; ++k)
+            v[r * K + k] = oracle_bipolar_value(codes[r * K + k] & mask, nbits);
+    return v;
+}
+
+/* Sec. 3.2: Y = W X on decoded values.  Here C[m][n] = sum_k a[m][k] * w[n][k],
+ * accumulated in int64.  Returns 0, or -1 on allocation failure. */
+int oracle_gemm_i64(int64_t M, int64_t N, int64_t K, int p, int q,
+                    const uint8_t *a_codes, const uint8_t *w_codes, int64_t *c)
+{
+    int64_t *a = decode_matrix(a_codes, M, K, p);
+    int64_t *w = decode_matrix(w_codes, N, K, q);
+    if (!a || !w) { free(a); free(w); return -1; }
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t acc = 0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += a[m * K + k] * w[n * K + k];
+            c[m * N + n] = acc;
+        }
+    }
+    free(a);
+    free(w);
+    return 0;
+}
+
+/* Sec. 3.2, the method itself, in the paper's order:
+ *   step 1 (decomposition): A^(j)[m][k] = bit j of the activation code,
+ *                           W^(i)[n][k] = bit i of the weight code;
+ *   step 2 (1-bit MatMul) : Y^(i,j)[m][n] = sum_k s(A^(j)[m][k]) * s(W^(i)[n][k]),
+ *                           s(b) = 2b - 1, i.e. a product of +-1 entries; with the
+ *                           XOR form of the 1-bit product this is
+ *                           K - 2 * (number of k where the two bits differ);
+ *   step 3 (recovery)     : Y = sum_i sum_j 2^(i+j) * Y^(i,j).
+ * The differing-bit count is taken bit by bit (no packed words) so that this
+ * routine stays a readable statement of the identity. */
+int oracle_gemm_planes_i64(int64_t M, int64_t N, int64_t K, int p, int q,
+                           const uint8_t *a_codes, const uint8_t *w_codes, int64_t *c)
+{
+    /* step 1: explicit plane matrices, one byte per bit */
+    uint8_t *ap = (uint8_t *)malloc((size_t)p * (size_t)M * (size_t)K);
+    uint8_t *wp = (uint8_t *)malloc((size_t)q * (size_t)N * (size_t)K);
+    if (!ap || !wp) { free(ap); free(wp); return -1; }
+    for (int j = 0; j < p; ++j)
+        for (int64_t m = 0; m < M; ++m)
+            for (int64_t k = 0; k < K; ++k)
+                ap[((size_t)j * M + m) * K + k] = (a_codes[m * K + k] >> j) & 1u;
+    for (int i = 0; i < q; ++i)
+        for (int64_t n = 0; n < N; ++n)
+            for (int64_t k = 0; k < K; ++k)
+                wp[((size_t)i * N + n) * K + k] = (w_codes[n * K + k] >> i) & 1u;
+
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t y = 0;
+            for (int i = 0; i < q; ++i) {
+                for (int j = 0; j < p; ++j) {
+                    /* step 2: one plane pair */
+                    const uint8_t *arow = ap + ((size_t)j * M + m) * K;
+                    const uint8_t *wrow = wp + ((size_t)i * N + n) * K;
+                    int64_t differ = 0;
+                    for (int64_t k = 0; k < K; ++k)
+                        differ += (arow[k] ^ wrow[k]);
+                    int64_t y_ij = K - 2 * differ;
+                    /* step 3: shift by the two bit positions and sum */
+                    y += y_ij * ((int64_t)1 << (i + j));
+                }
+            }
+            c[m * N + n] = y;
+        }
+    }
+    free(ap);
+    free(wp);
+    return 0;
+}
+
+/* IEEE-754 binary16 bit pattern -> double, exact. */
+double oracle_half_bits_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int exp = (h >> 10) & 0x1f;
+    int man = h & 0x3ff;
+    double v;
+    if (exp == 0) {
+        v = (double)man * (1.0 / 16777216.0);            /* man * 2^-24 (subnormal) */
+    } else if (exp == 31) {
+        v = man ? (0.0 / 0.0) : (1.0 / 0.0);
+    } else {
+        double scale = 1.0;
+        int e = exp - 15;
+        while (e > 0) { scale *= 2.0; --e; }
+        while (e < 0) { scale *= 0.5; ++e; }
+        v = (1.0 + (double)man / 1024.0) * scale;
+    }
+    return sign ? -v : v;
+}
+
+/* Epilogue reference: F[m][n] = C[m][n] * a_scale[m] * w_scale[n] in double.
+ * Scales are given as binary16 bit patterns; a NULL scale vector means 1.
+ * The result is NOT rounded to half: the GPU's half output is compared to it
+ * with a relative tolerance. */
+void oracle_scale_f64(int64_t M, int64_t N, const int64_t *c,
+                      const uint16_t *a_scale, const uint16_t *w_scale, double *f)
+{
+    for (int64_t m = 0; m < M; ++m) {
+        double sa = a_scale ? oracle_half_bits_to_double(a_scale[m]) : 1.0;
+        for (int64_t n = 0; n < N; ++n) {
+            double sw = w_scale ? oracle_half_bits_to_double(w_scale[n]) : 1.0;
+            f[m * N + n] = (double)c[m * N + n] * sa * sw;
+        }
+    }
+}
+
+/* Largest |C| over the result, for the 32-bit output requirement of Sec. 3.2. */
+int64_t oracle_max_abs(int64_t count, const int64_t *c)
+{
+    int64_t best = 0;
+    for (int64_t i = 0; i < count; ++i) {
+        int64_t v = c[i] < 0 ? -c[i] : c[i];
+        if (v > best) best = v;
+    }
+    return best;
+}
