@@ -1,0 +1,139 @@
+#!/usr/bin/env python3
+"""Benchmark of the bipolar-INT GEMM hot path on one MI355X.
+
+Default workload: the square W1A2 case (M = N = K = 4096, 1-bit weights, 2-bit
+activations, int32 output), the shape of the paper's Table 1 on which the headline
+metric is quoted.  One step = one pass of the hot path on device-resident inputs:
+online activation packing (paper Sec. 4.1) followed by the GEMM with on-chip recovery
+(paper Sec. 3.2 / 4.2).  The weights are packed once, outside the timed region, as an
+inference engine would do.
+
+Prints ONE JSON line.  `value` is effective TOPS = 2*M*N*K / step time.  `roofline`
+is for the dominant kernel (the GEMM) from HIP events recorded around every GEMM launch
+of the timed region, on the stream it is launched on.  `cpu_baseline` is the CPU oracle
+timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense int8, published
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+PAPER_W1A2_4096_TOPS = 2 * 4096 ** 3 / 160e-6 / 1e12   # paper Table 1: 160 us on an RTX 3090
+
+# HBM bytes per GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/);
+# None until such a run has been recorded for the kernel that is timed here.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--algo", type=int, default=0, help="kernel choice for apmm_gemm_ex (0 = auto)")
+    return ap.parse_args()
+
+
+def cpu_baseline(case, seed, sample_rows):
+    """Time the oracle (as it stands) on the first `sample_rows` activation rows of the workload."""
+    import oracle
+    from paper_2409_17870_amd import inputs
+    data = inputs.make_case(case, seed)
+    a = data["a_codes"][:sample_rows]
+    t0 = time.perf_counter()
+    oracle.gemm_i64(a, data["w_codes"], case["p"], case["q"])
+    dt = time.perf_counter() - t0
+    ops = 2.0 * sample_rows * case["N"] * case["K"]
+    return {
+        "value": ops / dt / 1e12, "unit": "TOPS", "cores": oracle.num_threads(), "kind": "oracle",
+        "seconds": dt,
+        "sample": "first %d of %d activation rows, all %d output channels, full K=%d" %
+                  (sample_rows, case["M"], case["N"], case["K"]),
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus %d refused)" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2409_17870_amd import binding, inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    binding.load()
+    dev = torch.device("cuda:0")
+
+    case = inputs.config_cases(2)[0]
+    seed = inputs.BASE_SEED + 2
+    M, N, K, p, q = case["M"], case["N"], case["K"], case["p"], case["q"]
+    data = inputs.make_case(case, seed)
+    a_codes = torch.from_numpy(data["a_codes"]).to(dev)
+    w_codes = torch.from_numpy(data["w_codes"]).to(dev)
+    w_packed = binding.apmm_pack_weights(w_codes, q)            # offline
+    a_packed = torch.empty(binding.apmm_packed_bytes(M, K, p), dtype=torch.uint8, device=dev)
+    c = torch.empty((M, N), dtype=torch.int32, device=dev)
+
+    def step(events=None):
+        binding.apmm_pack_activations(a_codes, p, out=a_packed)
+        if events is not None:
+            events[0].record()
+        binding.apmm_gemm(M, N, K, p, q, a_packed, w_packed, c_i32=c, algo=args.algo)
+        if events is not None:
+            events[1].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    gemm_ms = sum(e0.elapsed_time(e1) for e0, e1 in evs) / args.steps
+    ops = 2.0 * M * N * K
+    value = ops / (ms_per_step * 1e-3) / 1e12
+    achieved = ops / (gemm_ms * 1e-3) / 1e12
+
+    out = {
+        "metric": "effective TOPS (2*M*N*K/s), W1A2 bipolar-INT GEMM 4096^3 (activation pack + GEMM)",
+        "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": value / PAPER_W1A2_4096_TOPS,
+        "baseline_note": "paper Table 1: 160 us = %.0f effective TOPS on an NVIDIA RTX 3090 (GEMM only)"
+                         % PAPER_W1A2_4096_TOPS,
+        "dtype": "int8 MFMA operands recombined from 1-bit planes, int32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "square W1A2 GEMM M=N=K=4096, Bernoulli(1/2) bits, int32 output",
+                   "M": M, "N": N, "K": K, "weight_bits": q, "activation_bits": p,
+                   "step": "apmm_pack_activations + apmm_gemm, weights pre-packed"},
+        "gemm_ms": gemm_ms, "pack_ms": ms_per_step - gemm_ms,
+        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel", "achieved": achieved,
+                     "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / INT8_MFMA_PEAK_TOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(case, seed, sample_rows=2048)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,111 @@
+/*
+ * apmm.h - C ABI of the bipolar-INT arbitrary-precision GEMM library for MI355X (gfx950).
+ *
+ * The library computes C = A * W^T where A (M x K activations, p bits) and W (N x K
+ * weights, q bits) hold bipolar-INT codes: bit i of a code contributes (2*bit - 1) * 2^i
+ * (paper Sec. 3.1, Eq. 1), so an n-bit code u has the value 2u - (2^n - 1).
+ * The operands are first decomposed into 1-bit planes, reassembled into 32-bit words
+ * and concatenated into one buffer (paper Sec. 4.1, steps 1-3: apmm_pack_*); the GEMM
+ * multiplies the planes and recovers C = sum_i sum_j 2^(i+j) * D_ij on chip, never in
+ * global memory (paper Sec. 3.2 and Sec. 4.2: apmm_gemm).
+ *
+ * Conventions
+ *  - Every data pointer is a DEVICE pointer owned by the caller.  The library allocates
+ *    no device memory and keeps no state besides a thread-local error string.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is
+ *    enqueued asynchronously on it; the call returns once the kernels are launched.
+ *  - Argument errors are detected on the host before any launch and leave the outputs
+ *    untouched.
+ *  - Codes are one uint8 per element, row-major with K contiguous; only the low `bits`
+ *    bits are significant, higher bits are ignored.
+ *  - Packed buffers are opaque.  Their size is apmm_packed_bytes(); the only contractual
+ *    property is apmm_unpack(apmm_pack_*(x)) == x on the low `bits` bits.  They must be
+ *    16-byte aligned (any hipMalloc / PyTorch allocation is).
+ */
+#ifndef APMM_H
+#define APMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    APMM_OK = 0,
+    APMM_ERR_INVALID_ARG = 1, /* null pointer, negative size, bits outside [1, 8], misaligned buffer */
+    APMM_ERR_UNSUPPORTED = 2, /* valid request that no kernel in this build covers */
+    APMM_ERR_OVERFLOW = 3,    /* K * (2^p - 1) * (2^q - 1) does not fit the 32-bit output */
+    APMM_ERR_WORKSPACE = 4,   /* workspace smaller than apmm_workspace_bytes() */
+    APMM_ERR_HIP = 5          /* a HIP call failed; text in apmm_last_error() */
+} apmm_status;
+
+/* Kernel selection for apmm_gemm_ex.  apmm_gemm uses APMM_ALGO_AUTO. */
+typedef enum {
+    APMM_ALGO_AUTO = 0,
+    APMM_ALGO_VALU_POPCOUNT = 1, /* plane pairs by XOR + popcount on the vector ALU, D_ij = K - 2*popc */
+    APMM_ALGO_MFMA_INT8 = 2,     /* planes recombined to int8 in LDS, int8 MFMA, int32 accumulate */
+    APMM_ALGO_DECODE = 3         /* small-M (M <= 16) weight-streaming kernel */
+} apmm_algo;
+
+/* Bytes of the packed form of a rows x K operand of `bits`-bit codes (paper Sec. 4.1:
+ * `bits` one-bit planes in 32-bit words, concatenated).  Rows are padded to a multiple
+ * of 32 and K to a multiple of 128.  Returns 0 for invalid arguments. */
+size_t apmm_packed_bytes(int64_t rows, int64_t K, int bits);
+
+/* Bytes of scratch apmm_gemm needs for this problem (may be 0). */
+size_t apmm_workspace_bytes(int64_t M, int64_t N, int64_t K, int p, int q);
+
+/* Paper Sec. 4.1 (matrix decomposition and reassembly) for the weight matrix.
+ *   w_codes  : device, N x K uint8 codes, row-major.
+ *   w_packed : device, apmm_packed_bytes(N, K, q) bytes, written entirely.
+ * N == 0 is allowed (nothing is done).  K must be >= 1. */
+apmm_status apmm_pack_weights(const uint8_t *w_codes, int64_t N, int64_t K, int q,
+                              void *w_packed, void *stream);
+
+/* Same transform for the activation matrix (M x K codes of p bits); meant to run online,
+ * directly before apmm_gemm on the same stream. */
+apmm_status apmm_pack_activations(const uint8_t *a_codes, int64_t M, int64_t K, int p,
+                                  void *a_packed, void *stream);
+
+/* Inverse of the pack transform (test aid): writes rows x K uint8 codes. */
+apmm_status apmm_unpack(const void *packed, int64_t rows, int64_t K, int bits,
+                        uint8_t *codes, void *stream);
+
+/* Paper Sec. 3.2 (bit-wise MatMul reconstitution) with the recovery of Sec. 4.2 kept on chip.
+ *   a_packed : device, packed M x K activations of p bits (from apmm_pack_activations)
+ *   w_packed : device, packed N x K weights of q bits     (from apmm_pack_weights)
+ *   c_i32    : device, M x N row-major int32 result, or NULL
+ *   c_f16    : device, M x N row-major IEEE binary16 bit patterns of
+ *              C[m][n] * a_scale[m] * w_scale[n] (product in fp32, one rounding to
+ *              nearest-even at the end), or NULL
+ *   w_scale  : device, N binary16 per-output-channel scales, or NULL (= 1)
+ *   a_scale  : device, M binary16 per-token scales, or NULL (= 1)
+ *   workspace: device scratch of at least apmm_workspace_bytes() bytes (may be NULL if 0)
+ * At least one of c_i32 / c_f16 must be non-NULL.  M == 0 or N == 0 returns APMM_OK
+ * without a launch.  Returns APMM_ERR_OVERFLOW if roundup(K,128)*(2^p-1)*(2^q-1) > INT32_MAX. */
+apmm_status apmm_gemm(int64_t M, int64_t N, int64_t K, int p, int q,
+                      const void *a_packed, const void *w_packed,
+                      int32_t *c_i32, uint16_t *c_f16,
+                      const uint16_t *w_scale, const uint16_t *a_scale,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/* apmm_gemm with an explicit kernel choice (used to compare the two designs).
+ * Returns APMM_ERR_UNSUPPORTED if `algo` does not cover the request. */
+apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q,
+                         const void *a_packed, const void *w_packed,
+                         int32_t *c_i32, uint16_t *c_f16,
+                         const uint16_t *w_scale, const uint16_t *a_scale,
+                         void *workspace, size_t workspace_bytes, void *stream,
+                         int algo);
+
+const char *apmm_status_string(apmm_status status);
+/* Text of the last error on the calling thread ("" if none). */
+const char *apmm_last_error(void);
+int apmm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* APMM_H */

@@ -1,0 +1,160 @@
+// C ABI of the library (include/apmm.h): argument checks and kernel dispatch.  No kernel
+// lives here and nothing is allocated.
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/apmm.h"
+#include "apmm_kernels.h"
+
+namespace {
+
+thread_local char g_error[256] = "";
+
+apmm_status fail(apmm_status st, const char *msg)
+{
+    std::snprintf(g_error, sizeof(g_error), "%s", msg);
+    return st;
+}
+
+apmm_status fail_hip(hipError_t e, const char *where)
+{
+    std::snprintf(g_error, sizeof(g_error), "%s: %s", where, hipGetErrorString(e));
+    return APMM_ERR_HIP;
+}
+
+bool bits_ok(int bits) { return bits >= 1 && bits <= 8; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+apmm_status pack_common(const uint8_t *codes, int64_t rows, int64_t K, int bits, void *packed, void *stream,
+                        const char *what)
+{
+    if (rows < 0 || K < 1 || !bits_ok(bits)) return fail(APMM_ERR_INVALID_ARG, "pack: rows < 0, K < 1 or bits outside [1, 8]");
+    if (rows == 0) return APMM_OK;
+    if (!codes || !packed) return fail(APMM_ERR_INVALID_ARG, "pack: null pointer");
+    if (!aligned16(packed)) return fail(APMM_ERR_INVALID_ARG, "pack: packed buffer must be 16-byte aligned");
+    hipError_t e = apmm::launch_pack(codes, rows, K, bits, static_cast<uint32_t *>(packed),
+                                     static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip(e, what);
+    return APMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t apmm_packed_bytes(int64_t rows, int64_t K, int bits)
+{
+    if (rows < 0 || K < 1 || !bits_ok(bits)) return 0;
+    const int64_t rows_p = apmm::round_up(rows, apmm::kRowBlock);
+    const int64_t k_p = apmm::round_up(K, apmm::kKBlock);
+    return (size_t)rows_p * (size_t)k_p / 8u * (size_t)bits;
+}
+
+size_t apmm_workspace_bytes(int64_t, int64_t, int64_t, int, int) { return 0; }
+
+apmm_status apmm_pack_weights(const uint8_t *w_codes, int64_t N, int64_t K, int q, void *w_packed, void *stream)
+{
+    return pack_common(w_codes, N, K, q, w_packed, stream, "apmm_pack_weights");
+}
+
+apmm_status apmm_pack_activations(const uint8_t *a_codes, int64_t M, int64_t K, int p, void *a_packed,
+                                  void *stream)
+{
+    return pack_common(a_codes, M, K, p, a_packed, stream, "apmm_pack_activations");
+}
+
+apmm_status apmm_unpack(const void *packed, int64_t rows, int64_t K, int bits, uint8_t *codes, void *stream)
+{
+    if (rows < 0 || K < 1 || !bits_ok(bits)) return fail(APMM_ERR_INVALID_ARG, "unpack: rows < 0, K < 1 or bits outside [1, 8]");
+    if (rows == 0) return APMM_OK;
+    if (!codes || !packed) return fail(APMM_ERR_INVALID_ARG, "unpack: null pointer");
+    if (!aligned16(packed)) return fail(APMM_ERR_INVALID_ARG, "unpack: packed buffer must be 16-byte aligned");
+    hipError_t e = apmm::launch_unpack(static_cast<const uint32_t *>(packed), rows, K, bits, codes,
+                                       static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip(e, "apmm_unpack");
+    return APMM_OK;
+}
+
+apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const void *a_packed,
+                         const void *w_packed, int32_t *c_i32, uint16_t *c_f16, const uint16_t *w_scale,
+                         const uint16_t *a_scale, void *workspace, size_t workspace_bytes, void *stream,
+                         int algo)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    if (M < 0 || N < 0 || K < 1 || !bits_ok(p) || !bits_ok(q))
+        return fail(APMM_ERR_INVALID_ARG, "gemm: M < 0, N < 0, K < 1 or bits outside [1, 8]");
+    if (algo < APMM_ALGO_AUTO || algo > APMM_ALGO_DECODE) return fail(APMM_ERR_INVALID_ARG, "gemm: unknown algo");
+    const int64_t k_p = apmm::round_up(K, apmm::kKBlock);
+    const int64_t unit = (int64_t)((1 << p) - 1) * (int64_t)((1 << q) - 1);
+    if (k_p > INT32_MAX / unit) return fail(APMM_ERR_OVERFLOW, "gemm: K * (2^p - 1) * (2^q - 1) exceeds the 32-bit output");
+    if (M == 0 || N == 0) return APMM_OK;
+    if (!a_packed || !w_packed) return fail(APMM_ERR_INVALID_ARG, "gemm: null operand");
+    if (!c_i32 && !c_f16) return fail(APMM_ERR_INVALID_ARG, "gemm: no output requested");
+    if (!aligned16(a_packed) || !aligned16(w_packed))
+        return fail(APMM_ERR_INVALID_ARG, "gemm: packed operands must be 16-byte aligned");
+    if ((c_i32 && (reinterpret_cast<uintptr_t>(c_i32) & 3u)) || (c_f16 && (reinterpret_cast<uintptr_t>(c_f16) & 1u)))
+        return fail(APMM_ERR_INVALID_ARG, "gemm: misaligned output");
+
+    apmm::GemmArgs g;
+    g.M = M; g.N = N; g.K = K;
+    g.nkb = k_p / apmm::kKBlock;
+    g.p = p; g.q = q;
+    g.a = static_cast<const uint32_t *>(a_packed);
+    g.w = static_cast<const uint32_t *>(w_packed);
+    g.c_i32 = c_i32; g.c_f16 = c_f16;
+    g.w_scale = w_scale; g.a_scale = a_scale;
+    g.pad_corr = (int32_t)((k_p - K) * unit);
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (algo == APMM_ALGO_AUTO) {
+        if (M <= 16 && apmm::gemm_decode_supported(g)) algo = APMM_ALGO_DECODE;
+        else if (M > 16 && apmm::gemm_mfma_supported(g)) algo = APMM_ALGO_MFMA_INT8;
+        else algo = APMM_ALGO_VALU_POPCOUNT;
+    }
+    hipError_t e;
+    switch (algo) {
+    case APMM_ALGO_VALU_POPCOUNT:
+        e = apmm::launch_gemm_valu(g, s);
+        break;
+    case APMM_ALGO_MFMA_INT8:
+        if (!apmm::gemm_mfma_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: int8 MFMA kernel covers p, q in 1..4");
+        e = apmm::launch_gemm_mfma(g, s);
+        break;
+    case APMM_ALGO_DECODE:
+        if (!apmm::gemm_decode_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: decode kernel does not cover this request");
+        e = apmm::launch_gemm_decode(g, s);
+        break;
+    default:
+        return fail(APMM_ERR_INVALID_ARG, "gemm: unknown algo");
+    }
+    if (e != hipSuccess) return fail_hip(e, "apmm_gemm");
+    return APMM_OK;
+}
+
+apmm_status apmm_gemm(int64_t M, int64_t N, int64_t K, int p, int q, const void *a_packed, const void *w_packed,
+                      int32_t *c_i32, uint16_t *c_f16, const uint16_t *w_scale, const uint16_t *a_scale,
+                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    return apmm_gemm_ex(M, N, K, p, q, a_packed, w_packed, c_i32, c_f16, w_scale, a_scale, workspace,
+                        workspace_bytes, stream, APMM_ALGO_AUTO);
+}
+
+const char *apmm_status_string(apmm_status status)
+{
+    switch (status) {
+    case APMM_OK: return "ok";
+    case APMM_ERR_INVALID_ARG: return "invalid argument";
+    case APMM_ERR_UNSUPPORTED: return "unsupported";
+    case APMM_ERR_OVERFLOW: return "result exceeds 32 bits";
+    case APMM_ERR_WORKSPACE: return "workspace too small";
+    case APMM_ERR_HIP: return "HIP error";
+    }
+    return "unknown status";
+}
+
+const char *apmm_last_error(void) { return g_error; }
+
+int apmm_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,25 @@
+// Host-side launchers of the library's kernels (internal; the public ABI is include/apmm.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include "apmm_layout.h"
+
+namespace apmm {
+
+// Paper Sec. 4.1: decomposition into planes, reassembly into 32-bit words, concatenation.
+hipError_t launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits, uint32_t *packed,
+                       hipStream_t stream);
+hipError_t launch_unpack(const uint32_t *packed, int64_t rows, int64_t K, int bits, uint8_t *codes,
+                         hipStream_t stream);
+
+// Design B: plane pairs by XOR + popcount on the vector ALU (any p, q in 1..8).
+hipError_t launch_gemm_valu(const GemmArgs &args, hipStream_t stream);
+
+// Design A: planes recombined into int8, int8 MFMA (p, q in 1..7 as far as instantiated).
+bool gemm_mfma_supported(const GemmArgs &args);
+hipError_t launch_gemm_mfma(const GemmArgs &args, hipStream_t stream);
+
+// Small-M weight-streaming kernel (M <= 16).
+bool gemm_decode_supported(const GemmArgs &args);
+hipError_t launch_gemm_decode(const GemmArgs &args, hipStream_t stream);
+
+}  // namespace apmm

@@ -1,0 +1,57 @@
+// Packed bit-plane layout shared by every kernel of the library (paper Sec. 4.1).
+//
+// A rows x K operand of n-bit codes is stored as n one-bit planes in 32-bit words,
+// concatenated tile by tile:
+//
+//   word(rb, kb, r, i, g)   rb = row / 32       row block (rows padded to a multiple of 32)
+//                           kb = k / 128        k block   (K padded to a multiple of 128)
+//                           r  = row % 32
+//                           i  = plane (bit of the code), 0 .. n-1
+//                           g  = (k % 128) / 32 word inside the k block
+//   index = (((rb * nkb + kb) * 32 + r) * n + i) * 4 + g
+//
+// so one (rb, kb) tile is 512*n contiguous bytes and one row of a tile is n x 16 bytes:
+// a whole tile row, all planes, arrives with n 16-byte loads.
+//
+// Inside a word, element e = k % 32 sits at bit 8*(e % 4) + (e / 4): byte c of the word
+// holds elements c, c+4, c+8, ...  Then (word >> t) & 0x01010101 puts the plane bits of
+// four consecutive elements 4t .. 4t+3 into four separate bytes, which is what the
+// expansion to int8 MFMA operands needs; XOR/popcount does not care about bit order
+// as long as both operands use the same one.
+//
+// Padding: elements with k >= K have every plane bit set in BOTH operands.  Their
+// XOR is zero, and each contributes exactly (2^p - 1)(2^q - 1) to an integer dot
+// product, which the kernels subtract again.  Rows >= `rows` are all-zero words and
+// are never stored to C.
+#pragma once
+#include <stdint.h>
+
+namespace apmm {
+
+constexpr int kRowBlock = 32;    // rows per packed tile
+constexpr int kKBlock = 128;     // k elements per packed tile
+constexpr int kWordsPerRow = 4;  // 32-bit words per (row, plane) inside a tile
+
+inline __host__ __device__ int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// index of word g=0 of (row, plane i) in k block kb
+inline __host__ __device__ int64_t tile_row_word(int64_t row, int64_t kb, int64_t nkb, int n, int i)
+{
+    int64_t rb = row / kRowBlock, r = row % kRowBlock;
+    return (((rb * nkb + kb) * kRowBlock + r) * n + i) * kWordsPerRow;
+}
+
+struct GemmArgs {
+    int64_t M, N, K;
+    int64_t nkb;          // roundup(K,128)/128
+    int p, q;
+    const uint32_t *a;    // packed activations
+    const uint32_t *w;    // packed weights
+    int32_t *c_i32;       // may be null
+    uint16_t *c_f16;      // may be null
+    const uint16_t *w_scale;  // may be null
+    const uint16_t *a_scale;  // may be null
+    int32_t pad_corr;     // (Kp - K) * (2^p - 1) * (2^q - 1)
+};
+
+}  // namespace apmm

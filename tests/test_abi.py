@@ -1,0 +1,81 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, sizes are right and argument errors are reported before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "apmm.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2409_17870_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return binding.load()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(apmm_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2409_17870_amd import binding
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_single_hip_runtime_in_process(lib):
+    """The library must bind to the HIP runtime PyTorch already loaded, not bring a second one."""
+    paths = set()
+    with open("/proc/self/maps") as f:
+        for line in f:
+            if "libamdhip64" in line:
+                paths.add(line.split()[-1])
+    assert len(paths) == 1, paths
+
+
+def test_packed_bytes(lib):
+    assert lib.apmm_packed_bytes(32, 128, 1) == 32 * 128 // 8
+    assert lib.apmm_packed_bytes(1, 1, 1) == 32 * 128 // 8           # padded to one tile
+    assert lib.apmm_packed_bytes(4096, 4096, 2) == 4096 * 4096 * 2 // 8
+    assert lib.apmm_packed_bytes(33, 129, 3) == 64 * 256 * 3 // 8
+    assert lib.apmm_packed_bytes(0, 128, 2) == 0
+    assert lib.apmm_packed_bytes(8, 128, 0) == 0 and lib.apmm_packed_bytes(8, 128, 9) == 0
+    assert lib.apmm_packed_bytes(-1, 128, 2) == 0 and lib.apmm_packed_bytes(8, 0, 2) == 0
+    assert lib.apmm_version() >= 100
+
+
+def _gemm(lib, M, N, K, p, q, a=0x1000, w=0x2000, c=0x3000, f=None, algo=0):
+    return lib.apmm_gemm_ex(M, N, K, p, q, a, w, c, f, None, None, None, 0, None, algo)
+
+
+def test_argument_errors_come_before_any_launch(lib):
+    INVALID, UNSUPPORTED, OVERFLOW = 1, 2, 3
+    assert _gemm(lib, 4, 4, 128, 0, 1) == INVALID
+    assert _gemm(lib, 4, 4, 128, 1, 9) == INVALID
+    assert _gemm(lib, -1, 4, 128, 1, 1) == INVALID
+    assert _gemm(lib, 4, 4, 0, 1, 1) == INVALID
+    assert _gemm(lib, 4, 4, 128, 1, 1, a=None) == INVALID
+    assert _gemm(lib, 4, 4, 128, 1, 1, c=None) == INVALID          # no output requested
+    assert _gemm(lib, 4, 4, 128, 1, 1, a=0x1004) == INVALID         # misaligned packed operand
+    assert _gemm(lib, 4, 4, 128, 1, 1, algo=7) == INVALID
+    assert b"" != lib.apmm_last_error()
+    # 2^31 / (255 * 255) = 33025.5: K = 33024 fits, the next k block does not
+    assert _gemm(lib, 0, 4, 33024, 8, 8) == 0                       # M == 0: ok, nothing launched
+    assert _gemm(lib, 4, 4, 33025, 8, 8) == OVERFLOW
+    assert _gemm(lib, 4, 4, 40000, 8, 8) == OVERFLOW
+    assert _gemm(lib, 64, 64, 128, 8, 8, algo=2) == UNSUPPORTED     # int8 MFMA cannot hold 8-bit codes
+    assert lib.apmm_status_string(OVERFLOW) == b"result exceeds 32 bits"
+    assert lib.apmm_pack_weights(None, 4, 128, 2, None, None) == INVALID
+    assert lib.apmm_pack_activations(0x1000, 4, 128, 0, 0x2000, None) == INVALID
+    assert lib.apmm_pack_weights(None, 0, 128, 2, None, None) == 0  # empty operand
+    assert lib.apmm_unpack(None, 3, 128, 2, None, None) == INVALID

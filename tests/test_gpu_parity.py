@@ -1,0 +1,228 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Integer outputs must be bit-exact.  The fp16 epilogue must be within 1e-3 relative
+(+1e-6 absolute) of the oracle's double-precision product, the tolerance the problem
+statement fixes (one fp32 product chain plus one rounding to binary16 is <= 2^-11 + a few
+2^-24 relative).
+"""
+import numpy as np
+import pytest
+
+from paper_2409_17870_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+VALU, MFMA, DECODE = 1, 2, 3
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2409_17870_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load()          # fails loudly if the HIP library is missing
+    return torch, binding
+
+
+def run_case(gpu, data, case, algo=0, want_i32=True, want_f16=None):
+    torch, binding = gpu
+    dev = torch.device("cuda:0")
+    M, N, K, p, q = case["M"], case["N"], case["K"], case["p"], case["q"]
+    a = torch.from_numpy(data["a_codes"]).to(dev)
+    w = torch.from_numpy(data["w_codes"]).to(dev)
+    sa = torch.from_numpy(data["a_scale"]).to(dev) if data["a_scale"] is not None else None
+    sw = torch.from_numpy(data["w_scale"]).to(dev) if data["w_scale"] is not None else None
+    if want_f16 is None:
+        want_f16 = sa is not None or sw is not None
+    wp = binding.apmm_pack_weights(w, q)
+    ap = binding.apmm_pack_activations(a, p)
+    c32, c16 = binding.apmm_gemm(M, N, K, p, q, ap, wp, want_i32=want_i32, want_f16=want_f16,
+                                 w_scale=sw, a_scale=sa, algo=algo)
+    torch.cuda.synchronize()
+    return (c32.cpu().numpy() if c32 is not None else None,
+            c16.cpu().numpy() if c16 is not None else None)
+
+
+def check_f16(got_f16, want_i64, data, oracle):
+    sa = data["a_scale"].view(np.uint16) if data["a_scale"] is not None else None
+    sw = data["w_scale"].view(np.uint16) if data["w_scale"] is not None else None
+    f = oracle.scale_f64(want_i64, sa, sw)
+    got = got_f16.astype(np.float64)
+    assert np.all(np.abs(got - f) <= 1e-3 * np.abs(f) + 1e-6)
+
+
+def algos_for(case):
+    algos = [VALU]
+    if case["p"] <= 4 and case["q"] <= 4:
+        algos.append(MFMA)
+    return algos + [0]
+
+
+# ------------------------------------------------------------- pack layout --
+@pytest.mark.parametrize("rows,K,bits", [(1, 1, 1), (5, 31, 3), (32, 128, 2), (33, 129, 4), (70, 500, 8),
+                                         (16, 512, 2), (100, 4096, 1), (257, 1000, 5)])
+def test_pack_unpack_roundtrip(gpu, rows, K, bits):
+    torch, binding = gpu
+    rng = np.random.default_rng(rows * 7919 + K * 13 + bits)
+    codes = rng.integers(0, 256, size=(rows, K), dtype=np.uint8)     # high bits are dirt
+    dev_codes = torch.from_numpy(codes).to("cuda:0")
+    for pack in (binding.apmm_pack_weights, binding.apmm_pack_activations):
+        packed = pack(dev_codes, bits)
+        assert packed.numel() == binding.apmm_packed_bytes(rows, K, bits)
+        back = binding.apmm_unpack(packed, rows, K, bits).cpu().numpy()
+        assert np.array_equal(back, codes & ((1 << bits) - 1))
+
+
+def test_pack_is_plane_decomposition(gpu):
+    """Sec. 4.1: the packed buffer holds exactly `bits` one-bit planes (popcount per plane matches)."""
+    torch, binding = gpu
+    rows, K, bits = 32, 128, 3
+    rng = np.random.default_rng(5)
+    codes = rng.integers(0, 8, size=(rows, K), dtype=np.uint8)
+    packed = binding.apmm_pack_weights(torch.from_numpy(codes).to("cuda:0"), bits).cpu().numpy()
+    words = packed.view(np.uint32).reshape(rows, bits, 4)            # one tile: [row][plane][word]
+    for i in range(bits):
+        for r in range(rows):
+            ones = sum(bin(int(x)).count("1") for x in words[r, i])
+            assert ones == int(((codes[r] >> i) & 1).sum())
+
+
+# ------------------------------------------------------------- small cases --
+def test_config1_tiny_w1a2(gpu, oracle):
+    case = inputs.config_cases(1)[0]
+    data = inputs.make_case(case, inputs.BASE_SEED + 1)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], case["p"], case["q"])
+    for algo in algos_for(case):
+        c32, _ = run_case(gpu, data, case, algo=algo)
+        assert c32.dtype == np.int32
+        assert np.array_equal(c32.astype(np.int64), want), "algo %d" % algo
+
+
+@pytest.mark.parametrize("p,q", [(p, q) for p in range(1, 5) for q in range(1, 5)])
+def test_all_precisions_several_tiles_ragged(gpu, oracle, p, q):
+    """Shapes spanning several workgroup tiles with ragged M, N and K tails."""
+    for (M, N, K) in [(150, 300, 384), (70, 45, 200), (300, 520, 130)]:
+        case = dict(M=M, N=N, K=K, p=p, q=q, a_dist="bernoulli", scaled=True)
+        data = inputs.make_case(case, 1000 + 17 * p + q)
+        want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+        for algo in algos_for(case):
+            c32, c16 = run_case(gpu, data, case, algo=algo)
+            assert np.array_equal(c32.astype(np.int64), want), "algo %d shape %s" % (algo, (M, N, K))
+            check_f16(c16, want, data, oracle)
+
+
+@pytest.mark.parametrize("p,q", [(8, 8), (5, 7), (8, 1), (1, 6), (7, 3)])
+def test_wide_codes(gpu, oracle, p, q):
+    case = dict(M=37, N=50, K=333, p=p, q=q, a_dist="bernoulli", scaled=False)
+    data = inputs.make_case(case, 2000 + 17 * p + q)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+    c32, _ = run_case(gpu, data, case)
+    assert np.array_equal(c32.astype(np.int64), want)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (1, 257, 128), (16, 1, 4096), (3, 7, 127), (17, 33, 129)])
+def test_degenerate_shapes(gpu, oracle, M, N, K):
+    case = dict(M=M, N=N, K=K, p=2, q=2, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 3000 + M + N + K)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], 2, 2)
+    for algo in algos_for(case):
+        c32, c16 = run_case(gpu, data, case, algo=algo)
+        assert np.array_equal(c32.astype(np.int64), want), "algo %d" % algo
+        check_f16(c16, want, data, oracle)
+
+
+def test_extreme_values_hit_the_bound(gpu, oracle):
+    """All-ones x all-ones and all-ones x all-zeros reach +-K(2^p-1)(2^q-1)."""
+    torch, binding = gpu
+    M, N, K, p, q = 40, 40, 4096, 4, 4
+    a = np.full((M, K), 15, dtype=np.uint8)
+    w = np.full((N, K), 15, dtype=np.uint8)
+    w[::2] = 0
+    data = dict(a_codes=a, w_codes=w, a_scale=None, w_scale=None)
+    want = oracle.gemm_i64(a, w, p, q)
+    assert want.max() == K * 225 and want.min() == -K * 225
+    for algo in (VALU, MFMA):
+        c32, _ = run_case(gpu, data, dict(M=M, N=N, K=K, p=p, q=q), algo=algo)
+        assert np.array_equal(c32.astype(np.int64), want)
+
+
+def test_empty_problem_and_outputs_selection(gpu, oracle):
+    torch, binding = gpu
+    case = dict(M=20, N=24, K=256, p=2, q=1, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 4000)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], 2, 1)
+    c32, c16 = run_case(gpu, data, case, want_i32=False, want_f16=True)
+    assert c32 is None
+    check_f16(c16, want, data, oracle)
+    # fp16 output without scales is a plain conversion (values here are exactly representable)
+    plain = dict(data, a_scale=None, w_scale=None)
+    c32, c16 = run_case(gpu, plain, case, want_i32=True, want_f16=True)
+    assert np.array_equal(c16.astype(np.int64), want)
+    # M == 0: nothing to do
+    empty = torch.empty((0, 24), dtype=torch.int32, device="cuda:0")
+    wp = binding.apmm_pack_weights(torch.from_numpy(data["w_codes"]).to("cuda:0"), 1)
+    binding.apmm_gemm(0, 24, 256, 2, 1, wp, wp, c_i32=empty)
+
+
+def test_deterministic(gpu):
+    case = dict(M=200, N=330, K=1024, p=2, q=2, a_dist="bernoulli", scaled=False)
+    data = inputs.make_case(case, 4100)
+    first, _ = run_case(gpu, data, case)
+    second, _ = run_case(gpu, data, case)
+    assert np.array_equal(first, second)
+
+
+# ----------------------------------------- full-size workload configurations --
+def sampled_check(gpu, oracle, case, seed, n_rows=48, n_cols=48):
+    """Full-size run in the default launch configuration; the oracle recomputes a sample of
+    rows x columns, and two checksums that hold at any size cover every output."""
+    data = inputs.make_case(case, seed)
+    c32, c16 = run_case(gpu, data, case)
+    M, N, K, p, q = case["M"], case["N"], case["K"], case["p"], case["q"]
+    rng = np.random.default_rng(seed)
+    rows = np.sort(rng.choice(M, size=min(n_rows, M), replace=False))
+    cols = np.sort(rng.choice(N, size=min(n_cols, N), replace=False))
+    # always include the corners and tile borders
+    rows = np.unique(np.concatenate([rows, [0, M - 1], [r for r in (255, 256, 127, 128) if r < M]]))
+    cols = np.unique(np.concatenate([cols, [0, N - 1], [c for c in (255, 256, 127, 128) if c < N]]))
+    want = oracle.gemm_i64(data["a_codes"][rows], data["w_codes"][cols], p, q)
+    assert np.array_equal(c32[np.ix_(rows, cols)].astype(np.int64), want)
+    if c16 is not None:
+        sub = dict(a_scale=data["a_scale"][rows] if data["a_scale"] is not None else None,
+                   w_scale=data["w_scale"][cols] if data["w_scale"] is not None else None)
+        check_f16(c16[np.ix_(rows, cols)], want, sub, oracle)
+    # checksums over ALL outputs: sum_m C[m][n] = (sum_m a[m]) . w[n] and the same for rows
+    av = 2 * data["a_codes"].astype(np.int64) - ((1 << p) - 1)
+    wv = 2 * data["w_codes"].astype(np.int64) - ((1 << q) - 1)
+    c64 = c32.astype(np.int64)
+    assert np.array_equal(c64.sum(axis=0), wv @ av.sum(axis=0))
+    assert np.array_equal(c64.sum(axis=1), av @ wv.sum(axis=0))
+    assert np.all((c64 - K) % 2 == 0)
+
+
+def test_config2_square_4096_w1a2(gpu, oracle):
+    sampled_check(gpu, oracle, inputs.config_cases(2)[0], inputs.BASE_SEED + 2)
+
+
+@pytest.mark.parametrize("idx", range(9))
+def test_config3_decode_w2a2(gpu, oracle, idx):
+    case = inputs.config_cases(3)[idx]
+    data = inputs.make_case(case, inputs.BASE_SEED + 3)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"][:512], case["p"], case["q"])
+    c32, c16 = run_case(gpu, data, case, want_i32=True, want_f16=True)
+    assert np.array_equal(c32[:, :512].astype(np.int64), want)
+    sub = dict(a_scale=data["a_scale"], w_scale=data["w_scale"][:512])
+    check_f16(c16[:, :512], want, sub, oracle)
+    av = 2 * data["a_codes"].astype(np.int64) - 3
+    wv = 2 * data["w_codes"].astype(np.int64) - 3
+    assert np.array_equal(c32.astype(np.int64), av @ wv.T)       # tiny M: whole result by library matmul
+
+
+@pytest.mark.parametrize("idx", range(6))
+def test_config4_prefill_w1a4_w2a4(gpu, oracle, idx):
+    sampled_check(gpu, oracle, inputs.config_cases(4)[idx], inputs.BASE_SEED + 4)
+
+
+@pytest.mark.parametrize("idx", [0, 4, 6])
+def test_config5_decoder_layer_w2a4(gpu, oracle, idx):
+    sampled_check(gpu, oracle, inputs.config_cases(5)[idx], inputs.BASE_SEED + 5 + idx)
