@@ -2,12 +2,18 @@
 //
 // Paper Sec. 3.2 recovers C = sum_i sum_j 2^(i+j) * D_ij from p*q one-bit products.  The
 // matrix unit of gfx950 multiplies int8, not single bits, so the shift-and-add is moved in
-// front of the multiplier: the planes of each operand are combined into the int8 value
-//   v = sum_i (2*b_i - 1) * 2^i                                   (paper Eq. 1)
-// while the tile is copied from registers to LDS, and ONE int8 MFMA pass produces
-// sum_k a_k * w_k = sum_ij 2^(i+j) D_ij directly.  This is the recovery of paper Sec. 4.2
-// done entirely in registers/LDS (nothing but C reaches global memory), at the cost of one
-// MFMA pass instead of p*q.
+// front of the multiplier: while the tile is copied from registers to LDS, the planes of
+// each operand are combined into the code u = sum_i b_i 2^i as an int8 byte; by paper Eq. 1 the
+// value is v = sum_i (2*b_i - 1) * 2^i = 2u - (2^n - 1).  ONE int8 MFMA pass gives
+// S = sum_k ua_k * uw_k, and with the row sums of the codes (weighted popcounts of the planes,
+// taken by the same threads that expand them)
+//   C = sum_k (2 ua_k - ca)(2 uw_k - cw),   ca = 2^p - 1, cw = 2^q - 1
+//     = 4 S - 2 cw PA[m] - 2 ca PW[n] + K ca cw,
+//   PA[m] = sum_i 2^i * popcount(plane i of row m)  (padded k positions included: they hold the
+//   code ca resp. cw in both operands, which is why the true K appears in the constant),
+// which equals sum_ij 2^(i+j) D_ij.  This is the recovery of paper Sec. 4.2 done entirely in
+// registers/LDS (nothing but C reaches global memory), at the cost of one MFMA pass instead
+// of p*q, and the expansion costs one AND(-OR) per plane plus one rotate per four elements.
 //
 // Workgroup = 256 threads = 2 x 2 waves; wave tile (32*WM) x (32*WN), workgroup tile
 // BM x BN = (64*WM) x (64*WN); k step 128 (one packed tile per row block).
@@ -54,21 +60,17 @@ __device__ __forceinline__ void static_for(F &&f)
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-// Dword t (elements 4t .. 4t+3) of the int8 expansion of one 32-element group given its planes w[0..NB-1].
-// Two's-complement byte of v = 2u + 1 - 2^NB: collect x = 2u per byte (plane i to bit i+1), then
-// (x + (0x80 - 2^NB)) ^ 0x81; the sum stays below 0x100 for NB <= 7, so bytes never interact.
+// Dword t (elements 4t .. 4t+3) of the int8 expansion of one 32-element group given its planes
+// w[0..NB-1]: byte = code u.  Plane i is stored rotated left by i, so its bits for these four
+// elements are at in-byte position (t + i) % 8, and one rotate right by t brings every plane to
+// its own bit i (apmm_layout.h).
 template <int NB>
 __device__ __forceinline__ uint32_t expand_dword(const uint32_t (&w)[NB], int t)
 {
-    constexpr uint32_t bias = (uint32_t)(0x80 - (1 << NB)) * 0x01010101u;
-    uint32_t x = 0;
+    uint32_t y = 0;
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-        const int sh = t - (i + 1);
-        const uint32_t s = (sh >= 0) ? (w[i] >> sh) : (w[i] << (-sh));
-        x |= s & (0x01010101u << (i + 1));
-    }
-    return (x + bias) ^ 0x81818181u;
+    for (int i = 0; i < NB; ++i) y |= w[i] & (0x01010101u << ((t + i) % 8));
+    return t ? __builtin_rotateright32(y, t) : y;
 }
 
 // Per-thread share of one operand's workgroup tile: WX units, one unit = (row, 32-k word group).
@@ -101,16 +103,22 @@ struct Loader {
                 regs[s][i] = src[s][kb * (kRowBlock * kWordsPerRow * NB) + i * kWordsPerRow];
     }
     // whole share at once (prologue)
-    __device__ __forceinline__ void expand_to_lds(uint8_t *stage) const
+    __device__ __forceinline__ void expand_to_lds(uint8_t *stage, uint32_t (&counts)[NB]) const
     {
         uint32_t o[4];
 #pragma unroll
-        for (int task = 0; task < 8 * WX; ++task) expand_task(stage, task, o);
+        for (int task = 0; task < 8 * WX; ++task) expand_task(stage, task, o, counts);
     }
-    // one dword of the share: task = 8 * unit + t; every fourth task stores 16 bytes to LDS
-    __device__ __forceinline__ void expand_task(uint8_t *stage, int task, uint32_t (&o)[4]) const
+    // one dword of the share: task = 8 * unit + t; every fourth task stores 16 bytes to LDS, and the
+    // first task of a unit adds the unit's plane popcounts to `counts`
+    __device__ __forceinline__ void expand_task(uint8_t *stage, int task, uint32_t (&o)[4],
+                                                uint32_t (&counts)[NB]) const
     {
         const int s = task / 8, t = task % 8;
+        if (t == 0) {
+#pragma unroll
+            for (int i = 0; i < NB; ++i) counts[i] += __popc(regs[s][i]);
+        }
         o[t % 4] = expand_dword<NB>(regs[s], t);
         if (t % 4 == 3)
             *reinterpret_cast<uint4 *>(stage + lds_off[s] + (t / 4) * 512) = make_uint4(o[0], o[1], o[2], o[3]);
@@ -154,8 +162,14 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int til
     const int64_t last = g.nkb - 1;
     la.fetch(0);
     lb.fetch(0);
-    la.expand_to_lds(lds);
-    lb.expand_to_lds(lds + A_STAGE);
+    // per plane: set bits of this thread's units so far (all units of a thread lie in one row)
+    uint32_t pop_a[P], pop_b[Q];
+#pragma unroll
+    for (int i = 0; i < P; ++i) pop_a[i] = 0;
+#pragma unroll
+    for (int i = 0; i < Q; ++i) pop_b[i] = 0;
+    la.expand_to_lds(lds, pop_a);
+    lb.expand_to_lds(lds + A_STAGE, pop_b);
     la.fetch(last < 1 ? last : 1);
     lb.fetch(last < 1 ? last : 1);
     __syncthreads();
@@ -179,6 +193,12 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int til
         const int64_t kf = (kb + 2 <= last) ? kb + 2 : last;  // clamped: the surplus fetches are discarded
         la.fetch(kf);
         lb.fetch(kf);
+        // the last iteration re-expands the final k block: its popcounts must not be counted twice
+        uint32_t cnt_a[P], cnt_b[Q];
+#pragma unroll
+        for (int i = 0; i < P; ++i) cnt_a[i] = 0;
+#pragma unroll
+        for (int i = 0; i < Q; ++i) cnt_b[i] = 0;
 
         v4i af[2][WM], bf[2][WN];
         // fragment r of 32-k step ks: r = 0 -> A block 0, r = 1..WN -> B blocks, then the other A blocks
@@ -214,50 +234,108 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int til
                 constexpr int task = decltype(t_c)::value;
                 if constexpr (task * MFMAS / TASKS == i) {
                     if constexpr (task < TASKS_A)
-                        ea.expand_task(nxt, task, oa);
+                        ea.expand_task(nxt, task, oa, cnt_a);
                     else
-                        eb.expand_task(nxt + A_STAGE, task - TASKS_A, ob);
+                        eb.expand_task(nxt + A_STAGE, task - TASKS_A, ob, cnt_b);
                 }
             });
             __builtin_amdgcn_sched_barrier(0);
         });
+        const uint32_t keep = (kb < last) ? 0xffffffffu : 0u;
+#pragma unroll
+        for (int i = 0; i < P; ++i) pop_a[i] += cnt_a[i] & keep;
+#pragma unroll
+        for (int i = 0; i < Q; ++i) pop_b[i] += cnt_b[i] & keep;
         __syncthreads();
     }
+
+    // Row and column terms of the recovery.  A thread's units all lie in row tid % BX of its operand
+    // tile; 256 / BX threads share a row, each leaves its partial in LDS (free now: the loop ended
+    // with a barrier) and the readers add them up.
+    constexpr int SHARE_A = kThreads / BM > 0 ? kThreads / BM : 1;
+    constexpr int SHARE_B = kThreads / BN > 0 ? kThreads / BN : 1;
+    int32_t *sum_a = reinterpret_cast<int32_t *>(lds);        // [SHARE_A][BM]
+    int32_t *sum_b = sum_a + SHARE_A * BM;                    // [SHARE_B][BN]
+    {
+        uint32_t wa = 0, wb = 0;
+#pragma unroll
+        for (int i = 0; i < P; ++i) wa += pop_a[i] << i;
+#pragma unroll
+        for (int i = 0; i < Q; ++i) wb += pop_b[i] << i;
+        sum_a[(tid / BM) * BM + tid % BM] = (int32_t)wa;
+        sum_b[(tid / BN) * BN + tid % BN] = (int32_t)wb;
+    }
+    __syncthreads();
+    // C = 4 S - 2 cw PA[m] - 2 ca PW[n] + K ca cw, in wrapping 32-bit arithmetic (C itself fits)
+    constexpr uint32_t ca = (1u << P) - 1, cw = (1u << Q) - 1;
+    const uint32_t base = (uint32_t)g.K * ca * cw;
 
     // Accumulator layout of the 32x32 MFMA: lane l, register v holds
     //   row = 8*(v/4) + 4*(l/32) + v%4, column = l%32.
     const int col = lane & 31, rsub = (lane >> 5) * 4;
+    uint32_t col_term[WN];
+    float sw[WN];
+#pragma unroll
+    for (int bj = 0; bj < WN; ++bj) {
+        const int nl = (wave_n * WN + bj) * 32 + col;
+        uint32_t pw = 0;
+#pragma unroll
+        for (int h = 0; h < SHARE_B; ++h) pw += (uint32_t)sum_b[h * BN + nl];
+        col_term[bj] = base - 2u * ca * pw;
+        const int64_t n = n0 + nl;
+        sw[bj] = (g.w_scale && n < g.N) ? half_bits_to_float(g.w_scale[n]) : 1.0f;
+    }
+
+    // The output mode and the border test are uniform over the workgroup: pick one of six
+    // straight-line store sequences instead of testing per element.
+    const int64_t m_lane = m0 + wave_m * WM * 32 + rsub;  // row of (bi = 0, v4 = 0, r = 0)
+    const int64_t n_lane = n0 + wave_n * WN * 32 + col;   // column of bj = 0
+    auto emit = [&](auto guard_c, auto i32_c, auto f16_c) __attribute__((always_inline)) {
+        constexpr bool GUARD = decltype(guard_c)::value, I32 = decltype(i32_c)::value, F16 = decltype(f16_c)::value;
+        int32_t *ci = I32 ? g.c_i32 + m_lane * g.N + n_lane : nullptr;
+        uint16_t *ch = F16 ? g.c_f16 + m_lane * g.N + n_lane : nullptr;
+#pragma unroll
+        for (int bi = 0; bi < WM; ++bi) {
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const int ml = (wave_m * WM + bi) * 32 + 8 * v4 + rsub;  // first of four consecutive rows
+                int4 pa = *reinterpret_cast<const int4 *>(sum_a + ml);
+#pragma unroll
+                for (int h = 1; h < SHARE_A; ++h) {
+                    const int4 more = *reinterpret_cast<const int4 *>(sum_a + h * BM + ml);
+                    pa.x += more.x; pa.y += more.y; pa.z += more.z; pa.w += more.w;
+                }
+                const uint32_t row_term[4] = {0u - 2u * cw * (uint32_t)pa.x, 0u - 2u * cw * (uint32_t)pa.y,
+                                              0u - 2u * cw * (uint32_t)pa.z, 0u - 2u * cw * (uint32_t)pa.w};
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int64_t row = (int64_t)(bi * 32 + 8 * v4 + r);  // relative to m_lane
+                    if (GUARD && m_lane + row >= g.M) continue;
+                    float sa = 1.0f;
+                    if constexpr (F16) sa = g.a_scale ? half_bits_to_float(g.a_scale[m_lane + row]) : 1.0f;
+#pragma unroll
+                    for (int bj = 0; bj < WN; ++bj) {
+                        if (GUARD && n_lane + bj * 32 >= g.N) continue;
+                        const uint32_t c = ((uint32_t)acc[bi][bj][4 * v4 + r] << 2) + row_term[r] + col_term[bj];
+                        if constexpr (I32) ci[row * g.N + bj * 32] = (int32_t)c;
+                        if constexpr (F16) ch[row * g.N + bj * 32] = float_to_half_bits((float)(int32_t)c * sa * sw[bj]);
+                    }
+                }
+            }
+        }
+    };
+    using T = std::true_type;
+    using F = std::false_type;
     const bool interior = (m0 + BM <= g.M) && (n0 + BN <= g.N);
+    const bool i32 = g.c_i32 != nullptr, f16 = g.c_f16 != nullptr;
     if (interior) {
-#pragma unroll
-        for (int bj = 0; bj < WN; ++bj) {
-            const int64_t n = n0 + (wave_n * WN + bj) * 32 + col;
-            const float sw = load_scale(g.w_scale, n);
-#pragma unroll
-            for (int bi = 0; bi < WM; ++bi) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int64_t m = m0 + (wave_m * WM + bi) * 32 + 8 * (v / 4) + rsub + (v % 4);
-                    store_output(g, m, n, acc[bi][bj][v] - g.pad_corr, load_scale(g.a_scale, m), sw);
-                }
-            }
-        }
+        if (i32 && !f16) emit(F{}, T{}, F{});
+        else if (!i32 && f16) emit(F{}, F{}, T{});
+        else emit(F{}, T{}, T{});
     } else {
-#pragma unroll
-        for (int bj = 0; bj < WN; ++bj) {
-            const int64_t n = n0 + (wave_n * WN + bj) * 32 + col;
-            if (n >= g.N) continue;
-            const float sw = load_scale(g.w_scale, n);
-#pragma unroll
-            for (int bi = 0; bi < WM; ++bi) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int64_t m = m0 + (wave_m * WM + bi) * 32 + 8 * (v / 4) + rsub + (v % 4);
-                    if (m >= g.M) continue;
-                    store_output(g, m, n, acc[bi][bj][v] - g.pad_corr, load_scale(g.a_scale, m), sw);
-                }
-            }
-        }
+        if (i32 && !f16) emit(T{}, T{}, F{});
+        else if (!i32 && f16) emit(T{}, F{}, T{});
+        else emit(T{}, T{}, T{});
     }
 }
 

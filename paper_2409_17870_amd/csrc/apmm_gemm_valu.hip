@@ -32,9 +32,14 @@ __global__ __launch_bounds__(kTile * kTile) void gemm_valu_kernel(GemmArgs g)
         for (int i = 0; i < q; ++i) {
             const uint4 wv = wrow[i];
             for (int j = 0; j < p; ++j) {
+                // plane words are stored rotated by their plane index: bring the activation plane
+                // to the weight plane's rotation before comparing
                 const uint4 av = arow[j];
-                const uint32_t pc = __popc(av.x ^ wv.x) + __popc(av.y ^ wv.y) + __popc(av.z ^ wv.z) +
-                                    __popc(av.w ^ wv.w);
+                const int r = (plane_rotation(j) - plane_rotation(i)) & 31;
+                const uint32_t pc = __popc(__builtin_rotateright32(av.x, r) ^ wv.x) +
+                                    __popc(__builtin_rotateright32(av.y, r) ^ wv.y) +
+                                    __popc(__builtin_rotateright32(av.z, r) ^ wv.z) +
+                                    __popc(__builtin_rotateright32(av.w, r) ^ wv.w);
                 weighted += pc << (i + j);
             }
         }

@@ -13,11 +13,14 @@
 // so one (rb, kb) tile is 512*n contiguous bytes and one row of a tile is n x 16 bytes:
 // a whole tile row, all planes, arrives with n 16-byte loads.
 //
-// Inside a word, element e = k % 32 sits at bit 8*(e % 4) + (e / 4): byte c of the word
-// holds elements c, c+4, c+8, ...  Then (word >> t) & 0x01010101 puts the plane bits of
-// four consecutive elements 4t .. 4t+3 into four separate bytes, which is what the
-// expansion to int8 MFMA operands needs; XOR/popcount does not care about bit order
-// as long as both operands use the same one.
+// Inside a word, element e = k % 32 of plane i sits at bit (8*(e % 4) + (e / 4) + i) mod 32:
+// the "natural" word, whose byte c holds elements c, c+4, c+8, ..., rotated left by i.
+// Masking plane i with 0x01010101 << ((t + i) % 8) keeps the bits of the four elements
+// 4t .. 4t+3; OR-ing the masked planes and rotating right by t leaves, in each of the four
+// bytes, bit i = plane bit i, i.e. the code u of the element as a byte.  That is the whole
+// expansion to int8 MFMA operands: one AND(-OR) per plane and one rotate per four elements.
+// XOR/popcount kernels rotate a plane word by the difference of the plane indices to compare
+// planes of different index.
 //
 // Padding: elements with k >= K have every plane bit set in BOTH operands.  Their
 // XOR is zero, and each contributes exactly (2^p - 1)(2^q - 1) to an integer dot
@@ -31,6 +34,9 @@ namespace apmm {
 constexpr int kRowBlock = 32;    // rows per packed tile
 constexpr int kKBlock = 128;     // k elements per packed tile
 constexpr int kWordsPerRow = 4;  // 32-bit words per (row, plane) inside a tile
+
+// left rotation applied to the natural word of plane i
+inline __host__ __device__ int plane_rotation(int i) { return i; }
 
 inline __host__ __device__ int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
