@@ -12,7 +12,7 @@ import torch  # imported before the library so that both share one HIP runtime (
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libapmm.so")
 
-ALGO_AUTO, ALGO_VALU_POPCOUNT, ALGO_MFMA_INT8, ALGO_DECODE = 0, 1, 2, 3
+ALGO_AUTO, ALGO_VALU_POPCOUNT, ALGO_MFMA_INT8, ALGO_DECODE, ALGO_MFMA_FP4 = 0, 1, 2, 3, 4
 
 EXPORTS = [
     "apmm_packed_bytes", "apmm_workspace_bytes", "apmm_pack_weights", "apmm_pack_activations",

@@ -84,7 +84,7 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
     (void)workspace_bytes;
     if (M < 0 || N < 0 || K < 1 || !bits_ok(p) || !bits_ok(q))
         return fail(APMM_ERR_INVALID_ARG, "gemm: M < 0, N < 0, K < 1 or bits outside [1, 8]");
-    if (algo < APMM_ALGO_AUTO || algo > APMM_ALGO_DECODE) return fail(APMM_ERR_INVALID_ARG, "gemm: unknown algo");
+    if (algo < APMM_ALGO_AUTO || algo > APMM_ALGO_MFMA_FP4) return fail(APMM_ERR_INVALID_ARG, "gemm: unknown algo");
     const int64_t k_p = apmm::round_up(K, apmm::kKBlock);
     const int64_t unit = (int64_t)((1 << p) - 1) * (int64_t)((1 << q) - 1);
     if (k_p > INT32_MAX / unit) return fail(APMM_ERR_OVERFLOW, "gemm: K * (2^p - 1) * (2^q - 1) exceeds the 32-bit output");
@@ -109,6 +109,7 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (algo == APMM_ALGO_AUTO) {
         if (M <= 16 && apmm::gemm_decode_supported(g)) algo = APMM_ALGO_DECODE;
+        else if (M > 16 && apmm::gemm_mfma_fp4_supported(g)) algo = APMM_ALGO_MFMA_FP4;
         else if (M > 16 && apmm::gemm_mfma_supported(g)) algo = APMM_ALGO_MFMA_INT8;
         else algo = APMM_ALGO_VALU_POPCOUNT;
     }
@@ -120,6 +121,10 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
     case APMM_ALGO_MFMA_INT8:
         if (!apmm::gemm_mfma_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: int8 MFMA kernel covers p, q in 1..4");
         e = apmm::launch_gemm_mfma(g, s);
+        break;
+    case APMM_ALGO_MFMA_FP4:
+        if (!apmm::gemm_mfma_fp4_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: FP4 MFMA kernel covers p, q in 1..2 and K up to 2^20");
+        e = apmm::launch_gemm_mfma_fp4(g, s);
         break;
     case APMM_ALGO_DECODE:
         if (!apmm::gemm_decode_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: decode kernel does not cover this request");

@@ -1,5 +1,6 @@
-// Dispatch of the int8 MFMA GEMM (design A) over the activation width; the kernels are
-// instantiated in apmm_gemm_mfma_p<P>.hip so that they compile in parallel.
+// Dispatch of the MFMA GEMMs (design A).  The kernels are instantiated in
+// apmm_gemm_mfma_p<P>.hip (int8 operands) and apmm_gemm_mfma_fp4.hip (E2M1 operands) so that
+// they compile in parallel.
 #include "apmm_kernels.h"
 
 namespace apmm {
@@ -8,6 +9,7 @@ hipError_t launch_gemm_mfma_p1(const GemmArgs &g, hipStream_t stream);
 hipError_t launch_gemm_mfma_p2(const GemmArgs &g, hipStream_t stream);
 hipError_t launch_gemm_mfma_p3(const GemmArgs &g, hipStream_t stream);
 hipError_t launch_gemm_mfma_p4(const GemmArgs &g, hipStream_t stream);
+hipError_t launch_gemm_mfma_fp4_impl(const GemmArgs &g, hipStream_t stream);
 
 // p, q in 1..4 are instantiated.  The raw MFMA sum S = sum ua * uw is bounded by the same
 // K' (2^p - 1)(2^q - 1) <= INT32_MAX that the ABI checks, so no further limit applies.
@@ -23,5 +25,15 @@ hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t stream)
     }
     return hipErrorInvalidValue;
 }
+
+// E2M1 holds the codes 0..3 exactly (as 0, 0.5, 1, 1.5); the fp32 accumulator holds S/4 exactly
+// while 9 K' / 4 stays below 2^22 quarter units, i.e. for every K' the ABI's 32-bit bound admits
+// up to 2^20; larger K goes to the int8 kernel.
+bool gemm_mfma_fp4_supported(const GemmArgs &g)
+{
+    return g.p >= 1 && g.p <= 2 && g.q >= 1 && g.q <= 2 && g.nkb * kKBlock <= (1 << 20);
+}
+
+hipError_t launch_gemm_mfma_fp4(const GemmArgs &g, hipStream_t stream) { return launch_gemm_mfma_fp4_impl(g, stream); }
 
 }  // namespace apmm

@@ -1,36 +1,44 @@
-// Design A: bit planes recombined into int8 on chip, int8 MFMA, int32 accumulate.
+// Design A: bit planes recombined into matrix-unit operands on chip, one MFMA pass.
 //
 // Paper Sec. 3.2 recovers C = sum_i sum_j 2^(i+j) * D_ij from p*q one-bit products.  The
-// matrix unit of gfx950 multiplies int8, not single bits, so the shift-and-add is moved in
-// front of the multiplier: while the tile is copied from registers to LDS, the planes of
-// each operand are combined into the code u = sum_i b_i 2^i as an int8 byte; by paper Eq. 1 the
-// value is v = sum_i (2*b_i - 1) * 2^i = 2u - (2^n - 1).  ONE int8 MFMA pass gives
-// S = sum_k ua_k * uw_k, and with the row sums of the codes (weighted popcounts of the planes,
-// taken by the same threads that expand them)
+// matrix unit of gfx950 multiplies small numbers, not single bits, so the shift-and-add is
+// moved in front of the multiplier: while the tile is copied from registers to LDS, the planes
+// of each operand are combined into the code u = sum_i b_i 2^i; by paper Eq. 1 the value is
+// v = sum_i (2*b_i - 1) * 2^i = 2u - (2^n - 1).  ONE MFMA pass gives S = sum_k ua_k * uw_k, and
+// with the row sums of the codes (weighted popcounts of the planes, taken by the same threads
+// that expand them)
 //   C = sum_k (2 ua_k - ca)(2 uw_k - cw),   ca = 2^p - 1, cw = 2^q - 1
 //     = 4 S - 2 cw PA[m] - 2 ca PW[n] + K ca cw,
 //   PA[m] = sum_i 2^i * popcount(plane i of row m)  (padded k positions included: they hold the
 //   code ca resp. cw in both operands, which is why the true K appears in the constant),
 // which equals sum_ij 2^(i+j) D_ij.  This is the recovery of paper Sec. 4.2 done entirely in
 // registers/LDS (nothing but C reaches global memory), at the cost of one MFMA pass instead
-// of p*q, and the expansion costs one AND(-OR) per plane plus one rotate per four elements.
+// of p*q, and the expansion costs one AND(-OR) per plane plus one rotate per output dword.
+//
+// Two operand formats:
+//   INT8: code u as a byte, v_mfma_i32_32x32x32_i8, int32 accumulate (p, q <= 4 instantiated).
+//   FP4 : code u as the E2M1 pattern 00uu, whose value is u/2 (patterns 0..3 are 0, 0.5, 1, 1.5),
+//         v_mfma_scale_f32_32x32x64_f8f6f4 with unit scales, fp32 accumulate.  Every product is a
+//         multiple of 1/4 below 2.25 and every partial sum is exactly representable (K < 2^20),
+//         so 16 * acc = 4 S is exact whatever the summation order.  Twice the MFMA rate of int8;
+//         needs p, q <= 2.
 //
 // Workgroup = 256 threads = 2 x 2 waves; wave tile (32*WM) x (32*WN), workgroup tile
-// BM x BN = (64*WM) x (64*WN); k step 128 (one packed tile per row block).
-// Per k step (paper Sec. 4.2, items 2 and 3: K partition and ping-pong buffers):
-//   global -> registers : packed plane words two k blocks ahead (P + Q words per row and 32 k)
-//   registers -> LDS    : expand the next k block to int8 in MFMA operand order, into the idle buffer
-//   LDS -> MFMA         : ds_read_b128 fragments of the current buffer, v_mfma_i32_32x32x32_i8
-// The three activities of one k step sit in one basic block and are interleaved
-// instruction by instruction (one MFMA, then its share of expansion VALU work and LDS
-// traffic), because a wave owns its SIMD alone (512 registers) and nothing else would
-// cover the matrix unit while the VALU expands.
+// BM x BN = (64*WM) x (64*WN).  One pipeline stage = four MFMA k steps = 128 k (INT8, one packed
+// k block) or 256 k (FP4, two packed k blocks), double buffered in LDS (paper Sec. 4.2, items 2
+// and 3: K partition and ping-pong buffers).  Per stage:
+//   global -> registers : packed plane words of the stage after next
+//   registers -> LDS    : expand the next stage to operand bytes in MFMA order, into the idle buffer
+//   LDS -> MFMA         : ds_read_b128 fragments of the current buffer, one k step ahead of their MFMAs
+// The three activities sit in one basic block and are interleaved instruction by instruction
+// (one MFMA, then its share of expansion VALU work and LDS traffic), because a wave owns its
+// SIMD alone (512 registers) and nothing else would cover the matrix unit while the VALU expands.
 //
-// LDS tile layout of one operand and stage: [ks = 4][row block][half = 2][row = 32][16 bytes],
-// i.e. the 1 KB fragment of one MFMA (32 rows x 32 k) is contiguous and lane l reads bytes
+// LDS layout of one operand and stage: [ks = 4][row block][half = 2][row = 32][16 bytes], i.e. the
+// 1 KB fragment of one MFMA (32 rows x one k step) is contiguous and lane l reads bytes
 // 16*l .. 16*l+15: conflict free for ds_read_b128 and for the ds_write_b128 of the expansion.
-// The k order inside a fragment is (half, byte) = the order the expansion produces; both
-// operands use the same order, which is all the contraction needs.
+// The k order inside a fragment is whatever the expansion produces; both operands use the same
+// order, which is all the contraction needs.
 #pragma once
 #include <type_traits>
 #include <utility>
@@ -42,10 +50,12 @@ namespace apmm {
 namespace mfma {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
-constexpr int kStageK = 128;  // k elements per LDS stage (= one packed k block)
+constexpr int kStageSteps = 4;  // MFMA k steps per pipeline stage
 
 // Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), always flattened,
 // so that every index below is a constant (shift amounts, register numbers, LDS offsets).
@@ -60,79 +70,147 @@ __device__ __forceinline__ void static_for(F &&f)
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-// Dword t (elements 4t .. 4t+3) of the int8 expansion of one 32-element group given its planes
-// w[0..NB-1]: byte = code u.  Plane i is stored rotated left by i, so its bits for these four
-// elements are at in-byte position (t + i) % 8, and one rotate right by t brings every plane to
-// its own bit i (apmm_layout.h).
-template <int NB>
+// Output dword t of the expansion of one 32-element group given its planes w[0..NB-1].
+// Plane i is stored rotated left by i (apmm_layout.h).
+//   INT8: dword t of 8 holds 4 codes as bytes; their plane-i bits are at in-byte position (t+i) % 8.
+//   FP4 : dword t of 4 holds 8 codes as nibbles; their plane-i bits are at in-nibble position (t+i) % 4.
+// One rotate right by t brings every plane to its own bit i of the byte / nibble.
+template <int NB, bool FP4>
 __device__ __forceinline__ uint32_t expand_dword(const uint32_t (&w)[NB], int t)
 {
+    constexpr uint32_t ones = FP4 ? 0x11111111u : 0x01010101u;
+    constexpr int period = FP4 ? 4 : 8;
     uint32_t y = 0;
 #pragma unroll
-    for (int i = 0; i < NB; ++i) y |= w[i] & (0x01010101u << ((t + i) % 8));
+    for (int i = 0; i < NB; ++i) y |= w[i] & (ones << ((t + i) % period));
     return t ? __builtin_rotateright32(y, t) : y;
 }
 
-// Per-thread share of one operand's workgroup tile: WX units, one unit = (row, 32-k word group).
-template <int NB, int WX>
+// Per-thread share of one operand's workgroup tile and stage: UNITS units, one unit = (row, 32-k word
+// group).  A stage spans SB packed k blocks (1 for INT8, 2 for FP4), i.e. 4*SB word groups per row.
+template <int NB, int WX, bool FP4>
 struct Loader {
-    static constexpr int BX = 64 * WX;  // rows of the workgroup tile
-    uint32_t regs[WX][NB];
-    const uint32_t *src[WX];  // word address of (row, plane 0, word gq) in k block 0
-    int lds_off[WX];          // byte offset of the unit's first 16-byte chunk inside the operand stage
+    static constexpr int BX = 64 * WX;              // rows of the workgroup tile
+    static constexpr int SB = FP4 ? 2 : 1;          // packed k blocks per stage
+    static constexpr int UNITS = WX * SB;           // units per thread and stage
+    static constexpr int TPU = FP4 ? 4 : 8;         // output dwords (tasks) per unit
+    static constexpr int TASKS = UNITS * TPU;       // = 8 * WX in both formats
+    static constexpr int R = kThreads / BX;         // word-group stride between a thread's units
+    static_assert(R == 1 || R == 2 || R == 4, "workgroup tile rows must be 64, 128 or 256");
+    uint32_t regs[UNITS][NB];
+    uint32_t keep[SB];           // all ones, or zero for a k block past the end of K (FP4 stages only)
+    const uint32_t *src0;        // word address of (row, plane 0, word gq0) in k block 0, gq0 = tid / BX
+    int lds_off[UNITS];          // byte offset of the unit's first 16-byte chunk inside the operand's stage
 
+    // Unit s of a thread is word group gq0 + R*s of the stage: k block (R*s)/4 of the stage, word
+    // gq0 + (R*s)%4 of that block (gq0 < R, so the sum stays inside the block).
     __device__ __forceinline__ void init(const uint32_t *packed, int64_t row0, int64_t rows_p, int64_t nkb,
                                          int tid)
     {
+        const int row = tid % BX, gq0 = tid / BX;
+        int64_t grow = row0 + row;
+        if (grow >= rows_p) grow = rows_p - 1;  // rows past the operand: read a valid row, never stored
+        src0 = packed + tile_row_word(grow, 0, nkb, NB, 0) + gq0;
 #pragma unroll
-        for (int s = 0; s < WX; ++s) {
-            const int u = tid + kThreads * s;
-            const int row = u % BX, gq = u / BX;
-            int64_t grow = row0 + row;
-            if (grow >= rows_p) grow = rows_p - 1;  // rows past the operand: read a valid row, never stored
-            src[s] = packed + tile_row_word(grow, 0, nkb, NB, 0) + gq;
-            lds_off[s] = ((gq * (BX / 32) + row / 32) * 2) * 512 + (row % 32) * 16;
+        for (int s = 0; s < UNITS; ++s) {
+            const int gqs = gq0 + R * s;
+            // INT8: k step = word group, two 16-byte chunks (halves) per unit.
+            // FP4 : k step = pair of word groups, the unit is one half.
+            const int ks = FP4 ? gqs / 2 : gqs, half = FP4 ? gqs % 2 : 0;
+            lds_off[s] = ((ks * (BX / 32) + row / 32) * 2 + half) * 512 + (row % 32) * 16;
         }
+#pragma unroll
+        for (int b = 0; b < SB; ++b) keep[b] = 0xffffffffu;
     }
-    __device__ __forceinline__ void fetch(int64_t kb)
+    // Stage st covers k blocks st*SB .. st*SB+SB-1.  A block past the end is read from the last
+    // block and flagged; mask() later turns it into all-zero planes (code 0 in both operands adds
+    // nothing to S, PA or PW).  The flag is applied a stage later so that the loads stay in flight.
+    __device__ __forceinline__ void fetch(int64_t st, int64_t nkb)
     {
 #pragma unroll
-        for (int s = 0; s < WX; ++s)
+        for (int b = 0; b < SB; ++b) {
+            int64_t kb = st * SB + b;
+            keep[b] = 0xffffffffu;
+            if (SB > 1 && kb >= nkb) {
+                kb = nkb - 1;
+                keep[b] = 0u;
+            }
+            const uint32_t *blk = src0 + kb * (kRowBlock * kWordsPerRow * NB);
 #pragma unroll
-            for (int i = 0; i < NB; ++i)
-                regs[s][i] = src[s][kb * (kRowBlock * kWordsPerRow * NB) + i * kWordsPerRow];
+            for (int s = 0; s < UNITS; ++s) {
+                if ((R * s) / kWordsPerRow != b) continue;
+#pragma unroll
+                for (int i = 0; i < NB; ++i) regs[s][i] = blk[i * kWordsPerRow + (R * s) % kWordsPerRow];
+            }
+        }
+    }
+    __device__ __forceinline__ void mask()
+    {
+        if (SB == 1) return;
+#pragma unroll
+        for (int s = 0; s < UNITS; ++s)
+#pragma unroll
+            for (int i = 0; i < NB; ++i) regs[s][i] &= keep[(R * s) / kWordsPerRow];
     }
     // whole share at once (prologue)
     __device__ __forceinline__ void expand_to_lds(uint8_t *stage, uint32_t (&counts)[NB]) const
     {
         uint32_t o[4];
 #pragma unroll
-        for (int task = 0; task < 8 * WX; ++task) expand_task(stage, task, o, counts);
+        for (int task = 0; task < TASKS; ++task) expand_task(stage, task, o, counts);
     }
-    // one dword of the share: task = 8 * unit + t; every fourth task stores 16 bytes to LDS, and the
-    // first task of a unit adds the unit's plane popcounts to `counts`
+    // one output dword of the share: task = TPU * unit + t; every fourth task stores 16 bytes to LDS,
+    // and the first task of a unit adds the unit's plane popcounts to `counts`
     __device__ __forceinline__ void expand_task(uint8_t *stage, int task, uint32_t (&o)[4],
                                                 uint32_t (&counts)[NB]) const
     {
-        const int s = task / 8, t = task % 8;
+        const int s = task / TPU, t = task % TPU;
         if (t == 0) {
 #pragma unroll
             for (int i = 0; i < NB; ++i) counts[i] += __popc(regs[s][i]);
         }
-        o[t % 4] = expand_dword<NB>(regs[s], t);
+        o[t % 4] = expand_dword<NB, FP4>(regs[s], t);
         if (t % 4 == 3)
             *reinterpret_cast<uint4 *>(stage + lds_off[s] + (t / 4) * 512) = make_uint4(o[0], o[1], o[2], o[3]);
     }
 };
 
-template <int P, int Q, int WM, int WN>
+template <bool FP4>
+struct Acc;
+template <>
+struct Acc<false> {
+    typedef v16i type;
+    static __device__ __forceinline__ type mma(v4i a, v4i b, type c)
+    {
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+    }
+    // 4 S as a wrapping 32-bit integer
+    static __device__ __forceinline__ uint32_t four_s(int v) { return (uint32_t)v << 2; }
+};
+template <>
+struct Acc<true> {
+    typedef v16f type;
+    static __device__ __forceinline__ type mma(v4i a, v4i b, type c)
+    {
+        const v8i a8 = {a[0], a[1], a[2], a[3], 0, 0, 0, 0}, b8 = {b[0], b[1], b[2], b[3], 0, 0, 0, 0};
+        // formats 4 / 4 = E2M1 for both operands; scale exponent 127 = 2^0
+        return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 127, 0, 127);
+    }
+    // acc = S / 4 exactly, so 4 S = 16 acc
+    static __device__ __forceinline__ uint32_t four_s(float v) { return (uint32_t)(int32_t)(v * 16.0f); }
+};
+
+template <int P, int Q, int WM, int WN, bool FP4>
 __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int tiles_n, int tiles_total)
 {
+    static_assert(!FP4 || (P <= 2 && Q <= 2), "E2M1 patterns are linear in the code only up to 3");
     constexpr int BM = 64 * WM, BN = 64 * WN;
-    constexpr int A_STAGE = BM * kStageK, B_STAGE = BN * kStageK;  // bytes of int8
+    constexpr int KS = kStageSteps;
+    constexpr int A_STAGE = BM * 32 * KS, B_STAGE = BN * 32 * KS;  // bytes: 1 KB per 32 rows and k step
     constexpr int STAGE = A_STAGE + B_STAGE;
-    constexpr int KS = kStageK / 32;  // MFMA k steps per stage
+    constexpr int SB = FP4 ? 2 : 1;
     extern __shared__ __align__(16) uint8_t lds[];
+    typedef typename Acc<FP4>::type acc_t;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -146,12 +224,12 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int til
     const int tm = lid / tiles_n, tn = lid % tiles_n;
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
-    Loader<P, WM> la;
-    Loader<Q, WN> lb;
+    Loader<P, WM, FP4> la;
+    Loader<Q, WN, FP4> lb;
     la.init(g.a, m0, round_up(g.M, kRowBlock), g.nkb, tid);
     lb.init(g.w, n0, round_up(g.N, kRowBlock), g.nkb, tid);
 
-    v16i acc[WM][WN];
+    acc_t acc[WM][WN];
 #pragma unroll
     for (int bi = 0; bi < WM; ++bi)
 #pragma unroll
@@ -159,41 +237,45 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int til
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[bi][bj][v] = 0;
 
-    const int64_t last = g.nkb - 1;
-    la.fetch(0);
-    lb.fetch(0);
+    const int64_t nst = (g.nkb + SB - 1) / SB;  // pipeline stages
+    const int64_t last = nst - 1;
+    la.fetch(0, g.nkb);
+    lb.fetch(0, g.nkb);
     // per plane: set bits of this thread's units so far (all units of a thread lie in one row)
     uint32_t pop_a[P], pop_b[Q];
 #pragma unroll
     for (int i = 0; i < P; ++i) pop_a[i] = 0;
 #pragma unroll
     for (int i = 0; i < Q; ++i) pop_b[i] = 0;
+    la.mask();
+    lb.mask();
     la.expand_to_lds(lds, pop_a);
     lb.expand_to_lds(lds + A_STAGE, pop_b);
-    la.fetch(last < 1 ? last : 1);
-    lb.fetch(last < 1 ? last : 1);
+    la.fetch(last < 1 ? last : 1, g.nkb);
+    lb.fetch(last < 1 ? last : 1, g.nkb);
     __syncthreads();
 
     const int frag_a = (wave_m * WM) * 1024 + lane * 16;
     const int frag_b = A_STAGE + (wave_n * WN) * 1024 + lane * 16;
 
-    constexpr int MFMAS = WM * WN * KS;             // MFMAs per stage and wave
-    constexpr int PER_KS = WM * WN;                 // MFMAs per 32-k step
-    constexpr int READS = WM + WN;                  // fragment reads per 32-k step
+    constexpr int MFMAS = WM * WN * KS;              // MFMAs per stage and wave
+    constexpr int PER_KS = WM * WN;                  // MFMAs per k step
+    constexpr int READS = WM + WN;                   // fragment reads per k step
     constexpr int TASKS_A = 8 * WM, TASKS = 8 * (WM + WN);  // expansion dwords per thread and stage
-    static_assert(TASKS % MFMAS == 0 || MFMAS % TASKS == 0, "expansion tasks must spread evenly over the MFMAs");
 
-    for (int64_t kb = 0; kb < g.nkb; ++kb) {
-        const uint8_t *cur = lds + (kb & 1) * STAGE;
-        uint8_t *nxt = lds + ((kb + 1) & 1) * STAGE;
+    for (int64_t st = 0; st < nst; ++st) {
+        const uint8_t *cur = lds + (st & 1) * STAGE;
+        uint8_t *nxt = lds + ((st + 1) & 1) * STAGE;
 
-        // raw planes of k block kb+1 are in registers; start the loads of kb+2 right away
-        Loader<P, WM> ea = la;
-        Loader<Q, WN> eb = lb;
-        const int64_t kf = (kb + 2 <= last) ? kb + 2 : last;  // clamped: the surplus fetches are discarded
-        la.fetch(kf);
-        lb.fetch(kf);
-        // the last iteration re-expands the final k block: its popcounts must not be counted twice
+        // raw planes of stage st+1 are in registers; start the loads of st+2 right away
+        Loader<P, WM, FP4> ea = la;
+        Loader<Q, WN, FP4> eb = lb;
+        ea.mask();
+        eb.mask();
+        const int64_t sf = (st + 2 <= last) ? st + 2 : last;  // clamped: the surplus fetches are discarded
+        la.fetch(sf, g.nkb);
+        lb.fetch(sf, g.nkb);
+        // the last iteration re-expands the final stage: its popcounts must not be counted twice
         uint32_t cnt_a[P], cnt_b[Q];
 #pragma unroll
         for (int i = 0; i < P; ++i) cnt_a[i] = 0;
@@ -201,7 +283,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int til
         for (int i = 0; i < Q; ++i) cnt_b[i] = 0;
 
         v4i af[2][WM], bf[2][WN];
-        // fragment r of 32-k step ks: r = 0 -> A block 0, r = 1..WN -> B blocks, then the other A blocks
+        // fragment r of k step ks: r = 0 -> A block 0, r = 1..WN -> B blocks, then the other A blocks
         auto read_frag = [&](auto ks_c, auto r_c) __attribute__((always_inline)) {
             constexpr int ks = decltype(ks_c)::value, r = decltype(r_c)::value;
             if constexpr (r == 0)
@@ -220,16 +302,16 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int til
         static_for<MFMAS>([&](auto i_c) __attribute__((always_inline)) {
             constexpr int i = decltype(i_c)::value;
             constexpr int ks = i / PER_KS, j = i % PER_KS, bi = j / WN, bj = j % WN;
-            // prefetch the fragments of the next 32-k step, spread over this step's MFMAs
+            // prefetch the fragments of the next k step, spread over this step's MFMAs
             if constexpr (ks + 1 < KS) {
                 static_for<READS>([&](auto r_c) __attribute__((always_inline)) {
                     if constexpr (decltype(r_c)::value * PER_KS / READS == j)
                         read_frag(std::integral_constant<int, ks + 1>{}, r_c);
                 });
             }
-            acc[bi][bj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[ks & 1][bi], bf[ks & 1][bj], acc[bi][bj], 0, 0, 0);
-            // this MFMA's share of the expansion of k block kb+1 into the idle buffer (in the last
-            // iteration it rewrites the block already there: harmless, and keeps the body branch free)
+            acc[bi][bj] = Acc<FP4>::mma(af[ks & 1][bi], bf[ks & 1][bj], acc[bi][bj]);
+            // this MFMA's share of the expansion of stage st+1 into the idle buffer (in the last
+            // iteration it rewrites the stage already there: harmless, and keeps the body branch free)
             static_for<TASKS>([&](auto t_c) __attribute__((always_inline)) {
                 constexpr int task = decltype(t_c)::value;
                 if constexpr (task * MFMAS / TASKS == i) {
@@ -241,7 +323,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int til
             });
             __builtin_amdgcn_sched_barrier(0);
         });
-        const uint32_t keep = (kb < last) ? 0xffffffffu : 0u;
+        const uint32_t keep = (st < last) ? 0xffffffffu : 0u;
 #pragma unroll
         for (int i = 0; i < P; ++i) pop_a[i] += cnt_a[i] & keep;
 #pragma unroll
@@ -316,7 +398,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int til
 #pragma unroll
                     for (int bj = 0; bj < WN; ++bj) {
                         if (GUARD && n_lane + bj * 32 >= g.N) continue;
-                        const uint32_t c = ((uint32_t)acc[bi][bj][4 * v4 + r] << 2) + row_term[r] + col_term[bj];
+                        const uint32_t c = Acc<FP4>::four_s(acc[bi][bj][4 * v4 + r]) + row_term[r] + col_term[bj];
                         if constexpr (I32) ci[row * g.N + bj * 32] = (int32_t)c;
                         if constexpr (F16) ch[row * g.N + bj * 32] = float_to_half_bits((float)(int32_t)c * sa * sw[bj]);
                     }
@@ -339,15 +421,15 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int til
     }
 }
 
-template <int P, int Q, int WM, int WN>
+template <int P, int Q, int WM, int WN, bool FP4>
 hipError_t launch_variant(const GemmArgs &g, hipStream_t stream)
 {
     constexpr int BM = 64 * WM, BN = 64 * WN;
-    constexpr size_t lds_bytes = 2 * (size_t)(BM + BN) * kStageK;
+    constexpr size_t lds_bytes = 2 * (size_t)(BM + BN) * 32 * kStageSteps;
     const int64_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int64_t tiles = tiles_m * tiles_n;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-    auto kernel = gemm_mfma_kernel<P, Q, WM, WN>;
+    auto kernel = gemm_mfma_kernel<P, Q, WM, WN, FP4>;
     static bool attr_set = false;  // raising the dynamic LDS limit is idempotent; a race here is harmless
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -362,24 +444,34 @@ hipError_t launch_variant(const GemmArgs &g, hipStream_t stream)
 
 // Tile choice: the 256 x 256 tile has the lowest expansion and LDS cost per MFMA but needs
 // enough tiles to occupy the 256 CUs; otherwise 128 x 128.
-template <int P, int Q>
-hipError_t launch_pq(const GemmArgs &g, hipStream_t stream)
+template <int P, int Q, bool FP4>
+hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream)
 {
     const int64_t big = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-    if (big >= 192) return launch_variant<P, Q, 4, 4>(g, stream);
-    return launch_variant<P, Q, 2, 2>(g, stream);
+    if (big >= 192) return launch_variant<P, Q, 4, 4, FP4>(g, stream);
+    return launch_variant<P, Q, 2, 2, FP4>(g, stream);
 }
 
-// One translation unit per activation width instantiates launch_p<P>.
+// INT8 operands, one translation unit per activation width.
 template <int P>
-hipError_t launch_p(const GemmArgs &g, hipStream_t stream)
+hipError_t launch_int8_p(const GemmArgs &g, hipStream_t stream)
 {
     switch (g.q) {
-    case 1: return launch_pq<P, 1>(g, stream);
-    case 2: return launch_pq<P, 2>(g, stream);
-    case 3: return launch_pq<P, 3>(g, stream);
-    case 4: return launch_pq<P, 4>(g, stream);
+    case 1: return launch_tiles<P, 1, false>(g, stream);
+    case 2: return launch_tiles<P, 2, false>(g, stream);
+    case 3: return launch_tiles<P, 3, false>(g, stream);
+    case 4: return launch_tiles<P, 4, false>(g, stream);
     }
+    return hipErrorInvalidValue;
+}
+
+// FP4 operands: p, q in {1, 2}.
+inline hipError_t launch_fp4(const GemmArgs &g, hipStream_t stream)
+{
+    if (g.p == 1 && g.q == 1) return launch_tiles<1, 1, true>(g, stream);
+    if (g.p == 1 && g.q == 2) return launch_tiles<1, 2, true>(g, stream);
+    if (g.p == 2 && g.q == 1) return launch_tiles<2, 1, true>(g, stream);
+    if (g.p == 2 && g.q == 2) return launch_tiles<2, 2, true>(g, stream);
     return hipErrorInvalidValue;
 }
 

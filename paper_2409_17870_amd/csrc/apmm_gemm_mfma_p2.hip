@@ -2,5 +2,5 @@
 #include "apmm_gemm_mfma_impl.h"
 
 namespace apmm {
-hipError_t launch_gemm_mfma_p2(const GemmArgs &g, hipStream_t stream) { return mfma::launch_p<2>(g, stream); }
+hipError_t launch_gemm_mfma_p2(const GemmArgs &g, hipStream_t stream) { return mfma::launch_int8_p<2>(g, stream); }
 }  // namespace apmm

@@ -14,9 +14,13 @@ hipError_t launch_unpack(const uint32_t *packed, int64_t rows, int64_t K, int bi
 // Design B: plane pairs by XOR + popcount on the vector ALU (any p, q in 1..8).
 hipError_t launch_gemm_valu(const GemmArgs &args, hipStream_t stream);
 
-// Design A: planes recombined into int8, int8 MFMA (p, q in 1..7 as far as instantiated).
+// Design A: planes recombined into int8 codes, int8 MFMA (p, q in 1..4).
 bool gemm_mfma_supported(const GemmArgs &args);
 hipError_t launch_gemm_mfma(const GemmArgs &args, hipStream_t stream);
+
+// Design A with E2M1 operands on the f8f6f4 MFMA (p, q in 1..2), twice the int8 rate.
+bool gemm_mfma_fp4_supported(const GemmArgs &args);
+hipError_t launch_gemm_mfma_fp4(const GemmArgs &args, hipStream_t stream);
 
 // Small-M weight-streaming kernel (M <= 16).
 bool gemm_decode_supported(const GemmArgs &args);

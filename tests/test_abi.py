@@ -68,6 +68,7 @@ def test_argument_errors_come_before_any_launch(lib):
     assert _gemm(lib, 4, 4, 128, 1, 1, c=None) == INVALID          # no output requested
     assert _gemm(lib, 4, 4, 128, 1, 1, a=0x1004) == INVALID         # misaligned packed operand
     assert _gemm(lib, 4, 4, 128, 1, 1, algo=7) == INVALID
+    assert _gemm(lib, 64, 64, 128, 3, 1, algo=4) == UNSUPPORTED     # E2M1 holds 2-bit codes only
     assert b"" != lib.apmm_last_error()
     # 2^31 / (255 * 255) = 33025.5: K = 33024 fits, the next k block does not
     assert _gemm(lib, 0, 4, 33024, 8, 8) == 0                       # M == 0: ok, nothing launched

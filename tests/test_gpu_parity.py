@@ -12,7 +12,7 @@ from paper_2409_17870_amd import inputs
 
 pytestmark = pytest.mark.gpu
 
-VALU, MFMA, DECODE = 1, 2, 3
+VALU, MFMA, DECODE, FP4 = 1, 2, 3, 4
 
 
 @pytest.fixture(scope="module")
@@ -55,6 +55,8 @@ def algos_for(case):
     algos = [VALU]
     if case["p"] <= 4 and case["q"] <= 4:
         algos.append(MFMA)
+    if case["p"] <= 2 and case["q"] <= 2:
+        algos.append(FP4)
     return algos + [0]
 
 
