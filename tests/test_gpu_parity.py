@@ -57,6 +57,8 @@ def algos_for(case):
         algos.append(MFMA)
     if case["p"] <= 2 and case["q"] <= 2:
         algos.append(FP4)
+    if case["M"] <= 16 and case["q"] <= 4:
+        algos.append(DECODE)
     return algos + [0]
 
 
@@ -120,6 +122,18 @@ def test_wide_codes(gpu, oracle, p, q):
     want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
     c32, _ = run_case(gpu, data, case)
     assert np.array_equal(c32.astype(np.int64), want)
+
+
+@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (3, 3), (4, 4), (8, 2), (1, 4)])
+@pytest.mark.parametrize("M", [1, 2, 3, 5, 8, 13, 16])
+def test_decode_kernel_all_token_counts(gpu, oracle, M, p, q):
+    """Small-M kernel: every token-count bucket, ragged N and K, odd plane counts."""
+    case = dict(M=M, N=203, K=1100, p=p, q=q, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 5000 + 100 * M + 10 * p + q)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+    c32, c16 = run_case(gpu, data, case, algo=DECODE)
+    assert np.array_equal(c32.astype(np.int64), want)
+    check_f16(c16, want, data, oracle)
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (1, 257, 128), (16, 1, 4096), (3, 7, 127), (17, 33, 129)])
