@@ -23,13 +23,16 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense int8, published
-HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+# MI355X published dense matrix peaks (TFLOP/s or TOP/s) and HBM bandwidth
+PEAK = {"fp4": 10100.0, "int8": 5000.0}
+HBM_PEAK_GBS = 8000.0
 PAPER_W1A2_4096_TOPS = 2 * 4096 ** 3 / 160e-6 / 1e12   # paper Table 1: 160 us on an RTX 3090
 
-# HBM bytes per GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/);
-# None until such a run has been recorded for the kernel that is timed here.
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command,
+# each scaled by what the same counter reads for a plain 64 MiB copy (profiles/ holds the runs).
+MEASURED_TRAFFIC_BYTES = {"auto": None, "int8": None}
+
+ALGOS = {"auto": 0, "valu": 1, "int8": 2, "decode": 3, "fp4": 4}
 
 
 def parse_args():
@@ -38,14 +41,19 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
-    ap.add_argument("--algo", type=int, default=0, help="kernel choice for apmm_gemm_ex (0 = auto)")
+    ap.add_argument("--algo", choices=sorted(ALGOS), default="auto",
+                    help="GEMM kernel: auto picks the E2M1 (fp4) MFMA kernel for this workload")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 64 MiB device copy (reference for HBM byte counters)")
     return ap.parse_args()
 
 
-def cpu_baseline(case, seed, sample_rows):
-    """Time the oracle (as it stands) on the first `sample_rows` activation rows of the workload."""
+def cpu_baseline(case, seed):
+    """Time the oracle (as it stands) on a bounded sample of the workload."""
     import oracle
     from paper_2409_17870_amd import inputs
+    cores = oracle.num_threads()
+    sample_rows = case["M"] if cores >= 16 else case["M"] // 2
     data = inputs.make_case(case, seed)
     a = data["a_codes"][:sample_rows]
     t0 = time.perf_counter()
@@ -53,7 +61,7 @@ def cpu_baseline(case, seed, sample_rows):
     dt = time.perf_counter() - t0
     ops = 2.0 * sample_rows * case["N"] * case["K"]
     return {
-        "value": ops / dt / 1e12, "unit": "TOPS", "cores": oracle.num_threads(), "kind": "oracle",
+        "value": ops / dt / 1e12, "unit": "TOPS", "cores": cores, "kind": "oracle",
         "seconds": dt,
         "sample": "first %d of %d activation rows, all %d output channels, full K=%d" %
                   (sample_rows, case["M"], case["N"], case["K"]),
@@ -85,18 +93,25 @@ def main():
     w_packed = binding.apmm_pack_weights(w_codes, q)            # offline
     a_packed = torch.empty(binding.apmm_packed_bytes(M, K, p), dtype=torch.uint8, device=dev)
     c = torch.empty((M, N), dtype=torch.int32, device=dev)
+    algo = ALGOS[args.algo]
+    operand = "int8" if args.algo == "int8" else "fp4"
 
     def step(events=None):
         binding.apmm_pack_activations(a_codes, p, out=a_packed)
         if events is not None:
             events[0].record()
-        binding.apmm_gemm(M, N, K, p, q, a_packed, w_packed, c_i32=c, algo=args.algo)
+        binding.apmm_gemm(M, N, K, p, q, a_packed, w_packed, c_i32=c, algo=algo)
         if events is not None:
             events[1].record()
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
 
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
            for _ in range(args.steps)]
@@ -113,6 +128,8 @@ def main():
     value = ops / (ms_per_step * 1e-3) / 1e12
     achieved = ops / (gemm_ms * 1e-3) / 1e12
 
+    dtype = ("fp4 (E2M1) MFMA operands recombined from 1-bit planes, exact fp32 accumulate" if operand == "fp4"
+             else "int8 MFMA operands recombined from 1-bit planes, int32 accumulate")
     out = {
         "metric": "effective TOPS (2*M*N*K/s), W1A2 bipolar-INT GEMM 4096^3 (activation pack + GEMM)",
         "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -120,18 +137,20 @@ def main():
         "vs_baseline": value / PAPER_W1A2_4096_TOPS,
         "baseline_note": "paper Table 1: 160 us = %.0f effective TOPS on an NVIDIA RTX 3090 (GEMM only)"
                          % PAPER_W1A2_4096_TOPS,
-        "dtype": "int8 MFMA operands recombined from 1-bit planes, int32 accumulate",
+        "dtype": dtype,
         "data": "synthetic",
         "config": {"workload": "square W1A2 GEMM M=N=K=4096, Bernoulli(1/2) bits, int32 output",
                    "M": M, "N": N, "K": K, "weight_bits": q, "activation_bits": p,
-                   "step": "apmm_pack_activations + apmm_gemm, weights pre-packed"},
+                   "step": "apmm_pack_activations + apmm_gemm, weights pre-packed", "algo": args.algo},
         "gemm_ms": gemm_ms, "pack_ms": ms_per_step - gemm_ms,
-        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel", "achieved": achieved,
-                     "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / INT8_MFMA_PEAK_TOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES},
+        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel (%s operands, 256x256 tile)" % operand,
+                     "achieved": achieved, "peak": PEAK[operand], "unit": "TOP/s",
+                     "frac": achieved / PEAK[operand],
+                     "frac_of_int8_peak": achieved / PEAK["int8"],
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.algo)},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(case, seed, sample_rows=2048)
+        out["cpu_baseline"] = cpu_baseline(case, seed)
     print(json.dumps(out))
 
 

@@ -13,7 +13,7 @@
 //   workgroup : 16 output channels (half a packed row block), 8 waves
 //   wave      : k blocks 4*(w + 8*t) .. +3, t = 0, 1, ...
 //   lane l    : weight row l % 16, k block l / 16 of the wave's four; it loads the row's q planes
-//               of that block (q x 16 contiguous bytes) straight into registers
+//               of that block (q x 16 bytes, 256 contiguous bytes per 16 lanes) straight into registers
 // The activations (M rows, all K) are copied once per workgroup from their packed tiles into LDS
 // with every plane rotated back to the natural bit order; a weight plane is rotated back the same
 // way after loading, so that any activation plane can be XOR-ed with any weight plane.
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GemmArgs g)
         uint4 w[Q];
         const uint4 *wsrc = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld, kb, g.nkb, Q, 0));
 #pragma unroll
-        for (int i = 0; i < Q; ++i) w[i] = wsrc[i];
+        for (int i = 0; i < Q; ++i) w[i] = wsrc[i * (kPlaneWords / 4)];
 #pragma unroll
         for (int i = 0; i < Q; ++i) {
             w[i].x = __builtin_rotateright32(w[i].x, plane_rotation(i));

@@ -95,25 +95,26 @@ struct Loader {
     static constexpr int UNITS = WX * SB;           // units per thread and stage
     static constexpr int TPU = FP4 ? 4 : 8;         // output dwords (tasks) per unit
     static constexpr int TASKS = UNITS * TPU;       // = 8 * WX in both formats
-    static constexpr int R = kThreads / BX;         // word-group stride between a thread's units
+    static constexpr int R = kThreads / BX;         // threads sharing a row
     static_assert(R == 1 || R == 2 || R == 4, "workgroup tile rows must be 64, 128 or 256");
+    static constexpr int UPB = kWordsPerRow / R;    // consecutive word groups a thread owns per k block
     uint32_t regs[UNITS][NB];
     uint32_t keep[SB];           // all ones, or zero for a k block past the end of K (FP4 stages only)
-    const uint32_t *src0;        // word address of (row, plane 0, word gq0) in k block 0, gq0 = tid / BX
+    const uint32_t *src0;        // word address of (row, plane 0, word gq0 * UPB) in k block 0, gq0 = tid / BX
     int lds_off[UNITS];          // byte offset of the unit's first 16-byte chunk inside the operand's stage
 
-    // Unit s of a thread is word group gq0 + R*s of the stage: k block (R*s)/4 of the stage, word
-    // gq0 + (R*s)%4 of that block (gq0 < R, so the sum stays inside the block).
+    // Unit s of a thread: k block s / UPB of the stage, word group gq0 * UPB + s % UPB of that block,
+    // so that a thread's words of one plane and k block are consecutive (one 4-, 8- or 16-byte load).
     __device__ __forceinline__ void init(const uint32_t *packed, int64_t row0, int64_t rows_p, int64_t nkb,
                                          int tid)
     {
         const int row = tid % BX, gq0 = tid / BX;
         int64_t grow = row0 + row;
         if (grow >= rows_p) grow = rows_p - 1;  // rows past the operand: read a valid row, never stored
-        src0 = packed + tile_row_word(grow, 0, nkb, NB, 0) + gq0;
+        src0 = packed + tile_row_word(grow, 0, nkb, NB, 0) + gq0 * UPB;
 #pragma unroll
         for (int s = 0; s < UNITS; ++s) {
-            const int gqs = gq0 + R * s;
+            const int gqs = (s / UPB) * kWordsPerRow + gq0 * UPB + s % UPB;  // word group inside the stage
             // INT8: k step = word group, two 16-byte chunks (halves) per unit.
             // FP4 : k step = pair of word groups, the unit is one half.
             const int ks = FP4 ? gqs / 2 : gqs, half = FP4 ? gqs % 2 : 0;
@@ -135,13 +136,11 @@ struct Loader {
                 kb = nkb - 1;
                 keep[b] = 0u;
             }
-            const uint32_t *blk = src0 + kb * (kRowBlock * kWordsPerRow * NB);
+            const uint32_t *blk = src0 + kb * (kPlaneWords * NB);
 #pragma unroll
-            for (int s = 0; s < UNITS; ++s) {
-                if ((R * s) / kWordsPerRow != b) continue;
+            for (int i = 0; i < NB; ++i)
 #pragma unroll
-                for (int i = 0; i < NB; ++i) regs[s][i] = blk[i * kWordsPerRow + (R * s) % kWordsPerRow];
-            }
+                for (int u = 0; u < UPB; ++u) regs[b * UPB + u][i] = blk[i * kPlaneWords + u];
         }
     }
     __device__ __forceinline__ void mask()
@@ -150,7 +149,7 @@ struct Loader {
 #pragma unroll
         for (int s = 0; s < UNITS; ++s)
 #pragma unroll
-            for (int i = 0; i < NB; ++i) regs[s][i] &= keep[(R * s) / kWordsPerRow];
+            for (int i = 0; i < NB; ++i) regs[s][i] &= keep[s / UPB];
     }
     // whole share at once (prologue)
     __device__ __forceinline__ void expand_to_lds(uint8_t *stage, uint32_t (&counts)[NB]) const
@@ -442,14 +441,30 @@ hipError_t launch_variant(const GemmArgs &g, hipStream_t stream)
     return hipGetLastError();
 }
 
-// Tile choice: the 256 x 256 tile has the lowest expansion and LDS cost per MFMA but needs
-// enough tiles to occupy the 256 CUs; otherwise 128 x 128.
+// Tile choice.  The 256 x 256 tile has the lowest expansion and LDS cost per MFMA but the grid must
+// also fill the 256 CUs: estimate each candidate as (rounds of 256 tiles) x (tile area) x (relative
+// cost per MFMA of that tile shape, measured) and take the cheapest.
 template <int P, int Q, bool FP4>
 hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream)
 {
-    const int64_t big = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-    if (big >= 192) return launch_variant<P, Q, 4, 4, FP4>(g, stream);
-    return launch_variant<P, Q, 2, 2, FP4>(g, stream);
+    struct Cand { int bm, bn; double cost; };
+    const Cand cands[4] = {{256, 256, 1.0}, {256, 128, 1.2}, {128, 256, 1.2}, {128, 128, 1.5}};
+    int best = 0;
+    double best_t = 0;
+    for (int c = 0; c < 4; ++c) {
+        const int64_t tiles = ((g.M + cands[c].bm - 1) / cands[c].bm) * ((g.N + cands[c].bn - 1) / cands[c].bn);
+        const double t = (double)((tiles + 255) / 256) * cands[c].bm * cands[c].bn * cands[c].cost;
+        if (c == 0 || t < best_t) {
+            best = c;
+            best_t = t;
+        }
+    }
+    switch (best) {
+    case 0: return launch_variant<P, Q, 4, 4, FP4>(g, stream);
+    case 1: return launch_variant<P, Q, 4, 2, FP4>(g, stream);
+    case 2: return launch_variant<P, Q, 2, 4, FP4>(g, stream);
+    default: return launch_variant<P, Q, 2, 2, FP4>(g, stream);
+    }
 }
 
 // INT8 operands, one translation unit per activation width.

@@ -30,11 +30,11 @@ __global__ __launch_bounds__(kTile * kTile) void gemm_valu_kernel(GemmArgs g)
         const uint4 *arow = reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, kb, g.nkb, p, 0));
         const uint4 *wrow = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n, kb, g.nkb, q, 0));
         for (int i = 0; i < q; ++i) {
-            const uint4 wv = wrow[i];
+            const uint4 wv = wrow[i * (kPlaneWords / 4)];
             for (int j = 0; j < p; ++j) {
                 // plane words are stored rotated by their plane index: bring the activation plane
                 // to the weight plane's rotation before comparing
-                const uint4 av = arow[j];
+                const uint4 av = arow[j * (kPlaneWords / 4)];
                 const int r = (plane_rotation(j) - plane_rotation(i)) & 31;
                 const uint32_t pc = __popc(__builtin_rotateright32(av.x, r) ^ wv.x) +
                                     __popc(__builtin_rotateright32(av.y, r) ^ wv.y) +

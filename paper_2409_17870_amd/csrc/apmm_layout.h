@@ -3,15 +3,16 @@
 // A rows x K operand of n-bit codes is stored as n one-bit planes in 32-bit words,
 // concatenated tile by tile:
 //
-//   word(rb, kb, r, i, g)   rb = row / 32       row block (rows padded to a multiple of 32)
+//   word(rb, kb, i, r, g)   rb = row / 32       row block (rows padded to a multiple of 32)
 //                           kb = k / 128        k block   (K padded to a multiple of 128)
-//                           r  = row % 32
 //                           i  = plane (bit of the code), 0 .. n-1
+//                           r  = row % 32
 //                           g  = (k % 128) / 32 word inside the k block
-//   index = (((rb * nkb + kb) * 32 + r) * n + i) * 4 + g
+//   index = (((rb * nkb + kb) * n + i) * 32 + r) * 4 + g
 //
-// so one (rb, kb) tile is 512*n contiguous bytes and one row of a tile is n x 16 bytes:
-// a whole tile row, all planes, arrives with n 16-byte loads.
+// so one (rb, kb) tile is 512*n contiguous bytes, planes concatenated, and inside a plane the
+// 32 rows are 16 bytes each: when the lanes of a wave take one row each, every 16-byte load
+// instruction reads one contiguous 512-byte run per row block.
 //
 // Inside a word, element e = k % 32 of plane i sits at bit (8*(e % 4) + (e / 4) + i) mod 32:
 // the "natural" word, whose byte c holds elements c, c+4, c+8, ..., rotated left by i.
@@ -34,6 +35,7 @@ namespace apmm {
 constexpr int kRowBlock = 32;    // rows per packed tile
 constexpr int kKBlock = 128;     // k elements per packed tile
 constexpr int kWordsPerRow = 4;  // 32-bit words per (row, plane) inside a tile
+constexpr int kPlaneWords = kRowBlock * kWordsPerRow;  // words between consecutive planes of a tile
 
 // left rotation applied to the natural word of plane i
 inline __host__ __device__ int plane_rotation(int i) { return i; }
@@ -44,7 +46,7 @@ inline __host__ __device__ int64_t round_up(int64_t x, int64_t m) { return (x + 
 inline __host__ __device__ int64_t tile_row_word(int64_t row, int64_t kb, int64_t nkb, int n, int i)
 {
     int64_t rb = row / kRowBlock, r = row % kRowBlock;
-    return (((rb * nkb + kb) * kRowBlock + r) * n + i) * kWordsPerRow;
+    return (((rb * nkb + kb) * n + i) * kRowBlock + r) * kWordsPerRow;
 }
 
 struct GemmArgs {

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const uint8_t *__restric
         uint32_t word = 0;
 #pragma unroll
         for (int t4 = 0; t4 < 8; ++t4) word |= ((d[t4] >> i) & 0x01010101u) << t4;
-        dst[i * kWordsPerRow] = __builtin_rotateleft32(word, plane_rotation(i));
+        dst[i * kPlaneWords] = __builtin_rotateleft32(word, plane_rotation(i));
     }
 }
 
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(const uint32_t *__rest
 #pragma unroll
     for (int t4 = 0; t4 < 8; ++t4) d[t4] = 0u;
     for (int i = 0; i < bits; ++i) {
-        const uint32_t word = __builtin_rotateright32(src[i * kWordsPerRow], plane_rotation(i));
+        const uint32_t word = __builtin_rotateright32(src[i * kPlaneWords], plane_rotation(i));
 #pragma unroll
         for (int t4 = 0; t4 < 8; ++t4) d[t4] |= ((word >> t4) & 0x01010101u) << i;
     }

@@ -84,10 +84,10 @@ def test_pack_is_plane_decomposition(gpu):
     rng = np.random.default_rng(5)
     codes = rng.integers(0, 8, size=(rows, K), dtype=np.uint8)
     packed = binding.apmm_pack_weights(torch.from_numpy(codes).to("cuda:0"), bits).cpu().numpy()
-    words = packed.view(np.uint32).reshape(rows, bits, 4)            # one tile: [row][plane][word]
+    words = packed.view(np.uint32).reshape(bits, rows, 4)            # one tile: [plane][row][word]
     for i in range(bits):
         for r in range(rows):
-            ones = sum(bin(int(x)).count("1") for x in words[r, i])
+            ones = sum(bin(int(x)).count("1") for x in words[i, r])
             assert ones == int(((codes[r] >> i) & 1).sum())
 
 
