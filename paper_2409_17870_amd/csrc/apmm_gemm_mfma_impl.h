@@ -40,6 +40,7 @@
 // The k order inside a fragment is whatever the expansion produces; both operands use the same
 // order, which is all the contraction needs.
 #pragma once
+#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
@@ -448,9 +449,17 @@ template <int P, int Q, bool FP4>
 hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream)
 {
     struct Cand { int bm, bn; double cost; };
-    const Cand cands[4] = {{256, 256, 1.0}, {256, 128, 1.2}, {128, 256, 1.2}, {128, 128, 1.5}};
+    // measured on MI355X, per unit of tile area relative to 256 x 256: the smaller tiles expand more
+    // operand bytes per MFMA, which costs more where the VALU is the limit (int8 with 4-bit planes)
+    const Cand cands[4] = {{256, 256, 1.0}, {256, 128, FP4 ? 1.2 : 1.55}, {128, 256, FP4 ? 1.2 : 1.45},
+                           {128, 128, FP4 ? 1.2 : 1.55}};
     int best = 0;
     double best_t = 0;
+    // debugging aid: APMM_MFMA_TILE=0..3 forces a candidate
+    static const char *forced = std::getenv("APMM_MFMA_TILE");
+    if (forced && forced[0] >= '0' && forced[0] <= '3') {
+        best = forced[0] - '0';
+    } else
     for (int c = 0; c < 4; ++c) {
         const int64_t tiles = ((g.M + cands[c].bm - 1) / cands[c].bm) * ((g.N + cands[c].bn - 1) / cands[c].bn);
         const double t = (double)((tiles + 255) / 256) * cands[c].bm * cands[c].bn * cands[c].cost;
