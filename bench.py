@@ -30,7 +30,9 @@ PAPER_W1A2_4096_TOPS = 2 * 4096 ** 3 / 160e-6 / 1e12   # paper Table 1: 160 us o
 
 # HBM bytes per GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command,
 # each scaled by what the same counter reads for a plain 64 MiB copy (profiles/ holds the runs).
-MEASURED_TRAFFIC_BYTES = {"auto": None, "int8": None}
+# fp4 kernel: FETCH_SIZE 10435.2 KiB x 1.9989 (copy calibration) + WRITE_SIZE 65536 KiB x 1.0
+# int8 kernel: FETCH_SIZE 10398.2 KiB x 1.9989 + WRITE_SIZE 65536 KiB x 1.0
+MEASURED_TRAFFIC_BYTES = {"auto": 88468000, "fp4": 88468000, "int8": 88392000}
 
 ALGOS = {"auto": 0, "valu": 1, "int8": 2, "decode": 3, "fp4": 4}
 
