@@ -55,7 +55,7 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int kThreads = 256;
+constexpr int kMaxThreads = 512;
 constexpr int kStageSteps = 4;  // MFMA k steps per pipeline stage
 
 // Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), always flattened,
@@ -89,16 +89,15 @@ __device__ __forceinline__ uint32_t expand_dword(const uint32_t (&w)[NB], int t)
 
 // Per-thread share of one operand's workgroup tile and stage: UNITS units, one unit = (row, 32-k word
 // group).  A stage spans SB packed k blocks (1 for INT8, 2 for FP4), i.e. 4*SB word groups per row.
-template <int NB, int WX, bool FP4>
+template <int NB, int BX, int THREADS, bool FP4>
 struct Loader {
-    static constexpr int BX = 64 * WX;              // rows of the workgroup tile
     static constexpr int SB = FP4 ? 2 : 1;          // packed k blocks per stage
-    static constexpr int UNITS = WX * SB;           // units per thread and stage
-    static constexpr int TPU = FP4 ? 4 : 8;         // output dwords (tasks) per unit
-    static constexpr int TASKS = UNITS * TPU;       // = 8 * WX in both formats
-    static constexpr int R = kThreads / BX;         // threads sharing a row
-    static_assert(R == 1 || R == 2 || R == 4, "workgroup tile rows must be 64, 128 or 256");
+    static constexpr int R = THREADS / BX;          // threads sharing a row (BX = rows of the workgroup tile)
+    static_assert(R == 1 || R == 2 || R == 4, "a row of the workgroup tile is shared by 1, 2 or 4 threads");
     static constexpr int UPB = kWordsPerRow / R;    // consecutive word groups a thread owns per k block
+    static constexpr int UNITS = UPB * SB;          // units per thread and stage
+    static constexpr int TPU = FP4 ? 4 : 8;         // output dwords (tasks) per unit
+    static constexpr int TASKS = UNITS * TPU;       // expansion tasks per thread and stage
     uint32_t regs[UNITS][NB];
     uint32_t keep[SB];           // all ones, or zero for a k block past the end of K (FP4 stages only)
     const uint32_t *src0;        // word address of (row, plane 0, word gq0 * UPB) in k block 0, gq0 = tid / BX
@@ -200,11 +199,13 @@ struct Acc<true> {
     static __device__ __forceinline__ uint32_t four_s(float v) { return (uint32_t)(int32_t)(v * 16.0f); }
 };
 
-template <int P, int Q, int WM, int WN, bool FP4>
-__global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int tiles_n, int tiles_total)
+// Tile shape: GM x GN waves, each owning WM x WN blocks of 32 x 32.
+template <int P, int Q, int WM, int WN, int GM, int GN, bool FP4>
+__global__ __launch_bounds__(64 * GM * GN) void gemm_mfma_kernel(GemmArgs g, int tiles_n, int tiles_total)
 {
     static_assert(!FP4 || (P <= 2 && Q <= 2), "E2M1 patterns are linear in the code only up to 3");
-    constexpr int BM = 64 * WM, BN = 64 * WN;
+    constexpr int kThreads = 64 * GM * GN;
+    constexpr int BM = 32 * WM * GM, BN = 32 * WN * GN;
     constexpr int KS = kStageSteps;
     constexpr int A_STAGE = BM * 32 * KS, B_STAGE = BN * 32 * KS;  // bytes: 1 KB per 32 rows and k step
     constexpr int STAGE = A_STAGE + B_STAGE;
@@ -215,7 +216,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int til
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wave_m = wave >> 1, wave_n = wave & 1;
+    const int wave_m = wave / GN, wave_n = wave % GN;
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
     // tiles so that the packed rows it re-reads stay in its own L2.
@@ -224,8 +225,10 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int til
     const int tm = lid / tiles_n, tn = lid % tiles_n;
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
-    Loader<P, WM, FP4> la;
-    Loader<Q, WN, FP4> lb;
+    typedef Loader<P, BM, kThreads, FP4> LoaderA;
+    typedef Loader<Q, BN, kThreads, FP4> LoaderB;
+    LoaderA la;
+    LoaderB lb;
     la.init(g.a, m0, round_up(g.M, kRowBlock), g.nkb, tid);
     lb.init(g.w, n0, round_up(g.N, kRowBlock), g.nkb, tid);
 
@@ -261,15 +264,15 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int til
     constexpr int MFMAS = WM * WN * KS;              // MFMAs per stage and wave
     constexpr int PER_KS = WM * WN;                  // MFMAs per k step
     constexpr int READS = WM + WN;                   // fragment reads per k step
-    constexpr int TASKS_A = 8 * WM, TASKS = 8 * (WM + WN);  // expansion dwords per thread and stage
+    constexpr int TASKS_A = LoaderA::TASKS, TASKS = LoaderA::TASKS + LoaderB::TASKS;  // expansion dwords per thread and stage
 
     for (int64_t st = 0; st < nst; ++st) {
         const uint8_t *cur = lds + (st & 1) * STAGE;
         uint8_t *nxt = lds + ((st + 1) & 1) * STAGE;
 
         // raw planes of stage st+1 are in registers; start the loads of st+2 right away
-        Loader<P, WM, FP4> ea = la;
-        Loader<Q, WN, FP4> eb = lb;
+        LoaderA ea = la;
+        LoaderB eb = lb;
         ea.mask();
         eb.mask();
         const int64_t sf = (st + 2 <= last) ? st + 2 : last;  // clamped: the surplus fetches are discarded
@@ -421,15 +424,15 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g, int til
     }
 }
 
-template <int P, int Q, int WM, int WN, bool FP4>
+template <int P, int Q, int WM, int WN, int GM, int GN, bool FP4>
 hipError_t launch_variant(const GemmArgs &g, hipStream_t stream)
 {
-    constexpr int BM = 64 * WM, BN = 64 * WN;
+    constexpr int BM = 32 * WM * GM, BN = 32 * WN * GN, threads = 64 * GM * GN;
     constexpr size_t lds_bytes = 2 * (size_t)(BM + BN) * 32 * kStageSteps;
     const int64_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int64_t tiles = tiles_m * tiles_n;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-    auto kernel = gemm_mfma_kernel<P, Q, WM, WN, FP4>;
+    auto kernel = gemm_mfma_kernel<P, Q, WM, WN, GM, GN, FP4>;
     static bool attr_set = false;  // raising the dynamic LDS limit is idempotent; a race here is harmless
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -437,7 +440,7 @@ hipError_t launch_variant(const GemmArgs &g, hipStream_t stream)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)tiles), dim3(kThreads), lds_bytes, stream, g, (int)tiles_n,
+    hipLaunchKernelGGL(kernel, dim3((unsigned)tiles), dim3(threads), lds_bytes, stream, g, (int)tiles_n,
                        (int)tiles);
     return hipGetLastError();
 }
@@ -469,10 +472,10 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream)
         }
     }
     switch (best) {
-    case 0: return launch_variant<P, Q, 4, 4, FP4>(g, stream);
-    case 1: return launch_variant<P, Q, 4, 2, FP4>(g, stream);
-    case 2: return launch_variant<P, Q, 2, 4, FP4>(g, stream);
-    default: return launch_variant<P, Q, 2, 2, FP4>(g, stream);
+    case 0: return launch_variant<P, Q, 4, 4, 2, 2, FP4>(g, stream);
+    case 1: return launch_variant<P, Q, 4, 2, 2, 2, FP4>(g, stream);
+    case 2: return launch_variant<P, Q, 2, 4, 2, 2, FP4>(g, stream);
+    default: return launch_variant<P, Q, 2, 2, 2, 2, FP4>(g, stream);
     }
 }
 
