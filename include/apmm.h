@@ -52,7 +52,7 @@ typedef enum {
 
 /* Bytes of the packed form of a rows x K operand of `bits`-bit codes (paper Sec. 4.1:
  * `bits` one-bit planes in 32-bit words, concatenated).  Rows are padded to a multiple
- * of 32 and K to a multiple of 128.  Returns 0 for invalid arguments. */
+ * of 32 and K to a multiple of 512.  Returns 0 for invalid arguments. */
 size_t apmm_packed_bytes(int64_t rows, int64_t K, int bits);
 
 /* Bytes of scratch apmm_gemm needs for this problem (may be 0). */
@@ -85,7 +85,7 @@ apmm_status apmm_unpack(const void *packed, int64_t rows, int64_t K, int bits,
  *   a_scale  : device, M binary16 per-token scales, or NULL (= 1)
  *   workspace: device scratch of at least apmm_workspace_bytes() bytes (may be NULL if 0)
  * At least one of c_i32 / c_f16 must be non-NULL.  M == 0 or N == 0 returns APMM_OK
- * without a launch.  Returns APMM_ERR_OVERFLOW if roundup(K,128)*(2^p-1)*(2^q-1) > INT32_MAX. */
+ * without a launch.  Returns APMM_ERR_OVERFLOW if roundup(K,512)*(2^p-1)*(2^q-1) > INT32_MAX. */
 apmm_status apmm_gemm(int64_t M, int64_t N, int64_t K, int p, int q,
                       const void *a_packed, const void *w_packed,
                       int32_t *c_i32, uint16_t *c_f16,

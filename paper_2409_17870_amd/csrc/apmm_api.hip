@@ -46,7 +46,7 @@ size_t apmm_packed_bytes(int64_t rows, int64_t K, int bits)
 {
     if (rows < 0 || K < 1 || !bits_ok(bits)) return 0;
     const int64_t rows_p = apmm::round_up(rows, apmm::kRowBlock);
-    const int64_t k_p = apmm::round_up(K, apmm::kKBlock);
+    const int64_t k_p = apmm::round_up(K, apmm::kKPad);
     return (size_t)rows_p * (size_t)k_p / 8u * (size_t)bits;
 }
 
@@ -85,7 +85,7 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
     if (M < 0 || N < 0 || K < 1 || !bits_ok(p) || !bits_ok(q))
         return fail(APMM_ERR_INVALID_ARG, "gemm: M < 0, N < 0, K < 1 or bits outside [1, 8]");
     if (algo < APMM_ALGO_AUTO || algo > APMM_ALGO_MFMA_FP4) return fail(APMM_ERR_INVALID_ARG, "gemm: unknown algo");
-    const int64_t k_p = apmm::round_up(K, apmm::kKBlock);
+    const int64_t k_p = apmm::round_up(K, apmm::kKPad);
     const int64_t unit = (int64_t)((1 << p) - 1) * (int64_t)((1 << q) - 1);
     if (k_p > INT32_MAX / unit) return fail(APMM_ERR_OVERFLOW, "gemm: K * (2^p - 1) * (2^q - 1) exceeds the 32-bit output");
     if (M == 0 || N == 0) return APMM_OK;

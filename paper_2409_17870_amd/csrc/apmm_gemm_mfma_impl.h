@@ -40,52 +40,12 @@
 // The k order inside a fragment is whatever the expansion produces; both operands use the same
 // order, which is all the contraction needs.
 #pragma once
-#include <cstdlib>
-#include <type_traits>
-#include <utility>
-
-#include "apmm_epilogue.h"
-#include "apmm_kernels.h"
+#include "apmm_mfma_common.h"
 
 namespace apmm {
 namespace mfma {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-typedef float v16f __attribute__((ext_vector_type(16)));
-
-constexpr int kMaxThreads = 512;
 constexpr int kStageSteps = 4;  // MFMA k steps per pipeline stage
-
-// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), always flattened,
-// so that every index below is a constant (shift amounts, register numbers, LDS offsets).
-template <class F, int... Is>
-__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
-{
-    (f(std::integral_constant<int, Is>{}), ...);
-}
-template <int N, class F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
-// Output dword t of the expansion of one 32-element group given its planes w[0..NB-1].
-// Plane i is stored rotated left by i (apmm_layout.h).
-//   INT8: dword t of 8 holds 4 codes as bytes; their plane-i bits are at in-byte position (t+i) % 8.
-//   FP4 : dword t of 4 holds 8 codes as nibbles; their plane-i bits are at in-nibble position (t+i) % 4.
-// One rotate right by t brings every plane to its own bit i of the byte / nibble.
-template <int NB, bool FP4>
-__device__ __forceinline__ uint32_t expand_dword(const uint32_t (&w)[NB], int t)
-{
-    constexpr uint32_t ones = FP4 ? 0x11111111u : 0x01010101u;
-    constexpr int period = FP4 ? 4 : 8;
-    uint32_t y = 0;
-#pragma unroll
-    for (int i = 0; i < NB; ++i) y |= w[i] & (ones << ((t + i) % period));
-    return t ? __builtin_rotateright32(y, t) : y;
-}
 
 // Per-thread share of one operand's workgroup tile and stage: UNITS units, one unit = (row, 32-k word
 // group).  A stage spans SB packed k blocks (1 for INT8, 2 for FP4), i.e. 4*SB word groups per row.
@@ -172,31 +132,6 @@ struct Loader {
         if (t % 4 == 3)
             *reinterpret_cast<uint4 *>(stage + lds_off[s] + (t / 4) * 512) = make_uint4(o[0], o[1], o[2], o[3]);
     }
-};
-
-template <bool FP4>
-struct Acc;
-template <>
-struct Acc<false> {
-    typedef v16i type;
-    static __device__ __forceinline__ type mma(v4i a, v4i b, type c)
-    {
-        return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
-    }
-    // 4 S as a wrapping 32-bit integer
-    static __device__ __forceinline__ uint32_t four_s(int v) { return (uint32_t)v << 2; }
-};
-template <>
-struct Acc<true> {
-    typedef v16f type;
-    static __device__ __forceinline__ type mma(v4i a, v4i b, type c)
-    {
-        const v8i a8 = {a[0], a[1], a[2], a[3], 0, 0, 0, 0}, b8 = {b[0], b[1], b[2], b[3], 0, 0, 0, 0};
-        // formats 4 / 4 = E2M1 for both operands; scale exponent 127 = 2^0
-        return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 127, 0, 127);
-    }
-    // acc = S / 4 exactly, so 4 S = 16 acc
-    static __device__ __forceinline__ uint32_t four_s(float v) { return (uint32_t)(int32_t)(v * 16.0f); }
 };
 
 // Tile shape: GM x GN waves, each owning WM x WN blocks of 32 x 32.
@@ -489,16 +424,6 @@ hipError_t launch_int8_p(const GemmArgs &g, hipStream_t stream)
     case 3: return launch_tiles<P, 3, false>(g, stream);
     case 4: return launch_tiles<P, 4, false>(g, stream);
     }
-    return hipErrorInvalidValue;
-}
-
-// FP4 operands: p, q in {1, 2}.
-inline hipError_t launch_fp4(const GemmArgs &g, hipStream_t stream)
-{
-    if (g.p == 1 && g.q == 1) return launch_tiles<1, 1, true>(g, stream);
-    if (g.p == 1 && g.q == 2) return launch_tiles<1, 2, true>(g, stream);
-    if (g.p == 2 && g.q == 1) return launch_tiles<2, 1, true>(g, stream);
-    if (g.p == 2 && g.q == 2) return launch_tiles<2, 2, true>(g, stream);
     return hipErrorInvalidValue;
 }
 

@@ -4,7 +4,7 @@
 // concatenated tile by tile:
 //
 //   word(rb, kb, i, r, g)   rb = row / 32       row block (rows padded to a multiple of 32)
-//                           kb = k / 128        k block   (K padded to a multiple of 128)
+//                           kb = k / 128        k block   (K padded to a multiple of 512: nkb is a multiple of 4)
 //                           i  = plane (bit of the code), 0 .. n-1
 //                           r  = row % 32
 //                           g  = (k % 128) / 32 word inside the k block
@@ -34,6 +34,7 @@ namespace apmm {
 
 constexpr int kRowBlock = 32;    // rows per packed tile
 constexpr int kKBlock = 128;     // k elements per packed tile
+constexpr int kKPad = 512;       // K is padded to a multiple of this (four k blocks = two stages of the direct MFMA kernel)
 constexpr int kWordsPerRow = 4;  // 32-bit words per (row, plane) inside a tile
 constexpr int kPlaneWords = kRowBlock * kWordsPerRow;  // words between consecutive planes of a tile
 

@@ -96,7 +96,7 @@ hipError_t launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits, 
                        hipStream_t stream)
 {
     const int64_t rows_p = round_up(rows, kRowBlock);
-    const int64_t nkb = round_up(K, kKBlock) / kKBlock;
+    const int64_t nkb = round_up(K, kKPad) / kKBlock;
     const int64_t total = rows_p * nkb * kWordsPerRow;
     if (total == 0) return hipSuccess;
     const int64_t blocks = (total + kThreads - 1) / kThreads;
@@ -109,7 +109,7 @@ hipError_t launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits, 
 hipError_t launch_unpack(const uint32_t *packed, int64_t rows, int64_t K, int bits, uint8_t *codes,
                          hipStream_t stream)
 {
-    const int64_t nkb = round_up(K, kKBlock) / kKBlock;
+    const int64_t nkb = round_up(K, kKPad) / kKBlock;
     const int64_t total = rows * nkb * kWordsPerRow;
     if (total == 0) return hipSuccess;
     const int64_t blocks = (total + kThreads - 1) / kThreads;

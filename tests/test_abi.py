@@ -44,10 +44,10 @@ def test_single_hip_runtime_in_process(lib):
 
 
 def test_packed_bytes(lib):
-    assert lib.apmm_packed_bytes(32, 128, 1) == 32 * 128 // 8
-    assert lib.apmm_packed_bytes(1, 1, 1) == 32 * 128 // 8           # padded to one tile
+    assert lib.apmm_packed_bytes(32, 512, 1) == 32 * 512 // 8
+    assert lib.apmm_packed_bytes(1, 1, 1) == 32 * 512 // 8           # padded to 32 rows x 512 k
     assert lib.apmm_packed_bytes(4096, 4096, 2) == 4096 * 4096 * 2 // 8
-    assert lib.apmm_packed_bytes(33, 129, 3) == 64 * 256 * 3 // 8
+    assert lib.apmm_packed_bytes(33, 129, 3) == 64 * 512 * 3 // 8
     assert lib.apmm_packed_bytes(0, 128, 2) == 0
     assert lib.apmm_packed_bytes(8, 128, 0) == 0 and lib.apmm_packed_bytes(8, 128, 9) == 0
     assert lib.apmm_packed_bytes(-1, 128, 2) == 0 and lib.apmm_packed_bytes(8, 0, 2) == 0
@@ -70,9 +70,9 @@ def test_argument_errors_come_before_any_launch(lib):
     assert _gemm(lib, 4, 4, 128, 1, 1, algo=7) == INVALID
     assert _gemm(lib, 64, 64, 128, 3, 1, algo=4) == UNSUPPORTED     # E2M1 holds 2-bit codes only
     assert b"" != lib.apmm_last_error()
-    # 2^31 / (255 * 255) = 33025.5: K = 33024 fits, the next k block does not
-    assert _gemm(lib, 0, 4, 33024, 8, 8) == 0                       # M == 0: ok, nothing launched
-    assert _gemm(lib, 4, 4, 33025, 8, 8) == OVERFLOW
+    # 2^31 / (255 * 255) = 33025.5: K = 32768 = 64 * 512 fits, the next padded K (33280) does not
+    assert _gemm(lib, 0, 4, 32768, 8, 8) == 0                       # M == 0: ok, nothing launched
+    assert _gemm(lib, 4, 4, 32769, 8, 8) == OVERFLOW
     assert _gemm(lib, 4, 4, 40000, 8, 8) == OVERFLOW
     assert _gemm(lib, 64, 64, 128, 8, 8, algo=2) == UNSUPPORTED     # int8 MFMA cannot hold 8-bit codes
     assert lib.apmm_status_string(OVERFLOW) == b"result exceeds 32 bits"

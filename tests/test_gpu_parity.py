@@ -80,11 +80,11 @@ def test_pack_unpack_roundtrip(gpu, rows, K, bits):
 def test_pack_is_plane_decomposition(gpu):
     """Sec. 4.1: the packed buffer holds exactly `bits` one-bit planes (popcount per plane matches)."""
     torch, binding = gpu
-    rows, K, bits = 32, 128, 3
+    rows, K, bits = 32, 128, 3                                        # K is padded to 512: four tiles
     rng = np.random.default_rng(5)
     codes = rng.integers(0, 8, size=(rows, K), dtype=np.uint8)
     packed = binding.apmm_pack_weights(torch.from_numpy(codes).to("cuda:0"), bits).cpu().numpy()
-    words = packed.view(np.uint32).reshape(bits, rows, 4)            # one tile: [plane][row][word]
+    words = packed.view(np.uint32).reshape(4, bits, rows, 4)[0]      # first tile: [plane][row][word]
     for i in range(bits):
         for r in range(rows):
             ones = sum(bin(int(x)).count("1") for x in words[i, r])
