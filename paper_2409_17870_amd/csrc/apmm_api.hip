@@ -47,7 +47,7 @@ size_t apmm_packed_bytes(int64_t rows, int64_t K, int bits)
     if (rows < 0 || K < 1 || !bits_ok(bits)) return 0;
     const int64_t rows_p = apmm::round_up(rows, apmm::kRowBlock);
     const int64_t k_p = apmm::round_up(K, apmm::kKPad);
-    return (size_t)rows_p * (size_t)k_p / 8u * (size_t)bits;
+    return (size_t)rows_p * (size_t)k_p / 8u * (size_t)bits + (size_t)rows_p * 4u;  // planes + row sums
 }
 
 size_t apmm_workspace_bytes(int64_t, int64_t, int64_t, int, int) { return 0; }
@@ -102,6 +102,8 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
     g.p = p; g.q = q;
     g.a = static_cast<const uint32_t *>(a_packed);
     g.w = static_cast<const uint32_t *>(w_packed);
+    g.a_sum = reinterpret_cast<const int32_t *>(g.a + apmm::row_sum_word(apmm::round_up(M, apmm::kRowBlock), g.nkb, p));
+    g.w_sum = reinterpret_cast<const int32_t *>(g.w + apmm::row_sum_word(apmm::round_up(N, apmm::kRowBlock), g.nkb, q));
     g.c_i32 = c_i32; g.c_f16 = c_f16;
     g.w_scale = w_scale; g.a_scale = a_scale;
     g.pad_corr = (int32_t)((k_p - K) * unit);

@@ -36,7 +36,6 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
     constexpr int TASKS = 4 * FRAGS;         // expansion dwords per k step
     static_assert(TASKS % PER_KS == 0, "expansion tasks must spread evenly over the MFMAs of a k step");
     constexpr int TPM = TASKS / PER_KS;      // tasks per MFMA
-    __shared__ __align__(16) int32_t pa_lds[4][32 * WM];   // epilogue only: PA of each wave's rows
     typedef typename Acc<FP4>::type acc_t;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -85,17 +84,6 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[bi][bj][v] = 0;
 
-    // weighted popcounts of this lane's rows (its k blocks only; the other half of K is in lane ^ 32)
-    uint32_t pop_a[WM][P], pop_b[WN][Q];
-#pragma unroll
-    for (int bi = 0; bi < WM; ++bi)
-#pragma unroll
-        for (int i = 0; i < P; ++i) pop_a[bi][i] = 0;
-#pragma unroll
-    for (int bj = 0; bj < WN; ++bj)
-#pragma unroll
-        for (int i = 0; i < Q; ++i) pop_b[bj][i] = 0;
-
     v4i af[2][WM], bf[2][WN];
     // dword d of fragment f (f < WM: A block f, else B block f - WM) of k step ks, from buffer buf
     auto expand = [&](auto buf_c, auto ks_c, auto f_c, auto d_c) __attribute__((always_inline)) {
@@ -114,17 +102,6 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
             bf[ks & 1][f - WM][d] = (int)expand_dword<Q, FP4>(w, d);
         }
     };
-    // popcount task c of a stage: word c % 4 of raw vector c / 4 (A vectors first, then B)
-    constexpr int COUNT_TASKS = 4 * (WM * P + WN * Q);
-    auto count_task = [&](auto buf_c, auto c_c) __attribute__((always_inline)) {
-        constexpr int buf = decltype(buf_c)::value, c = decltype(c_c)::value, vec = c / 4, comp = c % 4;
-        auto word = [](const uint4 &v) { return comp == 0 ? v.x : comp == 1 ? v.y : comp == 2 ? v.z : v.w; };
-        if constexpr (vec < WM * P)
-            pop_a[vec / P][vec % P] += __popc(word(ra[buf][vec / P][vec % P]));
-        else
-            pop_b[(vec - WM * P) / Q][(vec - WM * P) % Q] += __popc(word(rb[buf][(vec - WM * P) / Q][(vec - WM * P) % Q]));
-    };
-
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
     const int64_t nst = g.nkb / 2;  // the packed K is a multiple of 512: an even number of whole stages
@@ -154,10 +131,6 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
                 else
                     expand(Other{}, I0{}, F{}, D{});
             });
-            // and of the stage's plane popcounts (PA, PW of the recovery)
-            static_for<COUNT_TASKS>([&](auto c_c) __attribute__((always_inline)) {
-                if constexpr (decltype(c_c)::value * (KS * PER_KS) / COUNT_TASKS == i) count_task(buf_c, c_c);
-            });
             __builtin_amdgcn_sched_barrier(0);
         });
     };
@@ -166,31 +139,24 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
         stage(I1{}, st + 1);
     }
 
-    // PA of the wave's rows: add the two k halves, leave them in LDS for the lanes that need them
-    uint32_t pw[WN];
-#pragma unroll
-    for (int bj = 0; bj < WN; ++bj) {
-        uint32_t v = 0;
-#pragma unroll
-        for (int i = 0; i < Q; ++i) v += pop_b[bj][i] << i;
-        pw[bj] = v + __shfl_xor(v, 32);  // this lane's column is row l % 32 of B block bj
-    }
-#pragma unroll
-    for (int bi = 0; bi < WM; ++bi) {
-        uint32_t v = 0;
-#pragma unroll
-        for (int i = 0; i < P; ++i) v += pop_a[bi][i] << i;
-        v += __shfl_xor(v, 32);
-        if (kh == 0) pa_lds[wave][bi * 32 + r32] = (int32_t)v;
-    }
-    __syncthreads();
-
+    // recovery terms: the code sums of the rows come with the packed operands
     const int rsub = kh * 4;
     const int64_t m_lane = m0 + wave_m * WM * 32 + rsub, n_lane = n0 + wave_n * WN * 32 + r32;
     const bool interior = (m0 + BM <= g.M) && (n0 + BN <= g.N);
+    uint32_t pw[WN];
+#pragma unroll
+    for (int bj = 0; bj < WN; ++bj) {
+        const int64_t n = n_lane + bj * 32;
+        pw[bj] = (uint32_t)g.w_sum[n < rows_b ? n : rows_b - 1];
+    }
     store_wave_tile<P, Q, WM, WN, FP4>(
         g, acc, m_lane, n_lane, interior,
-        [&](int bi, int v4) { return *reinterpret_cast<const int4 *>(&pa_lds[wave][bi * 32 + 8 * v4 + rsub]); }, pw);
+        [&](int bi, int v4) {
+            int64_t m = m_lane + bi * 32 + 8 * v4;  // four consecutive rows, 16-byte aligned
+            if (m + 4 > rows_a) m = rows_a - 4;     // past the operand: any valid address, never stored
+            return *reinterpret_cast<const int4 *>(g.a_sum + m);
+        },
+        pw);
 }
 
 template <int P, int Q, int WM, int WN>

@@ -112,22 +112,16 @@ struct Loader {
             for (int i = 0; i < NB; ++i) regs[s][i] &= keep[s / UPB];
     }
     // whole share at once (prologue)
-    __device__ __forceinline__ void expand_to_lds(uint8_t *stage, uint32_t (&counts)[NB]) const
+    __device__ __forceinline__ void expand_to_lds(uint8_t *stage) const
     {
         uint32_t o[4];
 #pragma unroll
-        for (int task = 0; task < TASKS; ++task) expand_task(stage, task, o, counts);
+        for (int task = 0; task < TASKS; ++task) expand_task(stage, task, o);
     }
-    // one output dword of the share: task = TPU * unit + t; every fourth task stores 16 bytes to LDS,
-    // and the first task of a unit adds the unit's plane popcounts to `counts`
-    __device__ __forceinline__ void expand_task(uint8_t *stage, int task, uint32_t (&o)[4],
-                                                uint32_t (&counts)[NB]) const
+    // one output dword of the share: task = TPU * unit + t; every fourth task stores 16 bytes to LDS
+    __device__ __forceinline__ void expand_task(uint8_t *stage, int task, uint32_t (&o)[4]) const
     {
         const int s = task / TPU, t = task % TPU;
-        if (t == 0) {
-#pragma unroll
-            for (int i = 0; i < NB; ++i) counts[i] += __popc(regs[s][i]);
-        }
         o[t % 4] = expand_dword<NB, FP4>(regs[s], t);
         if (t % 4 == 3)
             *reinterpret_cast<uint4 *>(stage + lds_off[s] + (t / 4) * 512) = make_uint4(o[0], o[1], o[2], o[3]);
@@ -179,16 +173,10 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_mfma_kernel(GemmArgs g, int
     const int64_t last = nst - 1;
     la.fetch(0, g.nkb);
     lb.fetch(0, g.nkb);
-    // per plane: set bits of this thread's units so far (all units of a thread lie in one row)
-    uint32_t pop_a[P], pop_b[Q];
-#pragma unroll
-    for (int i = 0; i < P; ++i) pop_a[i] = 0;
-#pragma unroll
-    for (int i = 0; i < Q; ++i) pop_b[i] = 0;
     la.mask();
     lb.mask();
-    la.expand_to_lds(lds, pop_a);
-    lb.expand_to_lds(lds + A_STAGE, pop_b);
+    la.expand_to_lds(lds);
+    lb.expand_to_lds(lds + A_STAGE);
     la.fetch(last < 1 ? last : 1, g.nkb);
     lb.fetch(last < 1 ? last : 1, g.nkb);
     __syncthreads();
@@ -213,13 +201,6 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_mfma_kernel(GemmArgs g, int
         const int64_t sf = (st + 2 <= last) ? st + 2 : last;  // clamped: the surplus fetches are discarded
         la.fetch(sf, g.nkb);
         lb.fetch(sf, g.nkb);
-        // the last iteration re-expands the final stage: its popcounts must not be counted twice
-        uint32_t cnt_a[P], cnt_b[Q];
-#pragma unroll
-        for (int i = 0; i < P; ++i) cnt_a[i] = 0;
-#pragma unroll
-        for (int i = 0; i < Q; ++i) cnt_b[i] = 0;
-
         v4i af[2][WM], bf[2][WN];
         // fragment r of k step ks: r = 0 -> A block 0, r = 1..WN -> B blocks, then the other A blocks
         auto read_frag = [&](auto ks_c, auto r_c) __attribute__((always_inline)) {
@@ -254,109 +235,35 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_mfma_kernel(GemmArgs g, int
                 constexpr int task = decltype(t_c)::value;
                 if constexpr (task * MFMAS / TASKS == i) {
                     if constexpr (task < TASKS_A)
-                        ea.expand_task(nxt, task, oa, cnt_a);
+                        ea.expand_task(nxt, task, oa);
                     else
-                        eb.expand_task(nxt + A_STAGE, task - TASKS_A, ob, cnt_b);
+                        eb.expand_task(nxt + A_STAGE, task - TASKS_A, ob);
                 }
             });
             __builtin_amdgcn_sched_barrier(0);
         });
-        const uint32_t keep = (st < last) ? 0xffffffffu : 0u;
-#pragma unroll
-        for (int i = 0; i < P; ++i) pop_a[i] += cnt_a[i] & keep;
-#pragma unroll
-        for (int i = 0; i < Q; ++i) pop_b[i] += cnt_b[i] & keep;
         __syncthreads();
     }
 
-    // Row and column terms of the recovery.  A thread's units all lie in row tid % BX of its operand
-    // tile; 256 / BX threads share a row, each leaves its partial in LDS (free now: the loop ended
-    // with a barrier) and the readers add them up.
-    constexpr int SHARE_A = kThreads / BM > 0 ? kThreads / BM : 1;
-    constexpr int SHARE_B = kThreads / BN > 0 ? kThreads / BN : 1;
-    int32_t *sum_a = reinterpret_cast<int32_t *>(lds);        // [SHARE_A][BM]
-    int32_t *sum_b = sum_a + SHARE_A * BM;                    // [SHARE_B][BN]
-    {
-        uint32_t wa = 0, wb = 0;
-#pragma unroll
-        for (int i = 0; i < P; ++i) wa += pop_a[i] << i;
-#pragma unroll
-        for (int i = 0; i < Q; ++i) wb += pop_b[i] << i;
-        sum_a[(tid / BM) * BM + tid % BM] = (int32_t)wa;
-        sum_b[(tid / BN) * BN + tid % BN] = (int32_t)wb;
-    }
-    __syncthreads();
-    // C = 4 S - 2 cw PA[m] - 2 ca PW[n] + K ca cw, in wrapping 32-bit arithmetic (C itself fits)
-    constexpr uint32_t ca = (1u << P) - 1, cw = (1u << Q) - 1;
-    const uint32_t base = (uint32_t)g.K * ca * cw;
-
-    // Accumulator layout of the 32x32 MFMA: lane l, register v holds
-    //   row = 8*(v/4) + 4*(l/32) + v%4, column = l%32.
+    // recovery terms: the code sums of the rows come with the packed operands
     const int col = lane & 31, rsub = (lane >> 5) * 4;
-    uint32_t col_term[WN];
-    float sw[WN];
+    const int64_t rows_a = round_up(g.M, kRowBlock), rows_b = round_up(g.N, kRowBlock);
+    const int64_t m_lane = m0 + wave_m * WM * 32 + rsub, n_lane = n0 + wave_n * WN * 32 + col;
+    const bool interior = (m0 + BM <= g.M) && (n0 + BN <= g.N);
+    uint32_t pw[WN];
 #pragma unroll
     for (int bj = 0; bj < WN; ++bj) {
-        const int nl = (wave_n * WN + bj) * 32 + col;
-        uint32_t pw = 0;
-#pragma unroll
-        for (int h = 0; h < SHARE_B; ++h) pw += (uint32_t)sum_b[h * BN + nl];
-        col_term[bj] = base - 2u * ca * pw;
-        const int64_t n = n0 + nl;
-        sw[bj] = (g.w_scale && n < g.N) ? half_bits_to_float(g.w_scale[n]) : 1.0f;
+        const int64_t n = n_lane + bj * 32;
+        pw[bj] = (uint32_t)g.w_sum[n < rows_b ? n : rows_b - 1];
     }
-
-    // The output mode and the border test are uniform over the workgroup: pick one of six
-    // straight-line store sequences instead of testing per element.
-    const int64_t m_lane = m0 + wave_m * WM * 32 + rsub;  // row of (bi = 0, v4 = 0, r = 0)
-    const int64_t n_lane = n0 + wave_n * WN * 32 + col;   // column of bj = 0
-    auto emit = [&](auto guard_c, auto i32_c, auto f16_c) __attribute__((always_inline)) {
-        constexpr bool GUARD = decltype(guard_c)::value, I32 = decltype(i32_c)::value, F16 = decltype(f16_c)::value;
-        int32_t *ci = I32 ? g.c_i32 + m_lane * g.N + n_lane : nullptr;
-        uint16_t *ch = F16 ? g.c_f16 + m_lane * g.N + n_lane : nullptr;
-#pragma unroll
-        for (int bi = 0; bi < WM; ++bi) {
-#pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                const int ml = (wave_m * WM + bi) * 32 + 8 * v4 + rsub;  // first of four consecutive rows
-                int4 pa = *reinterpret_cast<const int4 *>(sum_a + ml);
-#pragma unroll
-                for (int h = 1; h < SHARE_A; ++h) {
-                    const int4 more = *reinterpret_cast<const int4 *>(sum_a + h * BM + ml);
-                    pa.x += more.x; pa.y += more.y; pa.z += more.z; pa.w += more.w;
-                }
-                const uint32_t row_term[4] = {0u - 2u * cw * (uint32_t)pa.x, 0u - 2u * cw * (uint32_t)pa.y,
-                                              0u - 2u * cw * (uint32_t)pa.z, 0u - 2u * cw * (uint32_t)pa.w};
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int64_t row = (int64_t)(bi * 32 + 8 * v4 + r);  // relative to m_lane
-                    if (GUARD && m_lane + row >= g.M) continue;
-                    float sa = 1.0f;
-                    if constexpr (F16) sa = g.a_scale ? half_bits_to_float(g.a_scale[m_lane + row]) : 1.0f;
-#pragma unroll
-                    for (int bj = 0; bj < WN; ++bj) {
-                        if (GUARD && n_lane + bj * 32 >= g.N) continue;
-                        const uint32_t c = Acc<FP4>::four_s(acc[bi][bj][4 * v4 + r]) + row_term[r] + col_term[bj];
-                        if constexpr (I32) ci[row * g.N + bj * 32] = (int32_t)c;
-                        if constexpr (F16) ch[row * g.N + bj * 32] = float_to_half_bits((float)(int32_t)c * sa * sw[bj]);
-                    }
-                }
-            }
-        }
-    };
-    using T = std::true_type;
-    using F = std::false_type;
-    const bool interior = (m0 + BM <= g.M) && (n0 + BN <= g.N);
-    const bool i32 = g.c_i32 != nullptr, f16 = g.c_f16 != nullptr;
-    if (interior) {
-        if (i32 && !f16) emit(F{}, T{}, F{});
-        else if (!i32 && f16) emit(F{}, F{}, T{});
-        else emit(F{}, T{}, T{});
-    } else {
-        if (i32 && !f16) emit(T{}, T{}, F{});
-        else if (!i32 && f16) emit(T{}, F{}, T{});
-        else emit(T{}, T{}, T{});
-    }
+    store_wave_tile<P, Q, WM, WN, FP4>(
+        g, acc, m_lane, n_lane, interior,
+        [&](int bi, int v4) {
+            int64_t m = m_lane + bi * 32 + 8 * v4;  // four consecutive rows, 16-byte aligned
+            if (m + 4 > rows_a) m = rows_a - 4;     // past the operand: any valid address, never stored
+            return *reinterpret_cast<const int4 *>(g.a_sum + m);
+        },
+        pw);
 }
 
 template <int P, int Q, int WM, int WN, int GM, int GN, bool FP4>

@@ -23,6 +23,10 @@
 // XOR/popcount kernels rotate a plane word by the difference of the plane indices to compare
 // planes of different index.
 //
+// Behind the planes of all tiles follows one int32 per (padded) row: the sum of the row's codes over
+// the padded K, i.e. sum_i 2^i popcount(plane i).  The MFMA kernels multiply codes u instead of values
+// 2u - (2^n - 1) and need these sums to recover C.
+//
 // Padding: elements with k >= K have every plane bit set in BOTH operands.  Their
 // XOR is zero, and each contributes exactly (2^p - 1)(2^q - 1) to an integer dot
 // product, which the kernels subtract again.  Rows >= `rows` are all-zero words and
@@ -50,12 +54,20 @@ inline __host__ __device__ int64_t tile_row_word(int64_t row, int64_t kb, int64_
     return (((rb * nkb + kb) * n + i) * kRowBlock + r) * kWordsPerRow;
 }
 
+// index of the first row-sum word: the planes of rows_p x nkb*128 elements come first
+inline __host__ __device__ int64_t row_sum_word(int64_t rows_p, int64_t nkb, int n)
+{
+    return rows_p * nkb * n * (kKBlock / 32);
+}
+
 struct GemmArgs {
     int64_t M, N, K;
     int64_t nkb;          // roundup(K,128)/128
     int p, q;
     const uint32_t *a;    // packed activations
     const uint32_t *w;    // packed weights
+    const int32_t *a_sum; // per activation row: sum of its codes over the padded K
+    const int32_t *w_sum; // per weight row: the same
     int32_t *c_i32;       // may be null
     uint16_t *c_f16;      // may be null
     const uint16_t *w_scale;  // may be null

@@ -44,10 +44,10 @@ def test_single_hip_runtime_in_process(lib):
 
 
 def test_packed_bytes(lib):
-    assert lib.apmm_packed_bytes(32, 512, 1) == 32 * 512 // 8
-    assert lib.apmm_packed_bytes(1, 1, 1) == 32 * 512 // 8           # padded to 32 rows x 512 k
-    assert lib.apmm_packed_bytes(4096, 4096, 2) == 4096 * 4096 * 2 // 8
-    assert lib.apmm_packed_bytes(33, 129, 3) == 64 * 512 * 3 // 8
+    assert lib.apmm_packed_bytes(32, 512, 1) == 32 * 512 // 8 + 32 * 4  # planes + one int32 code sum per row
+    assert lib.apmm_packed_bytes(1, 1, 1) == 32 * 512 // 8 + 32 * 4  # padded to 32 rows x 512 k
+    assert lib.apmm_packed_bytes(4096, 4096, 2) == 4096 * 4096 * 2 // 8 + 4096 * 4
+    assert lib.apmm_packed_bytes(33, 129, 3) == 64 * 512 * 3 // 8 + 64 * 4
     assert lib.apmm_packed_bytes(0, 128, 2) == 0
     assert lib.apmm_packed_bytes(8, 128, 0) == 0 and lib.apmm_packed_bytes(8, 128, 9) == 0
     assert lib.apmm_packed_bytes(-1, 128, 2) == 0 and lib.apmm_packed_bytes(8, 0, 2) == 0

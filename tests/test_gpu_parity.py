@@ -84,11 +84,14 @@ def test_pack_is_plane_decomposition(gpu):
     rng = np.random.default_rng(5)
     codes = rng.integers(0, 8, size=(rows, K), dtype=np.uint8)
     packed = binding.apmm_pack_weights(torch.from_numpy(codes).to("cuda:0"), bits).cpu().numpy()
-    words = packed.view(np.uint32).reshape(4, bits, rows, 4)[0]      # first tile: [plane][row][word]
+    sums = packed.view(np.int32)[-rows:]                             # behind the planes: code sum per row
+    words = packed.view(np.uint32)[:-rows].reshape(4, bits, rows, 4)[0]  # first tile: [plane][row][word]
     for i in range(bits):
         for r in range(rows):
             ones = sum(bin(int(x)).count("1") for x in words[i, r])
             assert ones == int(((codes[r] >> i) & 1).sum())
+    pad = 512 - K                                                     # padded positions hold the all-ones code
+    assert np.array_equal(sums, codes.astype(np.int64).sum(axis=1) + pad * ((1 << bits) - 1))
 
 
 # ------------------------------------------------------------- small cases --
