@@ -47,7 +47,7 @@ typedef enum {
     APMM_ALGO_VALU_POPCOUNT = 1, /* plane pairs by XOR + popcount on the vector ALU, D_ij = K - 2*popc */
     APMM_ALGO_MFMA_INT8 = 2,     /* planes recombined to int8 codes in LDS, int8 MFMA, int32 accumulate (p, q <= 4) */
     APMM_ALGO_DECODE = 3,        /* small-M (M <= 16) weight-streaming kernel */
-    APMM_ALGO_MFMA_FP4 = 4       /* planes recombined to E2M1 codes in LDS, f8f6f4 MFMA, exact fp32 accumulate (p, q <= 2) */
+    APMM_ALGO_MFMA_FP4 = 4       /* planes recombined to E2M1 codes in registers, f8f6f4 MFMA, exact fp32 accumulate (p in {1,2,4}, q <= 2) */
 } apmm_algo;
 
 /* Bytes of the packed form of a rows x K operand of `bits`-bit codes (paper Sec. 4.1:

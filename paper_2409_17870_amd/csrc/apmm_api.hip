@@ -125,7 +125,7 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
         e = apmm::launch_gemm_mfma(g, s);
         break;
     case APMM_ALGO_MFMA_FP4:
-        if (!apmm::gemm_mfma_fp4_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: FP4 MFMA kernel covers p, q in 1..2 and K up to 2^20");
+        if (!apmm::gemm_mfma_fp4_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: FP4 MFMA kernel covers p in {1, 2, 4}, q in 1..2 and K up to 2^18");
         e = apmm::launch_gemm_mfma_fp4(g, s);
         break;
     case APMM_ALGO_DECODE:

@@ -26,12 +26,13 @@ hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t stream)
     return hipErrorInvalidValue;
 }
 
-// E2M1 holds the codes 0..3 exactly (as 0, 0.5, 1, 1.5); the fp32 accumulator holds S/4 exactly
-// while 9 K' / 4 stays below 2^22 quarter units, i.e. for every K' the ABI's 32-bit bound admits
-// up to 2^20; larger K goes to the int8 kernel.
+// E2M1 holds the codes 0..3 exactly (as 0, 0.5, 1, 1.5); the fp32 accumulator holds S/4 in quarter
+// units, exactly while S < 2^24: S <= 45 K' (4-bit x 2-bit codes), so K' up to 2^18 is safe; larger
+// K goes to the int8 kernel.
 bool gemm_mfma_fp4_supported(const GemmArgs &g)
 {
-    return g.p >= 1 && g.p <= 2 && g.q >= 1 && g.q <= 2 && g.nkb * kKBlock <= (1 << 20);
+    const bool p_ok = g.p == 1 || g.p == 2 || g.p == 4;  // 4-bit activations: two 2-bit plane groups
+    return p_ok && g.q >= 1 && g.q <= 2 && g.nkb * kKBlock <= (1 << 18);
 }
 
 hipError_t launch_gemm_mfma_fp4(const GemmArgs &g, hipStream_t stream) { return launch_gemm_mfma_fp4_impl(g, stream); }

@@ -10,7 +10,11 @@
 // stored so that one 16-byte load per plane brings a row's 128 k).  There is no LDS traffic, no
 // barrier in the k loop and nothing but C reaches global memory (paper Sec. 4.2).
 //
-// E2M1 (fp4) operands, p, q <= 2.  Workgroup = 2 x 2 waves, wave tile (32*WM) x (32*WN).
+// E2M1 (fp4) operands hold 2-bit codes.  q <= 2; p = 1, 2 or 4: 4-bit activation codes are split
+// into two 2-bit plane groups, u = 4 u_hi + u_lo, and K is swept once per group with the MFMA's
+// power-of-two operand scale set to 4 resp. 1, so that the one accumulator receives
+// S = 4 sum u_hi uw + sum u_lo uw (the plane-group form of the paper's shift-and-add, done by the
+// matrix unit's scale input).  Workgroup = 2 x 2 waves, wave tile (32*WM) x (32*WN).
 // Stage = two packed k blocks = four MFMA k steps of 64.  Lane l of a wave owns, for each of its
 // WM + WN row blocks, row l % 32 and k block l / 32 of the stage: per plane one 16-byte load = the
 // four 32-k word groups gq = 0..3 of that row.  MFMA k step ks multiplies word group gq = ks of both
@@ -27,8 +31,10 @@ namespace mfma {
 template <int P, int Q, int WM, int WN>
 __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int tiles_n, int tiles_total)
 {
-    static_assert(P <= 2 && Q <= 2, "E2M1 patterns are linear in the code only up to 3");
+    static_assert((P == 1 || P == 2 || P == 4) && Q <= 2, "E2M1 patterns are linear in the code only up to 3");
     constexpr bool FP4 = true;
+    constexpr int GROUPS = P > 2 ? 2 : 1;    // 2-bit plane groups of the activations
+    constexpr int PG = P / GROUPS;           // planes per group
     constexpr int BM = 64 * WM, BN = 64 * WN;
     constexpr int KS = 4;                    // MFMA k steps per stage (= word groups of a k block)
     constexpr int PER_KS = WM * WN;          // MFMAs per k step
@@ -63,13 +69,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
     constexpr int kPlaneVec = kPlaneWords / 4;             // uint4 between planes of a tile
     constexpr int kStageVecA = 2 * P * kPlaneVec, kStageVecB = 2 * Q * kPlaneVec;  // uint4 per stage (2 k blocks)
 
-    uint4 ra[2][WM][P], rb[2][WN][Q];  // raw plane words, double buffered by stage parity
+    uint4 ra[2][WM][PG], rb[2][WN][Q];  // raw plane words, double buffered by stage parity
+    int grp = 0;                        // plane group being swept
     auto load_stage = [&](auto buf_c, int64_t st) __attribute__((always_inline)) {
         constexpr int buf = decltype(buf_c)::value;
 #pragma unroll
         for (int bi = 0; bi < WM; ++bi)
 #pragma unroll
-            for (int i = 0; i < P; ++i) ra[buf][bi][i] = pa_src[bi][st * kStageVecA + i * kPlaneVec];
+            for (int i = 0; i < PG; ++i) ra[buf][bi][i] = pa_src[bi][st * kStageVecA + (grp * PG + i) * kPlaneVec];
 #pragma unroll
         for (int bj = 0; bj < WN; ++bj)
 #pragma unroll
@@ -91,10 +98,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
                       d = decltype(d_c)::value;
         auto word = [](const uint4 &v) { return ks == 0 ? v.x : ks == 1 ? v.y : ks == 2 ? v.z : v.w; };
         if constexpr (f < WM) {
-            uint32_t w[P];
+            uint32_t w[PG];
 #pragma unroll
-            for (int i = 0; i < P; ++i) w[i] = word(ra[buf][f][i]);
-            af[ks & 1][f][d] = (int)expand_dword<P, FP4>(w, d);
+            for (int i = 0; i < PG; ++i) w[i] = word(ra[buf][f][i]);
+            af[ks & 1][f][d] = GROUPS == 1 ? (int)expand_dword<PG, FP4>(w, d) : (int)expand_group_dword<PG>(w, d, grp * PG);
         } else {
             uint32_t w[Q];
 #pragma unroll
@@ -105,11 +112,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
     const int64_t nst = g.nkb / 2;  // the packed K is a multiple of 512: an even number of whole stages
-    load_stage(I0{}, 0);
-    // fragments of (stage 0, k step 0)
-    static_for<FRAGS>([&](auto f_c) __attribute__((always_inline)) {
-        static_for<4>([&](auto d_c) __attribute__((always_inline)) { expand(I0{}, I0{}, f_c, d_c); });
-    });
+    int scale_a = 127;
 
     // one stage with its raw words in buffer `buf`; loads stage st+1 (clamped) into the other buffer
     auto stage = [&](auto buf_c, int64_t st) __attribute__((always_inline)) {
@@ -120,7 +123,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
         static_for<KS * PER_KS>([&](auto i_c) __attribute__((always_inline)) {
             constexpr int i = decltype(i_c)::value;
             constexpr int ks = i / PER_KS, j = i % PER_KS, bi = j / WN, bj = j % WN;
-            acc[bi][bj] = Acc<FP4>::mma(af[ks & 1][bi], bf[ks & 1][bj], acc[bi][bj]);
+            acc[bi][bj] = Acc<FP4>::mma_scaled(af[ks & 1][bi], bf[ks & 1][bj], acc[bi][bj], scale_a);
             // this MFMA's share of the next k step's operands (after the last step: step 0 of stage st+1)
             static_for<TPM>([&](auto t_c) __attribute__((always_inline)) {
                 constexpr int task = j * TPM + decltype(t_c)::value;
@@ -134,9 +137,17 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
             __builtin_amdgcn_sched_barrier(0);
         });
     };
-    for (int64_t st = 0; st < nst; st += 2) {
-        stage(I0{}, st);
-        stage(I1{}, st + 1);
+    for (grp = 0; grp < GROUPS; ++grp) {
+        scale_a = 127 + grp * PG;  // E8M0 exponent: the codes of this group weigh 2^(grp * PG)
+        load_stage(I0{}, 0);
+        // fragments of (stage 0, k step 0)
+        static_for<FRAGS>([&](auto f_c) __attribute__((always_inline)) {
+            static_for<4>([&](auto d_c) __attribute__((always_inline)) { expand(I0{}, I0{}, f_c, d_c); });
+        });
+        for (int64_t st = 0; st < nst; st += 2) {
+            stage(I0{}, st);
+            stage(I1{}, st + 1);
+        }
     }
 
     // recovery terms: the code sums of the rows come with the packed operands

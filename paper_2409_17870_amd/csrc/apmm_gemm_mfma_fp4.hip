@@ -1,4 +1,4 @@
-// E2M1 (fp4) MFMA GEMM kernels for 1- and 2-bit operands: the register-direct kernel of
+// E2M1 (fp4) MFMA GEMM kernels for 1-, 2- and (activations only) 4-bit operands: the register-direct kernel of
 // apmm_gemm_mfma_direct.h in four tile shapes.
 #include "apmm_gemm_mfma_direct.h"
 
@@ -43,6 +43,8 @@ hipError_t launch_gemm_mfma_fp4_impl(const GemmArgs &g, hipStream_t stream)
     if (g.p == 1 && g.q == 2) return launch_tiles<1, 2>(g, stream);
     if (g.p == 2 && g.q == 1) return launch_tiles<2, 1>(g, stream);
     if (g.p == 2 && g.q == 2) return launch_tiles<2, 2>(g, stream);
+    if (g.p == 4 && g.q == 1) return launch_tiles<4, 1>(g, stream);
+    if (g.p == 4 && g.q == 2) return launch_tiles<4, 2>(g, stream);
     return hipErrorInvalidValue;
 }
 

@@ -45,6 +45,18 @@ __device__ __forceinline__ uint32_t expand_dword(const uint32_t (&w)[NB], int t)
     return t ? __builtin_rotateright32(y, t) : y;
 }
 
+// The same for a group of NB planes that starts at plane index `first` (uniform at run time): the
+// planes of the group are rotated by first + i, so the masks move by `first` and the final rotate
+// brings plane first + i to bit i of the nibble.  FP4 only.
+template <int NB>
+__device__ __forceinline__ uint32_t expand_group_dword(const uint32_t (&w)[NB], int t, int first)
+{
+    uint32_t y = 0;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) y |= w[i] & (0x11111111u << ((t + i + first) & 3));
+    return __builtin_rotateright32(y, (t + first) & 31);
+}
+
 // The two operand formats of the matrix unit.
 //   INT8: code u as a byte, v_mfma_i32_32x32x32_i8, int32 accumulate: acc = S.
 //   FP4 : code u as the E2M1 pattern 00uu = u/2, v_mfma_scale_f32_32x32x64_f8f6f4 with unit scales,
@@ -70,6 +82,12 @@ struct Acc<true> {
         const v8i a8 = {a[0], a[1], a[2], a[3], 0, 0, 0, 0}, b8 = {b[0], b[1], b[2], b[3], 0, 0, 0, 0};
         // formats 4 / 4 = E2M1 for both operands; scale exponent 127 = 2^0
         return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 127, 0, 127);
+    }
+    // the same with the A operand scaled by 2^(scale_a - 127) (E8M0 exponent, read from byte 0)
+    static __device__ __forceinline__ type mma_scaled(v4i a, v4i b, type c, int scale_a)
+    {
+        const v8i a8 = {a[0], a[1], a[2], a[3], 0, 0, 0, 0}, b8 = {b[0], b[1], b[2], b[3], 0, 0, 0, 0};
+        return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, scale_a, 0, 127);
     }
     static __device__ __forceinline__ uint32_t four_s(float v) { return (uint32_t)(int32_t)(v * 16.0f); }
 };

@@ -68,7 +68,8 @@ def test_argument_errors_come_before_any_launch(lib):
     assert _gemm(lib, 4, 4, 128, 1, 1, c=None) == INVALID          # no output requested
     assert _gemm(lib, 4, 4, 128, 1, 1, a=0x1004) == INVALID         # misaligned packed operand
     assert _gemm(lib, 4, 4, 128, 1, 1, algo=7) == INVALID
-    assert _gemm(lib, 64, 64, 128, 3, 1, algo=4) == UNSUPPORTED     # E2M1 holds 2-bit codes only
+    assert _gemm(lib, 64, 64, 128, 3, 1, algo=4) == UNSUPPORTED     # E2M1 path: p in {1, 2, 4}, q <= 2
+    assert _gemm(lib, 64, 64, 128, 2, 3, algo=4) == UNSUPPORTED
     assert b"" != lib.apmm_last_error()
     # 2^31 / (255 * 255) = 33025.5: K = 32768 = 64 * 512 fits, the next padded K (33280) does not
     assert _gemm(lib, 0, 4, 32768, 8, 8) == 0                       # M == 0: ok, nothing launched

@@ -55,7 +55,7 @@ def algos_for(case):
     algos = [VALU]
     if case["p"] <= 4 and case["q"] <= 4:
         algos.append(MFMA)
-    if case["p"] <= 2 and case["q"] <= 2:
+    if case["p"] in (1, 2, 4) and case["q"] <= 2:
         algos.append(FP4)
     if case["M"] <= 16 and case["q"] <= 4:
         algos.append(DECODE)
