@@ -30,9 +30,12 @@ PAPER_W1A2_4096_TOPS = 2 * 4096 ** 3 / 160e-6 / 1e12   # paper Table 1: 160 us o
 
 # HBM bytes per GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command,
 # each scaled by what the same counter reads for a plain 64 MiB copy (profiles/ holds the runs).
-# fp4 kernel: FETCH_SIZE 10435.2 KiB x 1.9989 (copy calibration) + WRITE_SIZE 65536 KiB x 1.0
-# int8 kernel: FETCH_SIZE 10398.2 KiB x 1.9989 + WRITE_SIZE 65536 KiB x 1.0
-MEASURED_TRAFFIC_BYTES = {"auto": 88468000, "fp4": 88468000, "int8": 88392000}
+# fp4 kernel: FETCH_SIZE 10530.7 KiB x 1.9989 (copy calibration) + WRITE_SIZE 65536 KiB x 1.0
+# int8 kernel: FETCH_SIZE 10478.6 KiB x 1.9989 + WRITE_SIZE 65536 KiB x 1.0
+MEASURED_TRAFFIC_BYTES = {"auto": 88664000, "fp4": 88664000, "int8": 88557000}
+
+KERNEL = {"fp4": "gemm_mfma_direct_kernel<2,1,4,4> (E2M1 operands expanded in registers, 256x256 tile)",
+          "int8": "gemm_mfma_kernel<2,1,4,4,2,2,false> (int8 operands staged in LDS, 256x256 tile)"}
 
 ALGOS = {"auto": 0, "valu": 1, "int8": 2, "decode": 3, "fp4": 4}
 
@@ -145,7 +148,7 @@ def main():
                    "M": M, "N": N, "K": K, "weight_bits": q, "activation_bits": p,
                    "step": "apmm_pack_activations + apmm_gemm, weights pre-packed", "algo": args.algo},
         "gemm_ms": gemm_ms, "pack_ms": ms_per_step - gemm_ms,
-        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel (%s operands, 256x256 tile)" % operand,
+        "roofline": {"bound": "mfma", "kernel": KERNEL[operand],
                      "achieved": achieved, "peak": PEAK[operand], "unit": "TOP/s",
                      "frac": achieved / PEAK[operand],
                      "frac_of_int8_peak": achieved / PEAK["int8"],
