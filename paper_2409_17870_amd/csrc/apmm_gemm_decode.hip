@@ -14,9 +14,10 @@
 //   wave      : k blocks 4*(w + 8*t) .. +3, t = 0, 1, ...
 //   lane l    : weight row l % 16, k block l / 16 of the wave's four; it loads the row's q planes
 //               of that block (q x 16 bytes, 256 contiguous bytes per 16 lanes) straight into registers
-// The activations (M rows, all K) are copied once per workgroup from their packed tiles into LDS
-// with every plane rotated back to the natural bit order; a weight plane is rotated back the same
-// way after loading, so that any activation plane can be XOR-ed with any weight plane.
+// The activations (M rows, all K) are copied once per workgroup from their packed tiles into LDS with
+// every plane in the common form of the XOR/popcount kernels (16 elements per word at the even bit
+// positions, apmm_layout.h); a weight plane is brought to the same form after loading, so that any
+// activation plane can be XOR-ed with any weight plane.
 #include "apmm_mfma_common.h"
 
 namespace apmm {
@@ -27,28 +28,43 @@ constexpr int kThreads = 64 * kWaves;
 constexpr int kRowsPerWg = 16;
 constexpr int kMaxLdsBytes = 128 * 1024;
 
+// Words 4*hh .. 4*hh+3 of plane i of an n-bit operand in the common form, from the slots of one row and
+// k block (`slots` points at the uint4 of slot 0; consecutive slots are kPlaneWords / 4 apart).
+__device__ __forceinline__ uint4 plane_half_words(const uint4 *slots, int n, int i, int hh)
+{
+    constexpr int kSlotVec = kPlaneWords / 4;
+    if (i < 2 * pair_groups(n)) {
+        const uint4 s = slots[(i / 2 * 2 + hh) * kSlotVec];  // S[4 hh .. 4 hh + 3] of pair group i / 2
+        const int b = i & 1;
+        return make_uint4((s.x >> b) & 0x55555555u, (s.y >> b) & 0x55555555u, (s.z >> b) & 0x55555555u,
+                          (s.w >> b) & 0x55555555u);
+    }
+    const uint4 l = slots[(n - 1) * kSlotVec];
+    // word w = 4 hh + x: k step 2 hh + x / 2, words L[2 (x % 2)], L[2 (x % 2) + 1]
+    const int k0 = 2 * hh, k1 = 2 * hh + 1;
+    return make_uint4(((l.x >> k0) & 0x11111111u) | (((l.y >> k0) & 0x11111111u) << 2),
+                      ((l.z >> k0) & 0x11111111u) | (((l.w >> k0) & 0x11111111u) << 2),
+                      ((l.x >> k1) & 0x11111111u) | (((l.y >> k1) & 0x11111111u) << 2),
+                      ((l.z >> k1) & 0x11111111u) | (((l.w >> k1) & 0x11111111u) << 2));
+}
+
 template <int MT, int Q>
 __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GemmArgs g)
 {
     extern __shared__ __align__(16) uint8_t lds_raw[];
-    uint4 *a_lds = reinterpret_cast<uint4 *>(lds_raw);  // [kb][m < MT][j < p] natural-order plane words
+    uint4 *a_lds = reinterpret_cast<uint4 *>(lds_raw);  // [kb][m < MT][j < p][hh < 2] plane words, common form
     const int p = g.p;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t n0 = (int64_t)blockIdx.x * kRowsPerWg;
 
-    // activations -> LDS: chunk (kb, m, j) = 16 bytes of plane j of row m in k block kb
-    const int chunks_per_kb = MT * p;
+    // activations -> LDS: chunk (kb, m, j, hh) = four words of plane j of row m in k block kb
+    const int chunks_per_kb = MT * p * 2;
     const int64_t total_chunks = g.nkb * chunks_per_kb;
     for (int64_t c = tid; c < total_chunks; c += kThreads) {
         const int64_t kb = c / chunks_per_kb;
-        const int rem = (int)(c % chunks_per_kb), m = rem / p, j = rem % p;
-        uint4 v = *reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, kb, g.nkb, p, j));
-        const int rot = plane_rotation(j);
-        v.x = __builtin_rotateright32(v.x, rot);
-        v.y = __builtin_rotateright32(v.y, rot);
-        v.z = __builtin_rotateright32(v.z, rot);
-        v.w = __builtin_rotateright32(v.w, rot);
-        a_lds[c] = v;
+        const int rem = (int)(c % chunks_per_kb), m = rem / (2 * p), j = (rem >> 1) % p, hh = rem & 1;
+        const uint4 *slots = reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, kb, g.nkb, p, 0));
+        a_lds[c] = plane_half_words(slots, p, j, hh);
     }
     __syncthreads();
 
@@ -61,26 +77,23 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GemmArgs g)
     for (int m = 0; m < MT; ++m) acc[m] = 0;
 
     for (int64_t kb = 4 * (int64_t)wave + sub; kb < g.nkb; kb += 4 * kWaves) {
-        uint4 w[Q];
         const uint4 *wsrc = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld, kb, g.nkb, Q, 0));
+        uint4 w[Q][2];
 #pragma unroll
-        for (int i = 0; i < Q; ++i) w[i] = wsrc[i * (kPlaneWords / 4)];
+        for (int i = 0; i < Q; ++i)
 #pragma unroll
-        for (int i = 0; i < Q; ++i) {
-            w[i].x = __builtin_rotateright32(w[i].x, plane_rotation(i));
-            w[i].y = __builtin_rotateright32(w[i].y, plane_rotation(i));
-            w[i].z = __builtin_rotateright32(w[i].z, plane_rotation(i));
-            w[i].w = __builtin_rotateright32(w[i].w, plane_rotation(i));
-        }
+            for (int hh = 0; hh < 2; ++hh) w[i][hh] = plane_half_words(wsrc, Q, i, hh);
         const uint4 *arow = a_lds + kb * chunks_per_kb;
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
             for (int j = 0; j < p; ++j) {
-                const uint4 a = arow[m * p + j];
+                const uint4 a0 = arow[(m * p + j) * 2], a1 = arow[(m * p + j) * 2 + 1];
 #pragma unroll
                 for (int i = 0; i < Q; ++i) {
-                    const uint32_t pc = __popc(a.x ^ w[i].x) + __popc(a.y ^ w[i].y) + __popc(a.z ^ w[i].z) +
-                                        __popc(a.w ^ w[i].w);
+                    const uint32_t pc = __popc(a0.x ^ w[i][0].x) + __popc(a0.y ^ w[i][0].y) +
+                                        __popc(a0.z ^ w[i][0].z) + __popc(a0.w ^ w[i][0].w) +
+                                        __popc(a1.x ^ w[i][1].x) + __popc(a1.y ^ w[i][1].y) +
+                                        __popc(a1.z ^ w[i][1].z) + __popc(a1.w ^ w[i][1].w);
                     acc[m] += pc << (i + j);
                 }
             }
@@ -115,7 +128,7 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GemmArgs g)
 
 size_t decode_lds_bytes(const GemmArgs &g, int mt)
 {
-    const size_t a_bytes = (size_t)g.nkb * mt * g.p * 16;
+    const size_t a_bytes = (size_t)g.nkb * mt * g.p * 32;
     const size_t part_bytes = (size_t)kWaves * mt * kRowsPerWg * 4;
     return a_bytes > part_bytes ? a_bytes : part_bytes;
 }
@@ -155,67 +168,62 @@ hipError_t launch_mt(const GemmArgs &g, hipStream_t stream)
 // ---------------------------------------------------------------------------------------------
 // Small-M kernel on the matrix unit (3 <= M <= 16, p, q <= 2).  With more than a couple of tokens
 // the XOR/popcount form needs 2 p q M lane-operations per weight word and becomes VALU bound; the
-// E2M1 MFMA needs one expansion of the weight word (q + 1 operations per 8 codes) whatever M is.
+// E2M1 MFMA needs one expansion of the weight words (1.25 - 1.5 operations per 8 codes) whatever M is.
 // Same split of the work (16 output channels per workgroup, 8 waves over K, lane = weight row l % 16
-// and k block l / 16 of four), same algebra as the large-M MFMA kernels:
+// and k block l / 16 of four), same algebra as the large-M MFMA kernel:
 //   v_mfma_scale_f32_16x16x128_f8f6f4: A = 16 weight rows x 128 k, B = 128 k x 16 tokens, codes as E2M1;
-//   MFMA g of an iteration multiplies word group g of the four k blocks held by the four lane groups;
-//   the packed activations of all K are copied once per workgroup into LDS as [k block][word group][token]
-//   plane words and expanded where they are used; C = 16 acc - 2 cw PA[m] - 2 ca PW[n] + K ca cw with the packed row sums.
+//   MFMA ks of an iteration multiplies k step ks of the four k blocks held by the four lane groups;
+//   the packed activations of all K are copied once per workgroup into LDS as they are, [k block][token][slot],
+//   and expanded where they are used; C = acc - 2 cw PA[m] - 2 ca PW[n] + K ca cw with the packed row sums
+//   (the operand scales make acc = 4 S).
 // ---------------------------------------------------------------------------------------------
-typedef float v4f __attribute__((ext_vector_type(4)));
-
 template <int P, int Q>
 __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GemmArgs g)
 {
+    static_assert(P <= 2 && Q <= 2, "one plane group per operand");
     extern __shared__ __align__(16) uint8_t lds_raw[];
-    uint32_t *a_lds = reinterpret_cast<uint32_t *>(lds_raw);  // [kb][gq][token < 16][plane]: raw plane words
+    uint4 *a_lds = reinterpret_cast<uint4 *>(lds_raw);  // [kb][token < 16][slot < P]: packed words as they are
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t n0 = (int64_t)blockIdx.x * kRowsPerWg;
+    constexpr int kSlotVec = kPlaneWords / 4;
 
-    // activations -> LDS as they are packed (expanded at use).  One 16-byte load brings the four word
-    // groups of (k block, plane, token); 16 tokens are 256 contiguous bytes.
+    // activations -> LDS; the 16 tokens of a slot are 256 contiguous bytes
     const int64_t total_vecs = g.nkb * P * 16;
     for (int64_t c = tid; c < total_vecs; c += kThreads) {
         const int m = (int)(c & 15);
-        const int i = (int)((c >> 4) % P);
+        const int s = (int)((c >> 4) % P);
         const int64_t kb = (c >> 4) / P;
-        const uint4 v = *reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, kb, g.nkb, P, i));
-        uint32_t *dst = a_lds + ((kb * kWordsPerRow) * 16 + m) * P + i;
-        dst[0 * 16 * P] = v.x;
-        dst[1 * 16 * P] = v.y;
-        dst[2 * 16 * P] = v.z;
-        dst[3 * 16 * P] = v.w;
+        a_lds[(kb * 16 + m) * P + s] = *reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, kb, g.nkb, P, s));
     }
     __syncthreads();
 
     const int r16 = lane & 15, kq = lane >> 4;
     const int64_t rows_b = round_up(g.N, kRowBlock);
     const int64_t n_ld = n0 + r16 < rows_b ? n0 + r16 : rows_b - 1;
-    v4f acc = {0.f, 0.f, 0.f, 0.f};
+    mfma::v4f acc = {0.f, 0.f, 0.f, 0.f};
     // nkb is a multiple of 4 (K is padded to 512): whole groups of four k blocks
     for (int64_t kb4 = wave; kb4 * 4 < g.nkb; kb4 += kWaves) {
         const int64_t kb = kb4 * 4 + kq;
-        uint4 wq[Q];
+        uint4 wq[2], aq[2];
         const uint4 *wsrc = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld, kb, g.nkb, Q, 0));
 #pragma unroll
-        for (int i = 0; i < Q; ++i) wq[i] = wsrc[i * (kPlaneWords / 4)];
-        const uint32_t *arow = a_lds + ((kb * kWordsPerRow) * 16 + r16) * P;
-        mfma::static_for<4>([&](auto g_c) __attribute__((always_inline)) {
-            constexpr int gq = decltype(g_c)::value;
-            uint32_t w[Q];
+        for (int s = 0; s < Q; ++s) wq[s] = wsrc[s * kSlotVec];
 #pragma unroll
-            for (int i = 0; i < Q; ++i) w[i] = gq == 0 ? wq[i].x : gq == 1 ? wq[i].y : gq == 2 ? wq[i].z : wq[i].w;
-            const mfma::v8i a8 = {(int)mfma::expand_dword<Q, true>(w, 0), (int)mfma::expand_dword<Q, true>(w, 1),
-                                  (int)mfma::expand_dword<Q, true>(w, 2), (int)mfma::expand_dword<Q, true>(w, 3),
-                                  0, 0, 0, 0};
-            uint32_t aw[P];
-#pragma unroll
-            for (int i = 0; i < P; ++i) aw[i] = arow[gq * 16 * P + i];
-            const mfma::v8i b8 = {(int)mfma::expand_dword<P, true>(aw, 0), (int)mfma::expand_dword<P, true>(aw, 1),
-                                  (int)mfma::expand_dword<P, true>(aw, 2), (int)mfma::expand_dword<P, true>(aw, 3),
-                                  0, 0, 0, 0};
-            acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, acc, 4, 4, 0, 127, 0, 127);
+        for (int s = 0; s < P; ++s) aq[s] = a_lds[(kb * 16 + r16) * P + s];
+        mfma::static_for<4>([&](auto ks_c) __attribute__((always_inline)) {
+            constexpr int ks = decltype(ks_c)::value;
+            mfma::v8i a8 = {0, 0, 0, 0, 0, 0, 0, 0}, b8 = {0, 0, 0, 0, 0, 0, 0, 0};
+            mfma::static_for<4>([&](auto d_c) __attribute__((always_inline)) {
+                constexpr int d = decltype(d_c)::value;
+                if constexpr (Q == 1) a8[d] = (int)mfma::fp4_single_dword<ks, d>(wq[0]);
+                else a8[d] = (int)mfma::fp4_pair_dword<ks, d>(wq[0], wq[1]);
+                if constexpr (P == 1) b8[d] = (int)mfma::fp4_single_dword<ks, d>(aq[0]);
+                else b8[d] = (int)mfma::fp4_pair_dword<ks, d>(aq[0], aq[1]);
+            });
+            // E8M0 exponents: 2^2 per operand turns (ua/2)(uw/2) into 4 ua uw
+            acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                a8, b8, acc, 4, 4, 0, 129 + (Q == 1 ? mfma::fp4_single_exponent(ks) : 0), 0,
+                129 + (P == 1 ? mfma::fp4_single_exponent(ks) : 0));
         });
     }
 
@@ -235,7 +243,7 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GemmArgs g)
         const int64_t n = n0 + 4 * (l >> 4) + v;
         if (m < g.M && n < g.N) {
             constexpr uint32_t ca = (1u << P) - 1, cw = (1u << Q) - 1;
-            const uint32_t c = (uint32_t)(int32_t)(s * 16.0f) - 2u * cw * (uint32_t)g.a_sum[m] -
+            const uint32_t c = (uint32_t)(int32_t)s - 2u * cw * (uint32_t)g.a_sum[m] -
                                2u * ca * (uint32_t)g.w_sum[n] + (uint32_t)g.K * ca * cw;
             store_output(g, m, n, (int32_t)c, load_scale(g.a_scale, m), load_scale(g.w_scale, n));
         }
@@ -244,7 +252,7 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GemmArgs g)
 
 size_t decode_mfma_lds_bytes(const GemmArgs &g)
 {
-    const size_t a_bytes = (size_t)g.nkb * kWordsPerRow * 16 * 4 * g.p;
+    const size_t a_bytes = (size_t)g.nkb * 16 * 16 * g.p;
     const size_t part_bytes = (size_t)kWaves * 4 * 64 * 4;
     return a_bytes > part_bytes ? a_bytes : part_bytes;
 }
@@ -252,7 +260,7 @@ size_t decode_mfma_lds_bytes(const GemmArgs &g)
 bool decode_mfma_supported(const GemmArgs &g)
 {
     return g.M >= 3 && g.M <= 16 && g.p <= 2 && g.q <= 2 && decode_mfma_lds_bytes(g) <= (size_t)kMaxLdsBytes &&
-           g.nkb * kKBlock <= (1 << 18);
+           4 * g.nkb * kKBlock * 9 < (1 << 24);
 }
 
 template <int P, int Q>

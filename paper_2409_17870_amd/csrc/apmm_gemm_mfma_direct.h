@@ -1,48 +1,68 @@
-// Design A without LDS: every wave expands its own MFMA operands in registers.
+// Design A: bit planes recombined into matrix-unit operands in registers, E2M1 (fp4) MFMA.
 //
-// Same algebra as apmm_gemm_mfma_impl.h (codes u on the matrix unit, C = 4S - 2cw PA - 2ca PW +
-// K ca cw), different data movement.  On gfx950 a wave that owns its SIMD alone has about 17 issue
-// cycles per 32-cycle MFMA for everything else; a ds_read_b128 costs ~20 and a ds_write_b128 ~40 of
-// them, a VALU instruction 4.  Staging the expanded tiles through LDS (one expansion per workgroup,
-// then 0.5 reads + 0.25 writes per MFMA) therefore costs more issue time than letting each of the
-// two waves that share a fragment expand it again from the packed planes, which are 4-8x smaller
-// than the operand bytes and come straight from L1/L2 into registers (paper Sec. 4.1: the planes are
-// stored so that one 16-byte load per plane brings a row's 128 k).  There is no LDS traffic, no
-// barrier in the k loop and nothing but C reaches global memory (paper Sec. 4.2).
+// Paper Sec. 3.2 recovers C = sum_i sum_j 2^(i+j) * D_ij from p*q one-bit products.  The matrix unit of
+// gfx950 multiplies small numbers, not single bits, so the shift-and-add is moved in front of the
+// multiplier.  With the code u = sum_i b_i 2^i of an element, whose value is 2u - (2^n - 1) (paper Eq. 1),
+//   C = sum_k (2 ua_k - ca)(2 uw_k - cw),   ca = 2^p - 1, cw = 2^q - 1
+//     = 4 S - 2 cw PA[m] - 2 ca PW[n] + K ca cw,     S = sum_k ua_k uw_k,
+//   PA[m], PW[n] = sums of the codes of a row over the padded K (they come with the packed operands;
+//   padded k positions hold the code ca resp. cw in both operands, which is why the true K appears),
+// which equals sum_ij 2^(i+j) D_ij.  The codes are cut into plane groups of two bits (and one of a single
+// bit when the width is odd): u = sum_h 4^h u_h.  A 2-bit code is the E2M1 pattern 00uu = u/2, exactly, and
+// S = sum_{h,h'} 4^(h+h') sum_k ua_h uw_h': K is swept once per pair of groups, every sweep adds into the
+// SAME fp32 accumulator, and the factor 4^(h+h') (times 16 for the two halvings and the leading 4) is the
+// MFMA's power-of-two operand scale: the paper's shift-and-add, done by the matrix unit.  The accumulator
+// starts at -2 cw PA[m] - 2 ca PW[n] + K ca cw, so that it ends at C: every term is an integer and every
+// partial sum stays below 2^24 (checked on the host), hence exact in any order.  Nothing but C reaches
+// global memory (paper Sec. 4.2).
 //
-// E2M1 (fp4) operands hold 2-bit codes.  q <= 2; p = 1, 2 or 4: 4-bit activation codes are split
-// into two 2-bit plane groups, u = 4 u_hi + u_lo, and K is swept once per group with the MFMA's
-// power-of-two operand scale set to 4 resp. 1, so that the one accumulator receives
-// S = 4 sum u_hi uw + sum u_lo uw (the plane-group form of the paper's shift-and-add, done by the
-// matrix unit's scale input).  Workgroup = 2 x 2 waves, wave tile (32*WM) x (32*WN).
-// Stage = two packed k blocks = four MFMA k steps of 64.  Lane l of a wave owns, for each of its
-// WM + WN row blocks, row l % 32 and k block l / 32 of the stage: per plane one 16-byte load = the
-// four 32-k word groups gq = 0..3 of that row.  MFMA k step ks multiplies word group gq = ks of both
-// lane halves; the lane's 32 codes of that group, expanded to nibbles, are exactly its 16 operand
-// bytes.  The expansion of k step ks+1 (and, at the end of a stage, of step 0 of the next stage) is
-// interleaved with the MFMAs of step ks, two output dwords per MFMA.  The raw words of the next
-// stage are loaded at the start of the current one (double buffered in registers).
+// Data movement: no LDS.  On gfx950 a wave that owns its SIMD alone has about 17 issue cycles per
+// 32-cycle MFMA for everything else; a ds_read_b128 costs ~20 and a ds_write_b128 ~40 of them, a VALU
+// instruction 4.  Staging expanded tiles through LDS therefore costs more issue time than letting each of
+// the two waves that share a fragment expand it again from the packed words, which are 2-4x smaller than
+// the operand bytes and come straight from L1/L2 into registers (paper Sec. 4.1: the planes are stored so
+// that one 16-byte load brings a row's share of a k block).  There is no barrier in the k loop.
+//
+// Workgroup = 2 x 2 waves, wave tile (32*WM) x (32*WN).  Stage = two packed k blocks = four MFMA k steps
+// of 64.  Lane l of a wave owns, for each of its row blocks, row l % 32 and k block l / 32 of the stage:
+// per group one or two 16-byte loads.  The expansion of k step ks+1 (and, at the end of a stage, of step 0
+// of the next stage) is interleaved with the MFMAs of step ks; the raw words of the next stage are loaded
+// at the start of the current one (double buffered in registers).
 #pragma once
 #include "apmm_mfma_common.h"
 
 namespace apmm {
 namespace mfma {
 
-template <int P, int Q, int WM, int WN>
+// SPLIT = 1: the wave tile is computed in one go and stored at the end.
+// SPLIT = 2: the wave tile is computed as two halves of WM / 2 row blocks, one after the other (each a full
+// sweep of K), and the int32 stores of the first half are interleaved with the MFMAs of the second half's
+// first kStoreStages stages, one element every other MFMA, so that half of the C traffic (which otherwise
+// keeps the matrix unit idle for 6 - 7 us at 4096^2 outputs) runs under the k loop.  The price is less
+// reuse per expanded fragment.  Used for interior tiles with int32 output only and K >= kStoreStages stages.
+constexpr int kStoreEvery = 2;
+
+template <int P, int Q, int WM, int WN, int SPLIT>
 __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int tiles_n, int tiles_total)
 {
-    static_assert((P == 1 || P == 2 || P == 4) && Q <= 2, "E2M1 patterns are linear in the code only up to 3");
-    constexpr bool FP4 = true;
-    constexpr int GROUPS = P > 2 ? 2 : 1;    // 2-bit plane groups of the activations
-    constexpr int PG = P / GROUPS;           // planes per group
+    static_assert(P >= 1 && P <= 4 && Q >= 1 && Q <= 4, "instantiated for codes of up to four bits");
+    static_assert(SPLIT == 1 || SPLIT == 2, "one or two phases");
+    constexpr int WMP = WM / SPLIT;          // row blocks per phase
     constexpr int BM = 64 * WM, BN = 64 * WN;
-    constexpr int KS = 4;                    // MFMA k steps per stage (= word groups of a k block)
-    constexpr int PER_KS = WM * WN;          // MFMAs per k step
-    constexpr int FRAGS = WM + WN;           // operand fragments per k step
+    constexpr int KS = 4;                    // MFMA k steps per stage
+    constexpr int PER_KS = WMP * WN;         // MFMAs per k step
+    constexpr int FRAGS = WMP + WN;          // operand fragments per k step
     constexpr int TASKS = 4 * FRAGS;         // expansion dwords per k step
     static_assert(TASKS % PER_KS == 0, "expansion tasks must spread evenly over the MFMAs of a k step");
     constexpr int TPM = TASKS / PER_KS;      // tasks per MFMA
-    typedef typename Acc<FP4>::type acc_t;
+    constexpr int PHASE_ELEMS = WMP * WN * 16;                  // outputs per lane and phase
+    constexpr int STAGE_ELEMS = KS * PER_KS / kStoreEvery;      // outputs stored under one stage
+    constexpr int STORE_STAGES = PHASE_ELEMS / STAGE_ELEMS;     // stages that carry stores
+    static_assert(STORE_STAGES % 2 == 0 && STORE_STAGES * STAGE_ELEMS == PHASE_ELEMS, "store schedule");
+    constexpr uint32_t ca = (1u << P) - 1, cw = (1u << Q) - 1;
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using NoStore = std::integral_constant<int, -1>;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave >> 1, wave_n = wave & 1;
@@ -51,7 +71,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
     const int tm = lid / tiles_n, tn = lid % tiles_n;
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
-    // per row block: address of (row, plane 0, words 0..3) in this lane's k block of stage 0
+    // per row block: address of (row, slot 0) in this lane's k block of stage 0
     const int64_t rows_a = round_up(g.M, kRowBlock), rows_b = round_up(g.N, kRowBlock);
     const uint4 *pa_src[WM], *pb_src[WN];
 #pragma unroll
@@ -66,119 +86,253 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
         if (row >= rows_b) row = rows_b - 1;
         pb_src[bj] = reinterpret_cast<const uint4 *>(g.w + tile_row_word(row, kh, g.nkb, Q, 0));
     }
-    constexpr int kPlaneVec = kPlaneWords / 4;             // uint4 between planes of a tile
-    constexpr int kStageVecA = 2 * P * kPlaneVec, kStageVecB = 2 * Q * kPlaneVec;  // uint4 per stage (2 k blocks)
+    constexpr int kSlotVec = kPlaneWords / 4;                                    // uint4 between slots of a tile
+    constexpr int kStageVecA = 2 * P * kSlotVec, kStageVecB = 2 * Q * kSlotVec;  // uint4 per stage (2 k blocks)
 
-    uint4 ra[2][WM][PG], rb[2][WN][Q];  // raw plane words, double buffered by stage parity
-    int grp = 0;                        // plane group being swept
-    auto load_stage = [&](auto buf_c, int64_t st) __attribute__((always_inline)) {
-        constexpr int buf = decltype(buf_c)::value;
-#pragma unroll
-        for (int bi = 0; bi < WM; ++bi)
-#pragma unroll
-            for (int i = 0; i < PG; ++i) ra[buf][bi][i] = pa_src[bi][st * kStageVecA + (grp * PG + i) * kPlaneVec];
-#pragma unroll
-        for (int bj = 0; bj < WN; ++bj)
-#pragma unroll
-            for (int i = 0; i < Q; ++i) rb[buf][bj][i] = pb_src[bj][st * kStageVecB + i * kPlaneVec];
-    };
+    // Accumulator layout of the 32x32 MFMA: lane l, register v holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+    const int64_t m_lane = m0 + wave_m * WM * 32 + kh * 4, n_lane = n0 + wave_n * WN * 32 + r32;
 
-    acc_t acc[WM][WN];
+    v16f acc[SPLIT][WMP][WN];
+    // The accumulators start at the recovery terms rt[m] + ct[n], rt = -2 cw PA, ct = K ca cw - 2 ca PW: a
+    // rank-2 matrix, written by one fp32 MFMA with k = 2 per block: A = (rt[m], 1), B = (1, ct[n]).
+    // Lane l supplies row resp. column l % 32 of k index l / 32.  All values are integers below 2^24.
+    float b_init[WN];
 #pragma unroll
-    for (int bi = 0; bi < WM; ++bi)
+    for (int bj = 0; bj < WN; ++bj) {
+        int64_t n = n_lane + bj * 32;
+        if (n >= rows_b) n = rows_b - 1;
+        const float ct = (float)(int32_t)((uint32_t)g.K * ca * cw - 2u * ca * (uint32_t)g.w_sum[n]);
+        b_init[bj] = kh == 0 ? 1.0f : ct;
+    }
+    auto init_phase = [&](auto ph_c) __attribute__((always_inline)) {
+        constexpr int ph = decltype(ph_c)::value;
+        v16f zero;
 #pragma unroll
-        for (int bj = 0; bj < WN; ++bj)
+        for (int v = 0; v < 16; ++v) zero[v] = 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[bi][bj][v] = 0;
-
-    v4i af[2][WM], bf[2][WN];
-    // dword d of fragment f (f < WM: A block f, else B block f - WM) of k step ks, from buffer buf
-    auto expand = [&](auto buf_c, auto ks_c, auto f_c, auto d_c) __attribute__((always_inline)) {
-        constexpr int buf = decltype(buf_c)::value, ks = decltype(ks_c)::value, f = decltype(f_c)::value,
-                      d = decltype(d_c)::value;
-        auto word = [](const uint4 &v) { return ks == 0 ? v.x : ks == 1 ? v.y : ks == 2 ? v.z : v.w; };
-        if constexpr (f < WM) {
-            uint32_t w[PG];
+        for (int bi = 0; bi < WMP; ++bi) {
+            int64_t m = m0 + (wave_m * WM + ph * WMP + bi) * 32 + r32;
+            if (m >= rows_a) m = rows_a - 1;
+            const float rt = -(float)(2u * cw * (uint32_t)g.a_sum[m]);
+            const float a_init = kh == 0 ? rt : 1.0f;
 #pragma unroll
-            for (int i = 0; i < PG; ++i) w[i] = word(ra[buf][f][i]);
-            af[ks & 1][f][d] = GROUPS == 1 ? (int)expand_dword<PG, FP4>(w, d) : (int)expand_group_dword<PG>(w, d, grp * PG);
-        } else {
-            uint32_t w[Q];
-#pragma unroll
-            for (int i = 0; i < Q; ++i) w[i] = word(rb[buf][f - WM][i]);
-            bf[ks & 1][f - WM][d] = (int)expand_dword<Q, FP4>(w, d);
+            for (int bj = 0; bj < WN; ++bj)
+                acc[ph][bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_init, b_init[bj], zero, 0, 0, 0);
         }
     };
-    using I0 = std::integral_constant<int, 0>;
-    using I1 = std::integral_constant<int, 1>;
-    const int64_t nst = g.nkb / 2;  // the packed K is a multiple of 512: an even number of whole stages
-    int scale_a = 127;
 
-    // one stage with its raw words in buffer `buf`; loads stage st+1 (clamped) into the other buffer
-    auto stage = [&](auto buf_c, int64_t st) __attribute__((always_inline)) {
-        constexpr int buf = decltype(buf_c)::value;
-        using Other = std::integral_constant<int, buf ^ 1>;
-        load_stage(Other{}, st + 1 < nst ? st + 1 : st);  // the surplus load of the last stage is discarded
-        __builtin_amdgcn_sched_barrier(0);
-        static_for<KS * PER_KS>([&](auto i_c) __attribute__((always_inline)) {
-            constexpr int i = decltype(i_c)::value;
-            constexpr int ks = i / PER_KS, j = i % PER_KS, bi = j / WN, bj = j % WN;
-            acc[bi][bj] = Acc<FP4>::mma_scaled(af[ks & 1][bi], bf[ks & 1][bj], acc[bi][bj], scale_a);
-            // this MFMA's share of the next k step's operands (after the last step: step 0 of stage st+1)
-            static_for<TPM>([&](auto t_c) __attribute__((always_inline)) {
-                constexpr int task = j * TPM + decltype(t_c)::value;
-                using F = std::integral_constant<int, task / 4>;
-                using D = std::integral_constant<int, task % 4>;
-                if constexpr (ks + 1 < KS)
-                    expand(buf_c, std::integral_constant<int, ks + 1>{}, F{}, D{});
-                else
-                    expand(Other{}, I0{}, F{}, D{});
-            });
-            __builtin_amdgcn_sched_barrier(0);
-        });
+    uint4 ra[2][WMP][2], rb[2][WN][2];  // raw words of a group (a single group uses [0] only), by stage parity
+    v4i af[2][WMP], bf[2][WN];          // expanded fragments, by k step parity
+    const int64_t nst = g.nkb / 2;      // the packed K is a multiple of 512: an even number of whole stages
+
+    // int32 store of element e of phase ph under the k loop of the next phase: elements run along the row
+    // blocks, then the 16 registers (rows), then the column blocks, so that the row pointer moves once per WN stores
+    const int64_t row_bytes = g.N * 4;
+    char *st_ptr = nullptr;
+    auto store_elem = [&](auto ph_c, auto e_c) __attribute__((always_inline)) {
+        constexpr int ph = decltype(ph_c)::value, e = decltype(e_c)::value;
+        constexpr int bi = e / (16 * WN), v = (e / WN) % 16, bj = e % WN;
+        // rows of consecutive registers: +1, +1, +1, +5 (the next group of four rows, or the next row block)
+        if constexpr (bj == 0 && e > 0) st_ptr += (v % 4 == 0 ? 5 : 1) * row_bytes;
+        *reinterpret_cast<int32_t *>(st_ptr + bj * 128) = (int32_t)acc[ph][bi][bj][v];
     };
-    for (grp = 0; grp < GROUPS; ++grp) {
-        scale_a = 127 + grp * PG;  // E8M0 exponent: the codes of this group weigh 2^(grp * PG)
+
+    // One sweep of K for phase ph, the activation group at slot slot_a and the weight group at slot slot_b
+    // (AS / BS: the group is a single one).  exp_a + exp_b - 254 = 4 + the bit positions of the two groups.
+    // STORES: the first STORE_STAGES stages also store phase ph - 1.
+    auto sweep = [&](auto ph_c, auto stores_c, auto as_c, auto bs_c, int slot_a, int slot_b, int exp_a, int exp_b)
+                     __attribute__((always_inline)) {
+        constexpr int ph = decltype(ph_c)::value;
+        constexpr bool STORES = decltype(stores_c)::value;
+        constexpr bool AS = decltype(as_c)::value, BS = decltype(bs_c)::value;
+        auto load_stage = [&](auto buf_c, int64_t st) __attribute__((always_inline)) {
+            constexpr int buf = decltype(buf_c)::value;
+#pragma unroll
+            for (int bi = 0; bi < WMP; ++bi) {
+                const uint4 *src = pa_src[ph * WMP + bi];
+                ra[buf][bi][0] = src[st * kStageVecA + slot_a * kSlotVec];
+                if constexpr (!AS) ra[buf][bi][1] = src[st * kStageVecA + (slot_a + 1) * kSlotVec];
+            }
+#pragma unroll
+            for (int bj = 0; bj < WN; ++bj) {
+                rb[buf][bj][0] = pb_src[bj][st * kStageVecB + slot_b * kSlotVec];
+                if constexpr (!BS) rb[buf][bj][1] = pb_src[bj][st * kStageVecB + (slot_b + 1) * kSlotVec];
+            }
+        };
+        // dword d of fragment f (f < WMP: A block f, else B block f - WMP) of k step ks, from buffer buf
+        auto expand = [&](auto buf_c, auto ks_c, auto f_c, auto d_c) __attribute__((always_inline)) {
+            constexpr int buf = decltype(buf_c)::value, ks = decltype(ks_c)::value, f = decltype(f_c)::value,
+                          d = decltype(d_c)::value;
+            if constexpr (f < WMP) {
+                if constexpr (AS) af[ks & 1][f][d] = (int)fp4_single_dword<ks, d>(ra[buf][f][0]);
+                else af[ks & 1][f][d] = (int)fp4_pair_dword<ks, d>(ra[buf][f][0], ra[buf][f][1]);
+            } else {
+                if constexpr (BS) bf[ks & 1][f - WMP][d] = (int)fp4_single_dword<ks, d>(rb[buf][f - WMP][0]);
+                else bf[ks & 1][f - WMP][d] = (int)fp4_pair_dword<ks, d>(rb[buf][f - WMP][0], rb[buf][f - WMP][1]);
+            }
+        };
+        // one stage with its raw words in buffer `buf`; loads stage st+1 (clamped) into the other buffer;
+        // chunk >= 0: stores elements chunk * STAGE_ELEMS ... of the previous phase on the way
+        auto stage = [&](auto buf_c, int64_t st, auto chunk_c) __attribute__((always_inline)) {
+            constexpr int buf = decltype(buf_c)::value, chunk = decltype(chunk_c)::value;
+            using Other = std::integral_constant<int, buf ^ 1>;
+            load_stage(Other{}, st + 1 < nst ? st + 1 : st);  // the surplus load of the last stage is discarded
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<KS * PER_KS>([&](auto i_c) __attribute__((always_inline)) {
+                constexpr int i = decltype(i_c)::value;
+                constexpr int ks = i / PER_KS, j = i % PER_KS, bi = j / WN, bj = j % WN;
+                const v4i a = af[ks & 1][bi], b = bf[ks & 1][bj];
+                const v8i a8 = {a[0], a[1], a[2], a[3], 0, 0, 0, 0}, b8 = {b[0], b[1], b[2], b[3], 0, 0, 0, 0};
+                // formats 4 / 4 = E2M1 for both operands; the scales are E8M0 exponents (127 = 2^0)
+                acc[ph][bi][bj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                    a8, b8, acc[ph][bi][bj], 4, 4, 0, exp_a + (AS ? fp4_single_exponent(ks) : 0), 0,
+                    exp_b + (BS ? fp4_single_exponent(ks) : 0));
+                // this MFMA's share of the next k step's operands (after the last step: step 0 of stage st+1)
+                static_for<TPM>([&](auto t_c) __attribute__((always_inline)) {
+                    constexpr int task = j * TPM + decltype(t_c)::value;
+                    using F = std::integral_constant<int, task / 4>;
+                    using D = std::integral_constant<int, task % 4>;
+                    if constexpr (ks + 1 < KS)
+                        expand(buf_c, std::integral_constant<int, ks + 1>{}, F{}, D{});
+                    else
+                        expand(Other{}, I0{}, F{}, D{});
+                });
+                if constexpr (chunk >= 0 && i % kStoreEvery == 0)
+                    store_elem(std::integral_constant<int, (ph > 0 ? ph - 1 : 0)>{},
+                               std::integral_constant<int, chunk * STAGE_ELEMS + i / kStoreEvery>{});
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        };
         load_stage(I0{}, 0);
         // fragments of (stage 0, k step 0)
         static_for<FRAGS>([&](auto f_c) __attribute__((always_inline)) {
             static_for<4>([&](auto d_c) __attribute__((always_inline)) { expand(I0{}, I0{}, f_c, d_c); });
         });
-        for (int64_t st = 0; st < nst; st += 2) {
-            stage(I0{}, st);
-            stage(I1{}, st + 1);
+        int64_t st = 0;
+        if constexpr (STORES) {
+            static_for<STORE_STAGES / 2>([&](auto h_c) __attribute__((always_inline)) {
+                constexpr int h = decltype(h_c)::value;
+                stage(I0{}, 2 * h, std::integral_constant<int, 2 * h>{});
+                stage(I1{}, 2 * h + 1, std::integral_constant<int, 2 * h + 1>{});
+            });
+            st = STORE_STAGES;
         }
-    }
+        for (; st < nst; st += 2) {
+            stage(I0{}, st, NoStore{});
+            stage(I1{}, st + 1, NoStore{});
+        }
+    };
 
-    // recovery terms: the code sums of the rows come with the packed operands
-    const int rsub = kh * 4;
-    const int64_t m_lane = m0 + wave_m * WM * 32 + rsub, n_lane = n0 + wave_n * WN * 32 + r32;
-    const bool interior = (m0 + BM <= g.M) && (n0 + BN <= g.N);
-    uint32_t pw[WN];
+    using T = std::true_type;
+    using F = std::false_type;
+    static_for<SPLIT>([&](auto ph_c) __attribute__((always_inline)) {
+        constexpr int ph = decltype(ph_c)::value;
+        init_phase(ph_c);
+        if constexpr (ph > 0)  // row pointer of element 0 of the previous phase
+            st_ptr = reinterpret_cast<char *>(g.c_i32 + (m_lane + (ph - 1) * WMP * 32) * g.N + n_lane);
+        // the first sweep of a later phase carries the stores of the phase before it
+        using First = std::integral_constant<bool, (ph > 0)>;
+        // pair x pair, pair x single, single x pair, single x single
+        if constexpr (pair_groups(P) > 0) {
+            if constexpr (pair_groups(Q) > 0) {
+                sweep(ph_c, First{}, F{}, F{}, 0, 0, 129, 129);
+                for (int hb = 1; hb < pair_groups(Q); ++hb) sweep(ph_c, F{}, F{}, F{}, 0, 2 * hb, 129, 129 + 2 * hb);
+                if constexpr (has_single_group(Q)) sweep(ph_c, F{}, F{}, T{}, 0, Q - 1, 129, 129 + Q - 1);
+            } else {
+                sweep(ph_c, First{}, F{}, T{}, 0, Q - 1, 129, 129 + Q - 1);
+            }
+            for (int ha = 1; ha < pair_groups(P); ++ha) {
+                for (int hb = 0; hb < pair_groups(Q); ++hb)
+                    sweep(ph_c, F{}, F{}, F{}, 2 * ha, 2 * hb, 129 + 2 * ha, 129 + 2 * hb);
+                if constexpr (has_single_group(Q)) sweep(ph_c, F{}, F{}, T{}, 2 * ha, Q - 1, 129 + 2 * ha, 129 + Q - 1);
+            }
+            if constexpr (has_single_group(P)) {
+                for (int hb = 0; hb < pair_groups(Q); ++hb)
+                    sweep(ph_c, F{}, T{}, F{}, P - 1, 2 * hb, 129 + P - 1, 129 + 2 * hb);
+                if constexpr (has_single_group(Q)) sweep(ph_c, F{}, T{}, T{}, P - 1, Q - 1, 129 + P - 1, 129 + Q - 1);
+            }
+        } else {  // P == 1
+            if constexpr (pair_groups(Q) > 0) {
+                sweep(ph_c, First{}, T{}, F{}, 0, 0, 129, 129);
+                for (int hb = 1; hb < pair_groups(Q); ++hb) sweep(ph_c, F{}, T{}, F{}, 0, 2 * hb, 129, 129 + 2 * hb);
+                if constexpr (has_single_group(Q)) sweep(ph_c, F{}, T{}, T{}, 0, Q - 1, 129, 129 + Q - 1);
+            } else {
+                sweep(ph_c, First{}, T{}, T{}, 0, 0, 129, 129);
+            }
+        }
+    });
+
+    // Store of the last phase.  The output mode and the border test are uniform over the workgroup, so one
+    // of six straight-line store sequences is chosen instead of testing per element.
+    constexpr int LAST = SPLIT - 1;
+    const int64_t m_last = m_lane + LAST * WMP * 32;
+    float sw[WN];
 #pragma unroll
     for (int bj = 0; bj < WN; ++bj) {
         const int64_t n = n_lane + bj * 32;
-        pw[bj] = (uint32_t)g.w_sum[n < rows_b ? n : rows_b - 1];
+        sw[bj] = (g.w_scale && n < g.N) ? half_bits_to_float(g.w_scale[n]) : 1.0f;
     }
-    store_wave_tile<P, Q, WM, WN, FP4>(
-        g, acc, m_lane, n_lane, interior,
-        [&](int bi, int v4) {
-            int64_t m = m_lane + bi * 32 + 8 * v4;  // four consecutive rows, 16-byte aligned
-            if (m + 4 > rows_a) m = rows_a - 4;     // past the operand: any valid address, never stored
-            return *reinterpret_cast<const int4 *>(g.a_sum + m);
-        },
-        pw);
+    auto emit = [&](auto guard_c, auto i32_c, auto f16_c) __attribute__((always_inline)) {
+        constexpr bool GUARD = decltype(guard_c)::value, I32 = decltype(i32_c)::value, F16 = decltype(f16_c)::value;
+        int32_t *ci = I32 ? g.c_i32 + m_last * g.N + n_lane : nullptr;
+        uint16_t *ch = F16 ? g.c_f16 + m_last * g.N + n_lane : nullptr;
+#pragma unroll
+        for (int bi = 0; bi < WMP; ++bi) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t row = (int64_t)(bi * 32 + 8 * (v / 4) + (v % 4));  // relative to m_last
+                if (GUARD && m_last + row >= g.M) continue;
+                float sa = 1.0f;
+                if constexpr (F16) sa = g.a_scale ? half_bits_to_float(g.a_scale[m_last + row]) : 1.0f;
+#pragma unroll
+                for (int bj = 0; bj < WN; ++bj) {
+                    if (GUARD && n_lane + bj * 32 >= g.N) continue;
+                    const float c = acc[LAST][bi][bj][v];  // = C, an integer
+                    if constexpr (I32) ci[row * g.N + bj * 32] = (int32_t)c;
+                    if constexpr (F16) ch[row * g.N + bj * 32] = float_to_half_bits(c * sa * sw[bj]);
+                }
+            }
+        }
+    };
+    if constexpr (SPLIT > 1) {
+        emit(F{}, T{}, F{});  // interior tiles, int32 output only (checked by the launcher)
+    } else {
+        const bool interior = (m0 + BM <= g.M) && (n0 + BN <= g.N);
+        const bool i32 = g.c_i32 != nullptr, f16 = g.c_f16 != nullptr;
+        if (interior) {
+            if (i32 && !f16) emit(F{}, T{}, F{});
+            else if (!i32 && f16) emit(F{}, F{}, T{});
+            else emit(F{}, T{}, T{});
+        } else {
+            if (i32 && !f16) emit(T{}, T{}, F{});
+            else if (!i32 && f16) emit(T{}, F{}, T{});
+            else emit(T{}, T{}, T{});
+        }
+    }
 }
 
+// The split kernel stores int32 only and needs whole tiles and at least STORE_STAGES stages of K.  It pays
+// where the hidden half of the store (about 3 us for 256 x 256 tiles on all CUs) outweighs the slower
+// k loop (about 2.7 ns per MFMA, measured): up to 24 stages over all sweeps (K <= 3072 with one sweep).
 template <int P, int Q, int WM, int WN>
+inline bool direct_split_usable(const GemmArgs &g)
+{
+    constexpr int store_stages = (WM / 2) * WN * 16 / (4 * (WM / 2) * WN / kStoreEvery);
+    constexpr int sweeps = ((P + 1) / 2) * ((Q + 1) / 2);
+    const int64_t nst = g.nkb / 2;
+    return g.c_i32 && !g.c_f16 && g.M % (64 * WM) == 0 && g.N % (64 * WN) == 0 && nst >= store_stages &&
+           sweeps * nst <= 24;
+}
+
+template <int P, int Q, int WM, int WN, int SPLIT = 1>
 hipError_t launch_direct_variant(const GemmArgs &g, hipStream_t stream)
 {
     constexpr int BM = 64 * WM, BN = 64 * WN;
     const int64_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int64_t tiles = tiles_m * tiles_n;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((gemm_mfma_direct_kernel<P, Q, WM, WN>), dim3((unsigned)tiles), dim3(256), 0, stream, g,
-                       (int)tiles_n, (int)tiles);
+    hipLaunchKernelGGL((gemm_mfma_direct_kernel<P, Q, WM, WN, SPLIT>), dim3((unsigned)tiles), dim3(256), 0, stream,
+                       g, (int)tiles_n, (int)tiles);
     return hipGetLastError();
 }
 

@@ -1,6 +1,6 @@
-// int8 MFMA GEMM kernels for 4-bit activations (all weight widths); see apmm_gemm_mfma_impl.h.
-#include "apmm_gemm_mfma_impl.h"
+// E2M1 MFMA GEMM kernels for 4-bit activations and 1..4-bit weights.
+#include "apmm_gemm_mfma_tiles.h"
 
 namespace apmm {
-hipError_t launch_gemm_mfma_p4(const GemmArgs &g, hipStream_t stream) { return mfma::launch_int8_p<4>(g, stream); }
+hipError_t launch_gemm_mfma_fp4_p4(const GemmArgs &g, hipStream_t stream) { return mfma::launch_fp4_p<4>(g, stream); }
 }  // namespace apmm

@@ -1,9 +1,10 @@
-// E2M1 (fp4) MFMA GEMM kernels for 1-, 2- and (activations only) 4-bit operands: the register-direct kernel of
-// apmm_gemm_mfma_direct.h in four tile shapes.
+// Tile choice and width dispatch of the E2M1 MFMA GEMM (apmm_gemm_mfma_direct.h).  One translation
+// unit per activation width instantiates the kernels, so that they compile in parallel.
+#pragma once
 #include "apmm_gemm_mfma_direct.h"
 
 namespace apmm {
-namespace {
+namespace mfma {
 
 // Tile choice: estimate each candidate as (rounds of 256 tiles) x (tile area) x (measured relative
 // cost per MFMA of that tile shape) and take the cheapest.  APMM_MFMA_TILE=0..3 forces one (debugging).
@@ -15,6 +16,7 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream)
     int best = 0;
     double best_t = 0;
     static const char *forced = std::getenv("APMM_MFMA_TILE");
+    static const char *no_split = std::getenv("APMM_MFMA_SPLIT");
     if (forced && forced[0] >= '0' && forced[0] <= '3') {
         best = forced[0] - '0';
     } else {
@@ -28,24 +30,28 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream)
         }
     }
     switch (best) {
-    case 0: return mfma::launch_direct_variant<P, Q, 4, 4>(g, stream);
-    case 1: return mfma::launch_direct_variant<P, Q, 4, 2>(g, stream);
-    case 2: return mfma::launch_direct_variant<P, Q, 2, 4>(g, stream);
-    default: return mfma::launch_direct_variant<P, Q, 2, 2>(g, stream);
+    case 0:
+        // APMM_MFMA_SPLIT=0 forces the one-phase kernel (debugging)
+        if (direct_split_usable<P, Q, 4, 4>(g) && !(no_split && no_split[0] == '0'))
+            return launch_direct_variant<P, Q, 4, 4, 2>(g, stream);
+        return launch_direct_variant<P, Q, 4, 4>(g, stream);
+    case 1: return launch_direct_variant<P, Q, 4, 2>(g, stream);
+    case 2: return launch_direct_variant<P, Q, 2, 4>(g, stream);
+    default: return launch_direct_variant<P, Q, 2, 2>(g, stream);
     }
 }
 
-}  // namespace
-
-hipError_t launch_gemm_mfma_fp4_impl(const GemmArgs &g, hipStream_t stream)
+template <int P>
+hipError_t launch_fp4_p(const GemmArgs &g, hipStream_t stream)
 {
-    if (g.p == 1 && g.q == 1) return launch_tiles<1, 1>(g, stream);
-    if (g.p == 1 && g.q == 2) return launch_tiles<1, 2>(g, stream);
-    if (g.p == 2 && g.q == 1) return launch_tiles<2, 1>(g, stream);
-    if (g.p == 2 && g.q == 2) return launch_tiles<2, 2>(g, stream);
-    if (g.p == 4 && g.q == 1) return launch_tiles<4, 1>(g, stream);
-    if (g.p == 4 && g.q == 2) return launch_tiles<4, 2>(g, stream);
+    switch (g.q) {
+    case 1: return launch_tiles<P, 1>(g, stream);
+    case 2: return launch_tiles<P, 2>(g, stream);
+    case 3: return launch_tiles<P, 3>(g, stream);
+    case 4: return launch_tiles<P, 4>(g, stream);
+    }
     return hipErrorInvalidValue;
 }
 
+}  // namespace mfma
 }  // namespace apmm

@@ -9,7 +9,10 @@
 //
 // This kernel is the general one: any p, q in 1..8, any M, N, K.  One thread per output
 // element, 16 x 16 outputs per workgroup; operands come straight from the packed tiles
-// (they are small and stay in L1/L2).
+// (they are small and stay in L1/L2).  It is the fallback for codes the matrix-unit kernels do
+// not cover, written for clarity: every plane is brought to the same form, 16 elements per word
+// at the even bit positions (apmm_layout.h), and then any activation plane can be XOR-ed with any
+// weight plane.
 #include "apmm_epilogue.h"
 #include "apmm_kernels.h"
 
@@ -17,6 +20,19 @@ namespace apmm {
 namespace {
 
 constexpr int kTile = 16;
+
+// Plane i of the 16 elements (ks = w / 2, tp = w % 2, all tt, jh, c) of one row and k block, at bits
+// 8c + 4jh + 2tt.  `tile_row` points at word 0 of (row, slot 0).
+__device__ __forceinline__ uint32_t plane_half_word(const uint32_t *tile_row, int n, int i, int w)
+{
+    if (i < 2 * pair_groups(n)) {
+        const uint32_t s = tile_row[(i / 2 * 2 + (w >> 2)) * kPlaneWords + (w & 3)];  // S[w] of pair group i / 2
+        return (s >> (i & 1)) & 0x55555555u;
+    }
+    const uint32_t *l = tile_row + (n - 1) * kPlaneWords + 2 * (w & 1);  // L[2 tp], L[2 tp + 1]
+    const int ks = w >> 1;
+    return ((l[0] >> ks) & 0x11111111u) | (((l[1] >> ks) & 0x11111111u) << 2);
+}
 
 __global__ __launch_bounds__(kTile * kTile) void gemm_valu_kernel(GemmArgs g)
 {
@@ -27,20 +43,17 @@ __global__ __launch_bounds__(kTile * kTile) void gemm_valu_kernel(GemmArgs g)
 
     uint32_t weighted = 0;  // sum_ij 2^(i+j) popcount, modulo 2^32 (the true C fits 32 bits)
     for (int64_t kb = 0; kb < g.nkb; ++kb) {
-        const uint4 *arow = reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, kb, g.nkb, p, 0));
-        const uint4 *wrow = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n, kb, g.nkb, q, 0));
-        for (int i = 0; i < q; ++i) {
-            const uint4 wv = wrow[i * (kPlaneWords / 4)];
+        const uint32_t *arow = g.a + tile_row_word(m, kb, g.nkb, p, 0);
+        const uint32_t *wrow = g.w + tile_row_word(n, kb, g.nkb, q, 0);
+        for (int w = 0; w < 8; ++w) {
+            uint32_t wp[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) wp[i] = i < q ? plane_half_word(wrow, q, i, w) : 0u;
             for (int j = 0; j < p; ++j) {
-                // plane words are stored rotated by their plane index: bring the activation plane
-                // to the weight plane's rotation before comparing
-                const uint4 av = arow[j * (kPlaneWords / 4)];
-                const int r = (plane_rotation(j) - plane_rotation(i)) & 31;
-                const uint32_t pc = __popc(__builtin_rotateright32(av.x, r) ^ wv.x) +
-                                    __popc(__builtin_rotateright32(av.y, r) ^ wv.y) +
-                                    __popc(__builtin_rotateright32(av.z, r) ^ wv.z) +
-                                    __popc(__builtin_rotateright32(av.w, r) ^ wv.w);
-                weighted += pc << (i + j);
+                const uint32_t ap = plane_half_word(arow, p, j, w);
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (i < q) weighted += (uint32_t)__popc(ap ^ wp[i]) << (i + j);
             }
         }
     }

@@ -1,36 +1,44 @@
 // Packed bit-plane layout shared by every kernel of the library (paper Sec. 4.1).
 //
-// A rows x K operand of n-bit codes is stored as n one-bit planes in 32-bit words,
-// concatenated tile by tile:
+// A rows x K operand of n-bit codes is stored with n bits per element in 32-bit words, concatenated
+// tile by tile:
 //
-//   word(rb, kb, i, r, g)   rb = row / 32       row block (rows padded to a multiple of 32)
+//   word(rb, kb, s, r, g)   rb = row / 32       row block (rows padded to a multiple of 32)
 //                           kb = k / 128        k block   (K padded to a multiple of 512: nkb is a multiple of 4)
-//                           i  = plane (bit of the code), 0 .. n-1
+//                           s  = plane slot, 0 .. n-1 (16 bytes per row and slot)
 //                           r  = row % 32
-//                           g  = (k % 128) / 32 word inside the k block
-//   index = (((rb * nkb + kb) * n + i) * 32 + r) * 4 + g
+//                           g  = word inside the slot, 0 .. 3
+//   index = (((rb * nkb + kb) * n + s) * 32 + r) * 4 + g
 //
-// so one (rb, kb) tile is 512*n contiguous bytes, planes concatenated, and inside a plane the
-// 32 rows are 16 bytes each: when the lanes of a wave take one row each, every 16-byte load
-// instruction reads one contiguous 512-byte run per row block.
+// so one (rb, kb) tile is 512*n contiguous bytes and inside a slot the 32 rows are 16 bytes each:
+// when the lanes of a wave take one row each, every 16-byte load instruction reads one contiguous
+// 512-byte run per row block.
 //
-// Inside a word, element e = k % 32 of plane i sits at bit (8*(e % 4) + (e / 4) + i) mod 32:
-// the "natural" word, whose byte c holds elements c, c+4, c+8, ..., rotated left by i.
-// Masking plane i with 0x01010101 << ((t + i) % 8) keeps the bits of the four elements
-// 4t .. 4t+3; OR-ing the masked planes and rotating right by t leaves, in each of the four
-// bytes, bit i = plane bit i, i.e. the code u of the element as a byte.  That is the whole
-// expansion to int8 MFMA operands: one AND(-OR) per plane and one rotate per four elements.
-// XOR/popcount kernels rotate a plane word by the difference of the plane indices to compare
-// planes of different index.
+// Which bit of which word holds plane i of element k is chosen for the consumers, the matrix-unit
+// kernels first.  The planes of a code are taken in groups: bits (0,1), (2,3), ... form PAIR groups,
+// and when n is odd the top bit is a SINGLE group.  With the element's position inside its k block
+// written as
+//       k % 128 = 32*ks + 8*t + 4*jh + c,   ks, t in 0..3, jh in 0..1, c in 0..3,   t = 2*tp + tt,
+//   pair group h (code bits 2h, 2h+1) fills slots 2h and 2h+1, seen as eight words S[0..7]
+//       (slot 2h + w/4, word w % 4):  bit b of the group sits in S[2*ks + tp] at bit 8*c + 4*jh + 2*tt + b;
+//   a single group (code bit n-1) fills slot n-1, four words L[0..3]:
+//       the bit sits in L[t] at bit 8*c + 4*jh + ks.
+// Reading them (apmm_mfma_common.h has the code):
+//   * E2M1 (fp4) MFMA operand of k step ks: its four dwords are (S[2ks + tp] >> 2tt) & 0x33333333, i.e.
+//     every nibble is 00uu with the 2-bit code of the group: 1.5 operations per dword.  For a single
+//     group L[t] & (0x11111111 << ks): the bit stands at another place of the nibble in every k step,
+//     which the MFMA's power-of-two operand scale undoes (1.25 operations per dword).
+//   * int8 MFMA operand: (S[w] >> (4jh + 2tt)) & 0x03030303 leaves four 2-bit codes, one per byte.
+//   * XOR/popcount: (S[w] >> b) & 0x55555555 is plane 2h+b of 16 elements; two single-group words give
+//     the same 16 elements with two shift-and-mask steps, so any two planes can be compared.
+// Both operands of a GEMM use the same element -> (ks, t, jh, c) map, which is all a contraction needs.
 //
-// Behind the planes of all tiles follows one int32 per (padded) row: the sum of the row's codes over
-// the padded K, i.e. sum_i 2^i popcount(plane i).  The MFMA kernels multiply codes u instead of values
-// 2u - (2^n - 1) and need these sums to recover C.
+// Behind the tiles follows one int32 per (padded) row: the sum of the row's codes over the padded K.
+// The MFMA kernels multiply codes u instead of values 2u - (2^n - 1) and need these sums to recover C.
 //
-// Padding: elements with k >= K have every plane bit set in BOTH operands.  Their
-// XOR is zero, and each contributes exactly (2^p - 1)(2^q - 1) to an integer dot
-// product, which the kernels subtract again.  Rows >= `rows` are all-zero words and
-// are never stored to C.
+// Padding: elements with k >= K have every plane bit set in BOTH operands.  Their XOR is zero, and each
+// contributes exactly (2^p - 1)(2^q - 1) to an integer dot product, which the kernels subtract again.
+// Rows >= `rows` are all-zero words and are never stored to C.
 #pragma once
 #include <stdint.h>
 
@@ -38,23 +46,24 @@ namespace apmm {
 
 constexpr int kRowBlock = 32;    // rows per packed tile
 constexpr int kKBlock = 128;     // k elements per packed tile
-constexpr int kKPad = 512;       // K is padded to a multiple of this (four k blocks = two stages of the direct MFMA kernel)
-constexpr int kWordsPerRow = 4;  // 32-bit words per (row, plane) inside a tile
-constexpr int kPlaneWords = kRowBlock * kWordsPerRow;  // words between consecutive planes of a tile
-
-// left rotation applied to the natural word of plane i
-inline __host__ __device__ int plane_rotation(int i) { return i; }
+constexpr int kKPad = 512;       // K is padded to a multiple of this (four k blocks = two stages of the MFMA kernel)
+constexpr int kWordsPerRow = 4;  // 32-bit words per (row, slot) inside a tile
+constexpr int kPlaneWords = kRowBlock * kWordsPerRow;  // words between consecutive slots of a tile
 
 inline __host__ __device__ int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
-// index of word g=0 of (row, plane i) in k block kb
-inline __host__ __device__ int64_t tile_row_word(int64_t row, int64_t kb, int64_t nkb, int n, int i)
+// number of pair groups of an n-bit code, and whether a single group follows them
+inline __host__ __device__ constexpr int pair_groups(int n) { return n / 2; }
+inline __host__ __device__ constexpr bool has_single_group(int n) { return (n & 1) != 0; }
+
+// index of word g=0 of (row, slot s) in k block kb
+inline __host__ __device__ int64_t tile_row_word(int64_t row, int64_t kb, int64_t nkb, int n, int s)
 {
     int64_t rb = row / kRowBlock, r = row % kRowBlock;
-    return (((rb * nkb + kb) * n + i) * kRowBlock + r) * kWordsPerRow;
+    return (((rb * nkb + kb) * n + s) * kRowBlock + r) * kWordsPerRow;
 }
 
-// index of the first row-sum word: the planes of rows_p x nkb*128 elements come first
+// index of the first row-sum word: the tiles of rows_p x nkb*128 elements come first
 inline __host__ __device__ int64_t row_sum_word(int64_t rows_p, int64_t nkb, int n)
 {
     return rows_p * nkb * n * (kKBlock / 32);
@@ -62,7 +71,7 @@ inline __host__ __device__ int64_t row_sum_word(int64_t rows_p, int64_t nkb, int
 
 struct GemmArgs {
     int64_t M, N, K;
-    int64_t nkb;          // roundup(K,128)/128
+    int64_t nkb;          // roundup(K,512)/128
     int p, q;
     const uint32_t *a;    // packed activations
     const uint32_t *w;    // packed weights
