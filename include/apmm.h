@@ -45,14 +45,15 @@ typedef enum {
 typedef enum {
     APMM_ALGO_AUTO = 0,
     APMM_ALGO_VALU_POPCOUNT = 1, /* plane pairs by XOR + popcount on the vector ALU, D_ij = K - 2*popc */
-    APMM_ALGO_MFMA_INT8 = 2,     /* planes recombined to int8 codes in LDS, int8 MFMA, int32 accumulate (p, q <= 4) */
+    APMM_ALGO_MFMA_INT8 = 2,     /* reserved: the int8 MFMA kernel of earlier builds; this build answers APMM_ERR_UNSUPPORTED */
     APMM_ALGO_DECODE = 3,        /* small-M (M <= 16) weight-streaming kernel */
-    APMM_ALGO_MFMA_FP4 = 4       /* planes recombined to E2M1 codes in registers, f8f6f4 MFMA, exact fp32 accumulate (p in {1,2,4}, q <= 2) */
+    APMM_ALGO_MFMA_FP4 = 4       /* plane groups recombined to E2M1 codes in registers, f8f6f4 MFMA, exact fp32 accumulate
+                                    (p, q <= 4 and 4 * roundup(K,512) * (2^p-1)(2^q-1) < 2^24) */
 } apmm_algo;
 
 /* Bytes of the packed form of a rows x K operand of `bits`-bit codes (paper Sec. 4.1:
- * `bits` one-bit planes in 32-bit words, concatenated).  Rows are padded to a multiple
- * of 32 and K to a multiple of 512.  Returns 0 for invalid arguments. */
+ * `bits` one-bit planes in 32-bit words, concatenated, plus one int32 per row).  Rows are padded
+ * to a multiple of 32 and K to a multiple of 512.  Returns 0 for invalid arguments. */
 size_t apmm_packed_bytes(int64_t rows, int64_t K, int bits);
 
 /* Bytes of scratch apmm_gemm needs for this problem (may be 0). */

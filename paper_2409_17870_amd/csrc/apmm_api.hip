@@ -121,11 +121,11 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
         e = apmm::launch_gemm_valu(g, s);
         break;
     case APMM_ALGO_MFMA_INT8:
-        if (!apmm::gemm_mfma_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: int8 MFMA kernel covers p, q in 1..4");
+        if (!apmm::gemm_mfma_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: no int8 MFMA kernel in this build");
         e = apmm::launch_gemm_mfma(g, s);
         break;
     case APMM_ALGO_MFMA_FP4:
-        if (!apmm::gemm_mfma_fp4_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: FP4 MFMA kernel covers p in {1, 2, 4}, q in 1..2 and K up to 2^18");
+        if (!apmm::gemm_mfma_fp4_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: FP4 MFMA kernel covers p, q in 1..4 while 4 K (2^p - 1)(2^q - 1) < 2^24");
         e = apmm::launch_gemm_mfma_fp4(g, s);
         break;
     case APMM_ALGO_DECODE:
