@@ -48,6 +48,24 @@ __device__ __forceinline__ uint4 plane_half_words(const uint4 *slots, int n, int
                       ((l.z >> k1) & 0x11111111u) | (((l.w >> k1) & 0x11111111u) << 2));
 }
 
+// The same from slots already in registers (weights of a Q-bit operand).
+template <int Q>
+__device__ __forceinline__ uint4 plane_half_words_reg(const uint4 (&slot)[Q], int i, int hh)
+{
+    if (i < 2 * pair_groups(Q)) {
+        const uint4 s = slot[i / 2 * 2 + hh];
+        const int b = i & 1;
+        return make_uint4((s.x >> b) & 0x55555555u, (s.y >> b) & 0x55555555u, (s.z >> b) & 0x55555555u,
+                          (s.w >> b) & 0x55555555u);
+    }
+    const uint4 l = slot[Q - 1];
+    const int k0 = 2 * hh, k1 = 2 * hh + 1;
+    return make_uint4(((l.x >> k0) & 0x11111111u) | (((l.y >> k0) & 0x11111111u) << 2),
+                      ((l.z >> k0) & 0x11111111u) | (((l.w >> k0) & 0x11111111u) << 2),
+                      ((l.x >> k1) & 0x11111111u) | (((l.y >> k1) & 0x11111111u) << 2),
+                      ((l.z >> k1) & 0x11111111u) | (((l.w >> k1) & 0x11111111u) << 2));
+}
+
 template <int MT, int Q>
 __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GemmArgs g)
 {
@@ -57,32 +75,62 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GemmArgs g)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t n0 = (int64_t)blockIdx.x * kRowsPerWg;
 
+    const int row = lane & 15, sub = lane >> 4;
+    int64_t n = n0 + row;
+    const int64_t n_ld = n < round_up(g.N, kRowBlock) ? n : round_up(g.N, kRowBlock) - 1;
+    constexpr int kSlotVec = kPlaneWords / 4;
+
+    // what the final store needs is requested first: a dependent round trip to memory at the end of
+    // a kernel this short would be a quarter of its duration
+    const int out_m = tid / kRowsPerWg;
+    const int64_t out_n = n0 + tid % kRowsPerWg;
+    const bool out_thread = tid < MT * kRowsPerWg && out_m < g.M && out_n < g.N;
+    float out_sa = 1.0f, out_sw = 1.0f;
+    if (out_thread && g.c_f16) {
+        out_sa = load_scale(g.a_scale, out_m);
+        out_sw = load_scale(g.w_scale, out_n);
+    }
+
+    // the weights of the first k block are requested before anything else: their latency is the
+    // longest thing in this kernel and overlaps with the copy of the activations
+    int64_t kb = 4 * (int64_t)wave + sub;
+    uint4 wnext[Q];
+    if (kb < g.nkb) {
+        const uint4 *wsrc = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld, kb, g.nkb, Q, 0));
+#pragma unroll
+        for (int s = 0; s < Q; ++s) wnext[s] = wsrc[s * kSlotVec];
+    }
+
     // activations -> LDS: chunk (kb, m, j, hh) = four words of plane j of row m in k block kb
     const int chunks_per_kb = MT * p * 2;
     const int64_t total_chunks = g.nkb * chunks_per_kb;
     for (int64_t c = tid; c < total_chunks; c += kThreads) {
-        const int64_t kb = c / chunks_per_kb;
+        const int64_t ckb = c / chunks_per_kb;
         const int rem = (int)(c % chunks_per_kb), m = rem / (2 * p), j = (rem >> 1) % p, hh = rem & 1;
-        const uint4 *slots = reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, kb, g.nkb, p, 0));
+        const uint4 *slots = reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, ckb, g.nkb, p, 0));
         a_lds[c] = plane_half_words(slots, p, j, hh);
     }
     __syncthreads();
-
-    const int row = lane & 15, sub = lane >> 4;
-    int64_t n = n0 + row;
-    const int64_t n_ld = n < round_up(g.N, kRowBlock) ? n : round_up(g.N, kRowBlock) - 1;
 
     uint32_t acc[MT];  // sum_ij 2^(i+j) popcount, modulo 2^32
 #pragma unroll
     for (int m = 0; m < MT; ++m) acc[m] = 0;
 
-    for (int64_t kb = 4 * (int64_t)wave + sub; kb < g.nkb; kb += 4 * kWaves) {
-        const uint4 *wsrc = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld, kb, g.nkb, Q, 0));
+    for (; kb < g.nkb; kb += 4 * kWaves) {
+        uint4 wraw[Q];
+#pragma unroll
+        for (int s = 0; s < Q; ++s) wraw[s] = wnext[s];
+        if (kb + 4 * kWaves < g.nkb) {  // next block of this lane
+            const uint4 *wsrc =
+                reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld, kb + 4 * kWaves, g.nkb, Q, 0));
+#pragma unroll
+            for (int s = 0; s < Q; ++s) wnext[s] = wsrc[s * kSlotVec];
+        }
         uint4 w[Q][2];
 #pragma unroll
         for (int i = 0; i < Q; ++i)
 #pragma unroll
-            for (int hh = 0; hh < 2; ++hh) w[i][hh] = plane_half_words(wsrc, Q, i, hh);
+            for (int hh = 0; hh < 2; ++hh) w[i][hh] = plane_half_words_reg<Q>(wraw, i, hh);
         const uint4 *arow = a_lds + kb * chunks_per_kb;
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
@@ -113,16 +161,12 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GemmArgs g)
         for (int m = 0; m < MT; ++m) part[(wave * MT + m) * kRowsPerWg + lane] = acc[m];
     }
     __syncthreads();
-    if (tid < MT * kRowsPerWg) {
-        const int m = tid / kRowsPerWg, r = tid % kRowsPerWg;
+    if (out_thread) {
         uint32_t s = 0;
 #pragma unroll
-        for (int w8 = 0; w8 < kWaves; ++w8) s += part[(w8 * MT + m) * kRowsPerWg + r];
-        n = n0 + r;
-        if (m < g.M && n < g.N) {
-            const uint32_t full = (uint32_t)g.K * (uint32_t)((1 << p) - 1) * (uint32_t)((1 << Q) - 1);
-            store_output(g, m, n, (int32_t)(full - 2u * s), load_scale(g.a_scale, m), load_scale(g.w_scale, n));
-        }
+        for (int w8 = 0; w8 < kWaves; ++w8) s += part[(w8 * MT + out_m) * kRowsPerWg + tid % kRowsPerWg];
+        const uint32_t full = (uint32_t)g.K * (uint32_t)((1 << p) - 1) * (uint32_t)((1 << Q) - 1);
+        store_output(g, out_m, out_n, (int32_t)(full - 2u * s), out_sa, out_sw);
     }
 }
 
@@ -187,27 +231,59 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GemmArgs g)
     const int64_t n0 = (int64_t)blockIdx.x * kRowsPerWg;
     constexpr int kSlotVec = kPlaneWords / 4;
 
+    const int r16 = lane & 15, kq = lane >> 4;
+    const int64_t rows_b = round_up(g.N, kRowBlock);
+    const int64_t n_ld = n0 + r16 < rows_b ? n0 + r16 : rows_b - 1;
+
+    // what the final store needs is requested first (see gemm_decode_kernel).
+    // 16x16 accumulator layout: lane l, register v holds row 4*(l/16) + v (weight row), column l%16 (token)
+    const int out_m = tid & 15;
+    const int64_t out_n = n0 + 4 * ((tid & 63) >> 4) + (tid >> 6);
+    const bool out_thread = tid < 256 && out_m < g.M && out_n < g.N;
+    float out_sa = 1.0f, out_sw = 1.0f;
+    uint32_t out_terms = 0;  // - 2 cw PA[m] - 2 ca PW[n] + K ca cw
+    if (out_thread) {
+        constexpr uint32_t ca = (1u << P) - 1, cw = (1u << Q) - 1;
+        out_terms = (uint32_t)g.K * ca * cw - 2u * cw * (uint32_t)g.a_sum[out_m] - 2u * ca * (uint32_t)g.w_sum[out_n];
+        if (g.c_f16) {
+            out_sa = load_scale(g.a_scale, out_m);
+            out_sw = load_scale(g.w_scale, out_n);
+        }
+    }
+
+    // the weights of the first k block are requested before anything else: their latency is the
+    // longest thing in this kernel and overlaps with the copy of the activations
+    int64_t kb4 = wave;
+    uint4 wnext[2];
+    if (kb4 * 4 < g.nkb) {
+        const uint4 *wsrc = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld, kb4 * 4 + kq, g.nkb, Q, 0));
+#pragma unroll
+        for (int s = 0; s < Q; ++s) wnext[s] = wsrc[s * kSlotVec];
+    }
+
     // activations -> LDS; the 16 tokens of a slot are 256 contiguous bytes
     const int64_t total_vecs = g.nkb * P * 16;
     for (int64_t c = tid; c < total_vecs; c += kThreads) {
         const int m = (int)(c & 15);
         const int s = (int)((c >> 4) % P);
-        const int64_t kb = (c >> 4) / P;
-        a_lds[(kb * 16 + m) * P + s] = *reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, kb, g.nkb, P, s));
+        const int64_t ckb = (c >> 4) / P;
+        a_lds[(ckb * 16 + m) * P + s] = *reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, ckb, g.nkb, P, s));
     }
     __syncthreads();
 
-    const int r16 = lane & 15, kq = lane >> 4;
-    const int64_t rows_b = round_up(g.N, kRowBlock);
-    const int64_t n_ld = n0 + r16 < rows_b ? n0 + r16 : rows_b - 1;
     mfma::v4f acc = {0.f, 0.f, 0.f, 0.f};
     // nkb is a multiple of 4 (K is padded to 512): whole groups of four k blocks
-    for (int64_t kb4 = wave; kb4 * 4 < g.nkb; kb4 += kWaves) {
+    for (; kb4 * 4 < g.nkb; kb4 += kWaves) {
         const int64_t kb = kb4 * 4 + kq;
         uint4 wq[2], aq[2];
-        const uint4 *wsrc = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld, kb, g.nkb, Q, 0));
 #pragma unroll
-        for (int s = 0; s < Q; ++s) wq[s] = wsrc[s * kSlotVec];
+        for (int s = 0; s < Q; ++s) wq[s] = wnext[s];
+        if ((kb4 + kWaves) * 4 < g.nkb) {  // next block of this lane
+            const uint4 *wsrc =
+                reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld, kb + 4 * kWaves, g.nkb, Q, 0));
+#pragma unroll
+            for (int s = 0; s < Q; ++s) wnext[s] = wsrc[s * kSlotVec];
+        }
 #pragma unroll
         for (int s = 0; s < P; ++s) aq[s] = a_lds[(kb * 16 + r16) * P + s];
         mfma::static_for<4>([&](auto ks_c) __attribute__((always_inline)) {
@@ -233,20 +309,12 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GemmArgs g)
 #pragma unroll
     for (int v = 0; v < 4; ++v) part[(wave * 4 + v) * 64 + lane] = acc[v];
     __syncthreads();
-    if (tid < 256) {
+    if (out_thread) {
         const int l = tid & 63, v = tid >> 6;
         float s = 0.f;
 #pragma unroll
         for (int w8 = 0; w8 < kWaves; ++w8) s += part[(w8 * 4 + v) * 64 + l];
-        // 16x16 accumulator layout: lane l, register v holds row 4*(l/16) + v (weight row), column l%16 (token)
-        const int m = l & 15;
-        const int64_t n = n0 + 4 * (l >> 4) + v;
-        if (m < g.M && n < g.N) {
-            constexpr uint32_t ca = (1u << P) - 1, cw = (1u << Q) - 1;
-            const uint32_t c = (uint32_t)(int32_t)s - 2u * cw * (uint32_t)g.a_sum[m] -
-                               2u * ca * (uint32_t)g.w_sum[n] + (uint32_t)g.K * ca * cw;
-            store_output(g, m, n, (int32_t)c, load_scale(g.a_scale, m), load_scale(g.w_scale, n));
-        }
+        store_output(g, out_m, out_n, (int32_t)((uint32_t)(int32_t)s + out_terms), out_sa, out_sw);
     }
 }
 
