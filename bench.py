@@ -24,20 +24,18 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 # MI355X published dense matrix peaks (TFLOP/s or TOP/s) and HBM bandwidth
-PEAK = {"fp4": 10100.0, "int8": 5000.0}
+PEAK = {"fp4": 10100.0, "int8": 5000.0}   # int8: the peak the problem statement's target is expressed against
 HBM_PEAK_GBS = 8000.0
 PAPER_W1A2_4096_TOPS = 2 * 4096 ** 3 / 160e-6 / 1e12   # paper Table 1: 160 us on an RTX 3090
 
 # HBM bytes per GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command,
 # each scaled by what the same counter reads for a plain 64 MiB copy (profiles/ holds the runs).
-# fp4 kernel: FETCH_SIZE 10530.7 KiB x 1.9989 (copy calibration) + WRITE_SIZE 65536 KiB x 1.0
-# int8 kernel: FETCH_SIZE 10478.6 KiB x 1.9989 + WRITE_SIZE 65536 KiB x 1.0
-MEASURED_TRAFFIC_BYTES = {"auto": 88664000, "fp4": 88664000, "int8": 88557000}
+# FETCH_SIZE 16146.4 KiB x 1.9989 (copy calibration) + WRITE_SIZE 65536 KiB x 1.0
+MEASURED_TRAFFIC_BYTES = {"auto": 100158000, "fp4": 100158000}
 
-KERNEL = {"fp4": "gemm_mfma_direct_kernel<2,1,4,4> (E2M1 operands expanded in registers, 256x256 tile)",
-          "int8": "gemm_mfma_kernel<2,1,4,4,2,2,false> (int8 operands staged in LDS, 256x256 tile)"}
+KERNEL = "gemm_mfma_direct_kernel<2,1,4,4,2> (E2M1 operands expanded in registers, 256x256 tile, two phases)"
 
-ALGOS = {"auto": 0, "valu": 1, "int8": 2, "decode": 3, "fp4": 4}
+ALGOS = {"auto": 0, "valu": 1, "fp4": 4}
 
 
 def parse_args():
@@ -99,7 +97,7 @@ def main():
     a_packed = torch.empty(binding.apmm_packed_bytes(M, K, p), dtype=torch.uint8, device=dev)
     c = torch.empty((M, N), dtype=torch.int32, device=dev)
     algo = ALGOS[args.algo]
-    operand = "int8" if args.algo == "int8" else "fp4"
+    operand = "fp4"
 
     def step(events=None):
         binding.apmm_pack_activations(a_codes, p, out=a_packed)
@@ -138,8 +136,7 @@ def main():
     value = ops / (ms_per_step * 1e-3) / 1e12
     achieved = ops / (gemm_ms * 1e-3) / 1e12
 
-    dtype = ("fp4 (E2M1) MFMA operands recombined from 1-bit planes, exact fp32 accumulate" if operand == "fp4"
-             else "int8 MFMA operands recombined from 1-bit planes, int32 accumulate")
+    dtype = "fp4 (E2M1) MFMA operands recombined from 1-bit planes, exact fp32 accumulate"
     out = {
         "metric": "effective TOPS (2*M*N*K/s), W1A2 bipolar-INT GEMM 4096^3 (activation pack + GEMM)",
         "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -153,7 +150,7 @@ def main():
                    "M": M, "N": N, "K": K, "weight_bits": q, "activation_bits": p,
                    "step": "apmm_pack_activations + apmm_gemm, weights pre-packed", "algo": args.algo},
         "gemm_ms": gemm_ms, "pack_ms": ms_per_step - gemm_ms,
-        "roofline": {"bound": "mfma", "kernel": KERNEL[operand],
+        "roofline": {"bound": "mfma", "kernel": KERNEL if args.algo != "valu" else "gemm_valu_kernel",
                      "achieved": achieved, "peak": PEAK[operand], "unit": "TOP/s",
                      "frac": achieved / PEAK[operand],
                      "frac_of_int8_peak": achieved / PEAK["int8"],

@@ -313,7 +313,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
 
 // The split kernel stores int32 only and needs whole tiles and at least STORE_STAGES stages of K.  It pays
 // where the hidden half of the store (about 3 us for 256 x 256 tiles on all CUs) outweighs the slower
-// k loop (about 2.7 ns per MFMA, measured): up to 24 stages over all sweeps (K <= 3072 with one sweep).
+// k loop (about 2.7 ns per MFMA, measured): up to 16 stages over all sweeps (K <= 4096 with one sweep).
 template <int P, int Q, int WM, int WN>
 inline bool direct_split_usable(const GemmArgs &g)
 {
@@ -321,7 +321,7 @@ inline bool direct_split_usable(const GemmArgs &g)
     constexpr int sweeps = ((P + 1) / 2) * ((Q + 1) / 2);
     const int64_t nst = g.nkb / 2;
     return g.c_i32 && !g.c_f16 && g.M % (64 * WM) == 0 && g.N % (64 * WN) == 0 && nst >= store_stages &&
-           sweeps * nst <= 24;
+           sweeps * nst <= 16;
 }
 
 template <int P, int Q, int WM, int WN, int SPLIT = 1>
