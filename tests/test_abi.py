@@ -68,14 +68,15 @@ def test_argument_errors_come_before_any_launch(lib):
     assert _gemm(lib, 4, 4, 128, 1, 1, c=None) == INVALID          # no output requested
     assert _gemm(lib, 4, 4, 128, 1, 1, a=0x1004) == INVALID         # misaligned packed operand
     assert _gemm(lib, 4, 4, 128, 1, 1, algo=7) == INVALID
-    assert _gemm(lib, 64, 64, 128, 3, 1, algo=4) == UNSUPPORTED     # E2M1 path: p in {1, 2, 4}, q <= 2
-    assert _gemm(lib, 64, 64, 128, 2, 3, algo=4) == UNSUPPORTED
+    assert _gemm(lib, 64, 64, 128, 5, 1, algo=4) == UNSUPPORTED     # E2M1 path: p, q <= 4 ...
+    assert _gemm(lib, 64, 64, 128, 2, 6, algo=4) == UNSUPPORTED
+    assert _gemm(lib, 64, 64, 32768, 4, 4, algo=4) == UNSUPPORTED   # ... and 4 K (2^p-1)(2^q-1) < 2^24
     assert b"" != lib.apmm_last_error()
     # 2^31 / (255 * 255) = 33025.5: K = 32768 = 64 * 512 fits, the next padded K (33280) does not
     assert _gemm(lib, 0, 4, 32768, 8, 8) == 0                       # M == 0: ok, nothing launched
     assert _gemm(lib, 4, 4, 32769, 8, 8) == OVERFLOW
     assert _gemm(lib, 4, 4, 40000, 8, 8) == OVERFLOW
-    assert _gemm(lib, 64, 64, 128, 8, 8, algo=2) == UNSUPPORTED     # int8 MFMA cannot hold 8-bit codes
+    assert _gemm(lib, 64, 64, 128, 2, 2, algo=2) == UNSUPPORTED     # reserved algo id: no int8 MFMA kernel in this build
     assert lib.apmm_status_string(OVERFLOW) == b"result exceeds 32 bits"
     assert lib.apmm_pack_weights(None, 4, 128, 2, None, None) == INVALID
     assert lib.apmm_pack_activations(0x1000, 4, 128, 0, 0x2000, None) == INVALID
