@@ -11,6 +11,8 @@ Functions (paper passages in brackets):
   gemm_planes_i64(a_codes, w_codes,..)  decomposition / 1-bit products /
                                         shift-add recovery              [Sec. 3.2]
   scale_f64(c, a_scale, w_scale)        double-precision scale epilogue
+  quantize_rows(x_f16, p)               per-row symmetric quantisation of binary16
+                                        features onto the bipolar-INT grid [Sec. 3.1]
 """
 import ctypes
 import os
@@ -55,6 +57,10 @@ def _load():
     lib.oracle_half_bits_to_double.argtypes = [ctypes.c_uint16]
     lib.oracle_scale_f64.restype = None
     lib.oracle_scale_f64.argtypes = [i64, i64, i64p, u16p, u16p, f64p]
+    lib.oracle_float_to_half_bits.restype = ctypes.c_uint16
+    lib.oracle_float_to_half_bits.argtypes = [ctypes.c_float]
+    lib.oracle_quantize_rows.restype = None
+    lib.oracle_quantize_rows.argtypes = [i64, i64, ctypes.c_int, u16p, u8p, u16p]
     lib.oracle_max_abs.restype = i64
     lib.oracle_max_abs.argtypes = [i64, i64p]
     _lib = lib
@@ -137,3 +143,23 @@ def scale_f64(c, a_scale_bits=None, w_scale_bits=None):
     _load().oracle_scale_f64(M, N, c.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
                              ap, wp, f.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
     return f
+
+
+def float_to_half_bits(f):
+    return int(_load().oracle_float_to_half_bits(float(f)))
+
+
+def quantize_rows(x_f16, p):
+    """(codes uint8 M x K, scale bit patterns uint16 M) of binary16 features x (M x K float16)."""
+    x = np.ascontiguousarray(x_f16, dtype=np.float16)
+    if x.ndim != 2:
+        raise ValueError("x must be a 2-D float16 array (rows x K)")
+    M, K = x.shape
+    codes = np.zeros((M, K), dtype=np.uint8)
+    scale = np.zeros((M,), dtype=np.uint16)
+    if M and K:
+        u8p, u16p = ctypes.POINTER(ctypes.c_uint8), ctypes.POINTER(ctypes.c_uint16)
+        _load().oracle_quantize_rows(M, K, int(p), x.view(np.uint16).ctypes.data_as(u16p),
+                                     codes.ctypes.data_as(u8p), scale.ctypes.data_as(u16p))
+    return codes, scale
+

@@ -188,3 +188,66 @@ int64_t oracle_max_abs(int64_t count, const int64_t *c)
     }
     return best;
 }
+
+/* float -> IEEE-754 binary16 bit pattern, round to nearest, ties to even (finite inputs;
+ * values beyond the half range become infinity). */
+uint16_t oracle_float_to_half_bits(float f)
+{
+    double a = f < 0 ? -(double)f : (double)f;
+    uint16_t sign = (f < 0 || (f == 0 && 1.0f / f < 0)) ? 0x8000u : 0u;
+    if (a != a) return (uint16_t)(sign | 0x7e00u);
+    if (a == 0.0) return sign;
+    /* spacing of half values around a: 2^-24 below 2^-14, else 2^(e-10) with 2^e <= a < 2^(e+1) */
+    int e = -14;
+    double pw = 1.0 / 16384.0;                          /* 2^-14 */
+    while (a >= 2.0 * pw && e < 16) { pw *= 2.0; ++e; }
+    double ulp = pw / 1024.0;
+    double q = a / ulp;                                 /* exact: division by a power of two */
+    double fl = (double)(int64_t)q;                     /* q >= 0 */
+    double frac = q - fl;
+    int64_t n = (int64_t)fl;
+    if (frac > 0.5 || (frac == 0.5 && (n & 1))) ++n;
+    /* n counts ulps: below 2^-14 it is the subnormal mantissa; else 1024 <= n <= 2048 */
+    if (a < 1.0 / 16384.0) return (uint16_t)(sign | (uint16_t)n);   /* n == 1024 rolls into the first normal */
+    if (n == 2048) { n = 1024; ++e; }
+    if (e > 15) return (uint16_t)(sign | 0x7c00u);
+    return (uint16_t)(sign | (uint16_t)((e + 15) << 10) | (uint16_t)(n - 1024));
+}
+
+/* Paper Sec. 3.1: the bipolar-INT grid is symmetric (the odd integers from -(2^p - 1) to 2^p - 1),
+ * which suits symmetric quantisation of the feature matrix.  Reading taken (the paper gives no
+ * formula): per row (token), scale = max|x| / (2^p - 1) rounded to binary16; every element is divided by
+ * that rounded scale and moved to the nearest odd integer (ties upward), clamped to the grid; the code is
+ * (value + 2^p - 1) / 2.  A row whose scale rounds to zero gets the code of +1 everywhere.
+ * The decision is taken in single precision, the precision the GPU kernel computes it in:
+ *   s = half(max|x| / (float)(2^p - 1));  u = clamp(floorf((x / s) * 0.5f) + 2^(p-1), 0, 2^p - 1).
+ * x: M x K binary16 bit patterns (finite); codes: M x K; scale_half: M binary16 bit patterns. */
+void oracle_quantize_rows(int64_t M, int64_t K, int p, const uint16_t *x_half,
+                          uint8_t *codes, uint16_t *scale_half)
+{
+    const int top = (1 << p) - 1;
+    for (int64_t m = 0; m < M; ++m) {
+        const uint16_t *x = x_half + m * K;
+        float amax = 0.0f;
+        for (int64_t k = 0; k < K; ++k) {
+            float v = (float)oracle_half_bits_to_double(x[k]);
+            if (v < 0) v = -v;
+            if (v > amax) amax = v;
+        }
+        const float s32 = amax / (float)top;
+        const uint16_t sh = oracle_float_to_half_bits(s32);
+        const float s = (float)oracle_half_bits_to_double(sh);
+        scale_half[m] = sh;
+        for (int64_t k = 0; k < K; ++k) {
+            int u = 1 << (p - 1);
+            if (s > 0.0f) {
+                const float v = (float)oracle_half_bits_to_double(x[k]) / s;
+                const double cell = __builtin_floor((double)(v * 0.5f));
+                const double shifted = cell + (double)(1 << (p - 1));
+                u = shifted < 0 ? 0 : shifted > top ? top : (int)shifted;
+            }
+            codes[m * K + k] = (uint8_t)u;
+        }
+    }
+}
+

@@ -64,6 +64,19 @@ def normal_codes(seed, tag, rows, K, bits=4, sigma_steps=5.0):
     return np.clip(cell, 0, (1 << bits) - 1).astype(np.uint8).reshape(rows, K)
 
 
+def normal_features_f16(seed, tag, rows, K, outlier_every=0):
+    """rows x K binary16 features ~ N(0,1) (Box-Muller on hashed uniforms); with outlier_every > 0 every
+    outlier_every-th column is multiplied by 8, the heavy-tailed channels that activations of language
+    models show.  Input of the fused quantise + pack step."""
+    n = rows * K
+    u1 = uniform01(seed, tag, n)
+    u2 = uniform01(seed ^ 0x5DEECE66D, tag, n)
+    z = (np.sqrt(-2.0 * np.log(1.0 - u1)) * np.cos(2.0 * np.pi * u2)).reshape(rows, K)
+    if outlier_every:
+        z[:, ::outlier_every] *= 8.0
+    return z.astype(np.float16)
+
+
 def scales_f16(seed, tag, count, lo=0.01, hi=0.1):
     """binary16 scale vector ~ U(lo, hi); returned as float16 (view as uint16 for bit patterns)."""
     u = uniform01(seed, tag, count)

@@ -152,6 +152,31 @@ def test_degenerate_shapes(gpu, oracle, M, N, K):
         check_f16(c16, want, data, oracle)
 
 
+@pytest.mark.parametrize("p,q,K", [(2, 1, 2048), (1, 1, 4096), (2, 2, 2560), (3, 1, 2048), (4, 2, 2048)])
+def test_two_phase_kernel_whole_tiles(gpu, oracle, p, q, K):
+    """Whole 256 x 256 tiles, int32 output only and a short K: the MFMA kernel that stores its first
+    half under the k loop of the second is the one that runs."""
+    case = dict(M=512, N=768, K=K, p=p, q=q, a_dist="bernoulli", scaled=False)
+    data = inputs.make_case(case, 7000 + 10 * p + q)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+    for algo in (FP4, 0):
+        c32, _ = run_case(gpu, data, case, algo=algo, want_f16=False)
+        assert np.array_equal(c32.astype(np.int64), want), "algo %d" % algo
+
+
+def test_long_k_beyond_the_fp32_exactness_bound(gpu, oracle):
+    """4 K (2^p - 1)(2^q - 1) >= 2^24: the MFMA kernel declines, auto falls back to XOR/popcount."""
+    torch, binding = gpu
+    case = dict(M=20, N=24, K=20000, p=4, q=4, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 7100)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], 4, 4)
+    with pytest.raises(binding.ApmmError):
+        run_case(gpu, data, case, algo=FP4)
+    c32, c16 = run_case(gpu, data, case, algo=0)
+    assert np.array_equal(c32.astype(np.int64), want)
+    check_f16(c16, want, data, oracle)
+
+
 def test_extreme_values_hit_the_bound(gpu, oracle):
     """All-ones x all-ones and all-ones x all-zeros reach +-K(2^p-1)(2^q-1)."""
     torch, binding = gpu

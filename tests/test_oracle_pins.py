@@ -244,3 +244,84 @@ def test_config_cases_cover_the_five_workloads():
     case = inputs.make_case(dict(M=2, N=3, K=64, p=4, q=2, a_dist="normal", scaled=True), 5)
     assert case["a_codes"].shape == (2, 64) and case["w_codes"].shape == (3, 64)
     assert case["a_scale"].shape == (2,) and case["w_scale"].shape == (3,)
+
+
+# --------------------------------------------- quantisation onto the grid --
+def _val(codes, p):
+    return 2 * codes.astype(np.int64) - ((1 << p) - 1)
+
+
+def test_float_to_half_matches_the_library_conversion(oracle):
+    """The oracle's own binary32 -> binary16 rounding against numpy's, including subnormals,
+    ties and the overflow threshold."""
+    rng = np.random.default_rng(11)
+    vals = [rng.normal(size=3000).astype(np.float32) * np.float32(s) for s in (1e-8, 1e-6, 1e-4, 1e-2, 1, 100, 30000)]
+    ties = np.array([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 2.0 ** -25, 3 * 2.0 ** -25, 2.0 ** -24, 65504.0, 65519.0,
+                     65520.0, 0.0, -0.0, 6.1e-5, -2.5], dtype=np.float32)
+    with np.errstate(over="ignore"):
+        for v in np.concatenate(vals + [ties]):
+            assert oracle.float_to_half_bits(v) == int(np.float32(v).astype(np.float16).view(np.uint16)), v
+
+
+def test_quantize_one_bit_is_the_sign(oracle):
+    """Sec. 3.1: 1-bit bipolar-INT is binary quantisation, code = [x >= 0], scale = max|x|."""
+    x = inputs.normal_features_f16(21, inputs.TAG_A, 9, 200)
+    codes, scale = oracle.quantize_rows(x, 1)
+    assert np.array_equal(codes, (x >= 0).astype(np.uint8))
+    assert np.array_equal(scale.view(np.float16), np.abs(x).max(axis=1))
+
+
+@pytest.mark.parametrize("p", [2, 3, 4, 8])
+def test_quantize_is_exact_on_the_grid(oracle, p):
+    """Features that already are scale * (odd integers of the grid) come back as their own codes."""
+    top = (1 << p) - 1
+    rng = np.random.default_rng(p)
+    for scale in (2.0 ** -3, 2.0 ** -10, 1.0):
+        want = rng.integers(0, top + 1, size=(6, 77)).astype(np.uint8)
+        want[:, 0] = top                                  # the row maximum fixes the scale
+        if scale * top > 65504:
+            continue
+        x = (scale * _val(want, p)).astype(np.float16)
+        codes, s = oracle.quantize_rows(x, p)
+        assert np.array_equal(codes, want)
+        assert np.all(s.view(np.float16) == np.float16(scale))
+
+
+@pytest.mark.parametrize("p", [2, 3, 4, 5])
+def test_quantize_properties(oracle, p):
+    """Nearest grid point: |x - s val(u)| <= s unless clamped; the row maximum takes an outermost code;
+    codes never decrease with x; a zero row has scale 0 and the code of +1."""
+    top = (1 << p) - 1
+    x = inputs.normal_features_f16(30 + p, inputs.TAG_A, 40, 333, outlier_every=50)
+    x[7] = 0
+    codes, sbits = oracle.quantize_rows(x, p)
+    s = sbits.view(np.float16).astype(np.float64)
+    xd = x.astype(np.float64)
+    err = np.abs(xd - s[:, None] * _val(codes, p))
+    inside = np.abs(xd) <= s[:, None] * top
+    assert np.all(err[inside] <= s[:, None].repeat(x.shape[1], 1)[inside] * (1 + 1e-6))
+    rows = np.arange(x.shape[0])
+    at_max = codes[rows, np.abs(xd).argmax(axis=1)]
+    nz = s > 0
+    assert np.all((at_max[nz] == top) | (at_max[nz] == 0))
+    for m in range(x.shape[0]):
+        order = np.argsort(xd[m], kind="stable")
+        assert np.all(np.diff(codes[m, order].astype(np.int64)) >= 0)
+    assert sbits[7] == 0 and np.all(codes[7] == 1 << (p - 1))
+    want_scale = (np.abs(x.astype(np.float32)).max(axis=1) / np.float32(top)).astype(np.float16)
+    assert np.array_equal(sbits, want_scale.view(np.uint16))
+
+
+def test_quantize_brute_force_all_halves(oracle):
+    """Every finite binary16 value in one row with a power-of-two scale: the code is the cell of width 2
+    (in units of the scale) that holds the value, counted from the bottom of the grid."""
+    p, top = 3, 7
+    bits = np.arange(0x10000, dtype=np.uint16)
+    x = bits.view(np.float16)
+    x = x[np.isfinite(x) & (np.abs(x.astype(np.float64)) <= 7 * 0.25)]      # max |x| = 1.75 -> scale 0.25
+    codes, s = oracle.quantize_rows(x.reshape(1, -1), p)
+    assert s.view(np.float16)[0] == np.float16(0.25)
+    t = x.astype(np.float64) / 0.25                                          # exact
+    want = np.clip(np.floor(t / 2.0) + 4, 0, top).astype(np.uint8)
+    assert np.array_equal(codes[0], want)
+
