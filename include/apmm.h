@@ -71,6 +71,20 @@ apmm_status apmm_pack_weights(const uint8_t *w_codes, int64_t N, int64_t K, int 
 apmm_status apmm_pack_activations(const uint8_t *a_codes, int64_t M, int64_t K, int p,
                                   void *a_packed, void *stream);
 
+/* Paper Sec. 3.1 (the feature matrix is quantised onto the symmetric bipolar-INT grid) fused with the
+ * packing of Sec. 4.1, for activations that arrive as binary16 numbers: one pass instead of writing and
+ * re-reading one code byte per element.  Per row (token) m:
+ *   a_scale[m] = half(max_k |x[m][k]| / (2^p - 1))          (single precision division, rounded to nearest even)
+ *   code       = clamp(floor((x / a_scale[m]) / 2) + 2^(p-1), 0, 2^p - 1)
+ * i.e. x / a_scale moved to the nearest odd integer (ties upward) of the grid; a row whose scale rounds to
+ * zero gets the code of +1 everywhere.  The result is the packed operand apmm_pack_activations would give
+ * for those codes, and a_scale is the per-token scale for apmm_gemm's fp16 epilogue.
+ *   x_f16    : device, M x K binary16 bit patterns, row-major, finite values
+ *   a_packed : device, apmm_packed_bytes(M, K, p) bytes, written entirely
+ *   a_scale  : device, M binary16 bit patterns, written */
+apmm_status apmm_quantize_pack_activations(const uint16_t *x_f16, int64_t M, int64_t K, int p,
+                                           void *a_packed, uint16_t *a_scale, void *stream);
+
 /* Inverse of the pack transform (test aid): writes rows x K uint8 codes. */
 apmm_status apmm_unpack(const void *packed, int64_t rows, int64_t K, int bits,
                         uint8_t *codes, void *stream);

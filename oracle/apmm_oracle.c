@@ -219,8 +219,10 @@ uint16_t oracle_float_to_half_bits(float f)
  * formula): per row (token), scale = max|x| / (2^p - 1) rounded to binary16; every element is divided by
  * that rounded scale and moved to the nearest odd integer (ties upward), clamped to the grid; the code is
  * (value + 2^p - 1) / 2.  A row whose scale rounds to zero gets the code of +1 everywhere.
- * The decision is taken in single precision, the precision the GPU kernel computes it in:
- *   s = half(max|x| / (float)(2^p - 1));  u = clamp(floorf((x / s) * 0.5f) + 2^(p-1), 0, 2^p - 1).
+ * The decision is taken in single precision, the precision the GPU kernel computes it in, and, as
+ * quantisers usually do, by multiplying with the reciprocal of the scale (one division per row):
+ *   s = half(max|x| / (float)(2^p - 1));  r = 1.0f / s;
+ *   u = clamp(floorf(x * (r * 0.5f)) + 2^(p-1), 0, 2^p - 1).
  * x: M x K binary16 bit patterns (finite); codes: M x K; scale_half: M binary16 bit patterns. */
 void oracle_quantize_rows(int64_t M, int64_t K, int p, const uint16_t *x_half,
                           uint8_t *codes, uint16_t *scale_half)
@@ -241,8 +243,9 @@ void oracle_quantize_rows(int64_t M, int64_t K, int p, const uint16_t *x_half,
         for (int64_t k = 0; k < K; ++k) {
             int u = 1 << (p - 1);
             if (s > 0.0f) {
-                const float v = (float)oracle_half_bits_to_double(x[k]) / s;
-                const double cell = __builtin_floor((double)(v * 0.5f));
+                const float half_r = (1.0f / s) * 0.5f;
+                const float v = (float)oracle_half_bits_to_double(x[k]) * half_r;
+                const double cell = __builtin_floor((double)v);
                 const double shifted = cell + (double)(1 << (p - 1));
                 u = shifted < 0 ? 0 : shifted > top ? top : (int)shifted;
             }

@@ -16,7 +16,7 @@ ALGO_AUTO, ALGO_VALU_POPCOUNT, ALGO_MFMA_INT8, ALGO_DECODE, ALGO_MFMA_FP4 = 0, 1
 
 EXPORTS = [
     "apmm_packed_bytes", "apmm_workspace_bytes", "apmm_pack_weights", "apmm_pack_activations",
-    "apmm_unpack", "apmm_gemm", "apmm_gemm_ex", "apmm_status_string", "apmm_last_error", "apmm_version",
+    "apmm_quantize_pack_activations", "apmm_unpack", "apmm_gemm", "apmm_gemm_ex", "apmm_status_string", "apmm_last_error", "apmm_version",
 ]
 
 _lib = None
@@ -46,6 +46,8 @@ def load():
         fn = getattr(lib, name)
         fn.restype = ci
         fn.argtypes = [vp, i64, i64, ci, vp, vp]
+    lib.apmm_quantize_pack_activations.restype = ci
+    lib.apmm_quantize_pack_activations.argtypes = [vp, i64, i64, ci, vp, vp, vp]
     lib.apmm_unpack.restype = ci
     lib.apmm_unpack.argtypes = [vp, i64, i64, ci, vp, vp]
     gemm_args = [i64, i64, i64, ci, ci, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -111,6 +113,24 @@ def apmm_pack_weights(w_codes, q, out=None):
 def apmm_pack_activations(a_codes, p, out=None):
     """M x K uint8 activation codes -> opaque packed buffer (uint8 tensor)."""
     return _pack("apmm_pack_activations", a_codes, p, out)
+
+
+def apmm_quantize_pack_activations(x_f16, p, out=None, scale_out=None):
+    """M x K float16 activations -> (opaque packed buffer, float16 per-token scales)."""
+    if x_f16.dtype != torch.float16 or not x_f16.is_cuda or not x_f16.is_contiguous() or x_f16.dim() != 2:
+        raise ValueError("x must be a contiguous 2-D float16 CUDA tensor")
+    M, K = x_f16.shape
+    nbytes = apmm_packed_bytes(M, K, p)
+    if out is None:
+        out = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=x_f16.device)
+    elif out.numel() * out.element_size() < nbytes:
+        raise ValueError("packed buffer too small")
+    if scale_out is None:
+        scale_out = torch.empty(M, dtype=torch.float16, device=x_f16.device)
+    elif scale_out.dtype != torch.float16 or scale_out.numel() < M:
+        raise ValueError("scale_out must hold M float16 values")
+    _check(load().apmm_quantize_pack_activations(_ptr(x_f16), M, K, p, _ptr(out), _ptr(scale_out), _stream()))
+    return out, scale_out
 
 
 def apmm_unpack(packed, rows, K, bits):

@@ -63,6 +63,21 @@ apmm_status apmm_pack_activations(const uint8_t *a_codes, int64_t M, int64_t K, 
     return pack_common(a_codes, M, K, p, a_packed, stream, "apmm_pack_activations");
 }
 
+apmm_status apmm_quantize_pack_activations(const uint16_t *x_f16, int64_t M, int64_t K, int p, void *a_packed,
+                                           uint16_t *a_scale, void *stream)
+{
+    if (M < 0 || K < 1 || !bits_ok(p)) return fail(APMM_ERR_INVALID_ARG, "quantize_pack: M < 0, K < 1 or bits outside [1, 8]");
+    if (M == 0) return APMM_OK;
+    if (!x_f16 || !a_packed || !a_scale) return fail(APMM_ERR_INVALID_ARG, "quantize_pack: null pointer");
+    if (!aligned16(a_packed)) return fail(APMM_ERR_INVALID_ARG, "quantize_pack: packed buffer must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(x_f16) & 1u) || (reinterpret_cast<uintptr_t>(a_scale) & 1u))
+        return fail(APMM_ERR_INVALID_ARG, "quantize_pack: misaligned binary16 buffer");
+    hipError_t e = apmm::launch_quantize_pack(x_f16, M, K, p, static_cast<uint32_t *>(a_packed), a_scale,
+                                              static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip(e, "apmm_quantize_pack_activations");
+    return APMM_OK;
+}
+
 apmm_status apmm_unpack(const void *packed, int64_t rows, int64_t K, int bits, uint8_t *codes, void *stream)
 {
     if (rows < 0 || K < 1 || !bits_ok(bits)) return fail(APMM_ERR_INVALID_ARG, "unpack: rows < 0, K < 1 or bits outside [1, 8]");

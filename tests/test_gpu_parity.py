@@ -177,6 +177,45 @@ def test_long_k_beyond_the_fp32_exactness_bound(gpu, oracle):
     check_f16(c16, want, data, oracle)
 
 
+@pytest.mark.parametrize("M,K,p", [(1, 64, 2), (5, 100, 3), (33, 513, 4), (64, 4096, 2), (16, 11008, 4), (7, 250, 1),
+                                   (40, 1000, 8)])
+def test_quantize_pack_matches_the_oracle(gpu, oracle, M, K, p):
+    """Fused quantise + pack of float16 activations: codes and per-token scales bit-exact."""
+    torch, binding = gpu
+    x = inputs.normal_features_f16(8000 + M + K + p, inputs.TAG_A, M, K, outlier_every=37)
+    if M > 3:
+        x[3] = 0                                                       # a row of zeros: scale 0, code of +1
+    want_codes, want_scale = oracle.quantize_rows(x, p)
+    packed, scale = binding.apmm_quantize_pack_activations(torch.from_numpy(x).to("cuda:0"), p)
+    codes = binding.apmm_unpack(packed, M, K, p).cpu().numpy()
+    assert np.array_equal(scale.cpu().numpy().view(np.uint16), want_scale)
+    assert np.array_equal(codes, want_codes)
+    # the packed operand is the one apmm_pack_activations gives for those codes (row sums included)
+    again = binding.apmm_pack_activations(torch.from_numpy(want_codes).to("cuda:0"), p)
+    assert torch.equal(packed, again)
+
+
+def test_quantized_activations_through_the_gemm(gpu, oracle):
+    """float16 activations -> quantise + pack -> GEMM with the fp16 epilogue, against the oracle's
+    quantiser, integer GEMM and double-precision scaling."""
+    torch, binding = gpu
+    M, N, K, p, q = 48, 200, 1024, 4, 2
+    x = inputs.normal_features_f16(8100, inputs.TAG_A, M, K, outlier_every=64)
+    w = inputs.bernoulli_codes(8100, inputs.TAG_W, N, K, q)
+    sw = inputs.scales_f16(8100, inputs.TAG_W_SCALE, N)
+    codes, sa_bits = oracle.quantize_rows(x, p)
+    want = oracle.gemm_i64(codes, w, p, q)
+    ap, sa = binding.apmm_quantize_pack_activations(torch.from_numpy(x).to("cuda:0"), p)
+    wp = binding.apmm_pack_weights(torch.from_numpy(w).to("cuda:0"), q)
+    c32, c16 = binding.apmm_gemm(M, N, K, p, q, ap, wp, want_i32=True, want_f16=True,
+                                 w_scale=torch.from_numpy(sw).to("cuda:0"), a_scale=sa)
+    torch.cuda.synchronize()
+    assert np.array_equal(c32.cpu().numpy().astype(np.int64), want)
+    f = oracle.scale_f64(want, sa_bits, sw.view(np.uint16))
+    got = c16.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - f) <= 1e-3 * np.abs(f) + 1e-6)
+
+
 def test_extreme_values_hit_the_bound(gpu, oracle):
     """All-ones x all-ones and all-ones x all-zeros reach +-K(2^p-1)(2^q-1)."""
     torch, binding = gpu
