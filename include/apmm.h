@@ -116,6 +116,27 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q,
                          void *workspace, size_t workspace_bytes, void *stream,
                          int algo);
 
+/* One linear of a grouped call: C = A * W^T with the arguments of apmm_gemm. */
+typedef struct apmm_problem {
+    int64_t M, N, K;
+    const void *a_packed;     /* device, packed M x K activations of p bits */
+    const void *w_packed;     /* device, packed N x K weights of q bits */
+    int32_t *c_i32;           /* device, M x N, or NULL */
+    uint16_t *c_f16;          /* device, M x N binary16 bit patterns, or NULL */
+    const uint16_t *w_scale;  /* device, N, or NULL */
+    const uint16_t *a_scale;  /* device, M, or NULL */
+} apmm_problem;
+
+/* Several independent GEMMs of equal p and q with as few launches as possible (for callers whose
+ * linears are small enough that the launch, not the data, bounds them: the q/k/v or gate/up
+ * projections of one decoder layer at a few tokens share their activations and can go in one launch).
+ * `problems` is a HOST array of `count` entries, read before the call returns.  Each entry obeys the
+ * rules of apmm_gemm and gives the same result as apmm_gemm on it.  Problems with M <= 16 that the same
+ * small-M kernel covers are launched eight at a time; all others are launched one by one.  The outputs
+ * of different entries must not overlap.  At most 256 entries.  On an argument error nothing is launched. */
+apmm_status apmm_gemm_grouped(int count, const apmm_problem *problems, int p, int q,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
 const char *apmm_status_string(apmm_status status);
 /* Text of the last error on the calling thread ("" if none). */
 const char *apmm_last_error(void);

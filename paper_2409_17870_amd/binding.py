@@ -16,8 +16,19 @@ ALGO_AUTO, ALGO_VALU_POPCOUNT, ALGO_MFMA_INT8, ALGO_DECODE, ALGO_MFMA_FP4 = 0, 1
 
 EXPORTS = [
     "apmm_packed_bytes", "apmm_workspace_bytes", "apmm_pack_weights", "apmm_pack_activations",
-    "apmm_quantize_pack_activations", "apmm_unpack", "apmm_gemm", "apmm_gemm_ex", "apmm_status_string", "apmm_last_error", "apmm_version",
+    "apmm_quantize_pack_activations", "apmm_unpack", "apmm_gemm", "apmm_gemm_ex", "apmm_gemm_grouped",
+    "apmm_status_string", "apmm_last_error", "apmm_version",
 ]
+
+
+
+class ApmmProblem(ctypes.Structure):
+    """struct apmm_problem of include/apmm.h"""
+    _fields_ = [("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
+                ("a_packed", ctypes.c_void_p), ("w_packed", ctypes.c_void_p),
+                ("c_i32", ctypes.c_void_p), ("c_f16", ctypes.c_void_p),
+                ("w_scale", ctypes.c_void_p), ("a_scale", ctypes.c_void_p)]
+
 
 _lib = None
 
@@ -55,6 +66,8 @@ def load():
     lib.apmm_gemm.argtypes = gemm_args
     lib.apmm_gemm_ex.restype = ci
     lib.apmm_gemm_ex.argtypes = gemm_args + [ci]
+    lib.apmm_gemm_grouped.restype = ci
+    lib.apmm_gemm_grouped.argtypes = [ci, ctypes.POINTER(ApmmProblem), ci, ci, vp, ctypes.c_size_t, vp]
     lib.apmm_status_string.restype = ctypes.c_char_p
     lib.apmm_status_string.argtypes = [ci]
     lib.apmm_last_error.restype = ctypes.c_char_p
@@ -163,3 +176,19 @@ def apmm_gemm(M, N, K, p, q, a_packed, w_packed, want_i32=True, want_f16=False, 
 
 def apmm_version():
     return int(load().apmm_version())
+
+
+def apmm_gemm_grouped(problems, p, q):
+    """Several GEMMs of equal p, q with as few launches as possible.
+
+    problems: list of dicts with keys M, N, K, a_packed, w_packed and optionally c_i32, c_f16 (output
+    tensors), w_scale, a_scale.  Outputs must be preallocated by the caller.
+    """
+    arr = (ApmmProblem * max(len(problems), 1))()
+    for i, pr in enumerate(problems):
+        arr[i].M, arr[i].N, arr[i].K = pr["M"], pr["N"], pr["K"]
+        for key in ("a_packed", "w_packed", "c_i32", "c_f16", "w_scale", "a_scale"):
+            t = pr.get(key)
+            setattr(arr[i], key, t.data_ptr() if t is not None else None)
+    _check(load().apmm_gemm_grouped(len(problems), arr, p, q, None, 0, _stream()))
+

@@ -90,28 +90,31 @@ apmm_status apmm_unpack(const void *packed, int64_t rows, int64_t K, int bits, u
     return APMM_OK;
 }
 
-apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const void *a_packed,
-                         const void *w_packed, int32_t *c_i32, uint16_t *c_f16, const uint16_t *w_scale,
-                         const uint16_t *a_scale, void *workspace, size_t workspace_bytes, void *stream,
-                         int algo)
+}  // extern "C"
+
+namespace {
+
+// Argument checks of one GEMM; fills `g`.  `empty` is set when M == 0 or N == 0 (nothing to launch).
+apmm_status check_gemm(int64_t M, int64_t N, int64_t K, int p, int q, const void *a_packed, const void *w_packed,
+                       int32_t *c_i32, uint16_t *c_f16, const uint16_t *w_scale, const uint16_t *a_scale,
+                       apmm::GemmArgs &g, bool &empty)
 {
-    (void)workspace;
-    (void)workspace_bytes;
+    empty = false;
     if (M < 0 || N < 0 || K < 1 || !bits_ok(p) || !bits_ok(q))
         return fail(APMM_ERR_INVALID_ARG, "gemm: M < 0, N < 0, K < 1 or bits outside [1, 8]");
-    if (algo < APMM_ALGO_AUTO || algo > APMM_ALGO_MFMA_FP4) return fail(APMM_ERR_INVALID_ARG, "gemm: unknown algo");
     const int64_t k_p = apmm::round_up(K, apmm::kKPad);
     const int64_t unit = (int64_t)((1 << p) - 1) * (int64_t)((1 << q) - 1);
     if (k_p > INT32_MAX / unit) return fail(APMM_ERR_OVERFLOW, "gemm: K * (2^p - 1) * (2^q - 1) exceeds the 32-bit output");
-    if (M == 0 || N == 0) return APMM_OK;
+    if (M == 0 || N == 0) {
+        empty = true;
+        return APMM_OK;
+    }
     if (!a_packed || !w_packed) return fail(APMM_ERR_INVALID_ARG, "gemm: null operand");
     if (!c_i32 && !c_f16) return fail(APMM_ERR_INVALID_ARG, "gemm: no output requested");
     if (!aligned16(a_packed) || !aligned16(w_packed))
         return fail(APMM_ERR_INVALID_ARG, "gemm: packed operands must be 16-byte aligned");
     if ((c_i32 && (reinterpret_cast<uintptr_t>(c_i32) & 3u)) || (c_f16 && (reinterpret_cast<uintptr_t>(c_f16) & 1u)))
         return fail(APMM_ERR_INVALID_ARG, "gemm: misaligned output");
-
-    apmm::GemmArgs g;
     g.M = M; g.N = N; g.K = K;
     g.nkb = k_p / apmm::kKBlock;
     g.p = p; g.q = q;
@@ -121,13 +124,16 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
     g.w_sum = reinterpret_cast<const int32_t *>(g.w + apmm::row_sum_word(apmm::round_up(N, apmm::kRowBlock), g.nkb, q));
     g.c_i32 = c_i32; g.c_f16 = c_f16;
     g.w_scale = w_scale; g.a_scale = a_scale;
-    g.pad_corr = (int32_t)((k_p - K) * unit);
+    return APMM_OK;
+}
 
-    hipStream_t s = static_cast<hipStream_t>(stream);
+constexpr int kMaxProblems = 256;  // entries of one apmm_gemm_grouped call
+
+apmm_status run_gemm(const apmm::GemmArgs &g, int algo, hipStream_t s)
+{
     if (algo == APMM_ALGO_AUTO) {
-        if (M <= 16 && apmm::gemm_decode_supported(g)) algo = APMM_ALGO_DECODE;
-        else if (M > 16 && apmm::gemm_mfma_fp4_supported(g)) algo = APMM_ALGO_MFMA_FP4;
-        else if (M > 16 && apmm::gemm_mfma_supported(g)) algo = APMM_ALGO_MFMA_INT8;
+        if (g.M <= 16 && apmm::gemm_decode_supported(g)) algo = APMM_ALGO_DECODE;
+        else if (g.M > 16 && apmm::gemm_mfma_fp4_supported(g)) algo = APMM_ALGO_MFMA_FP4;
         else algo = APMM_ALGO_VALU_POPCOUNT;
     }
     hipError_t e;
@@ -136,9 +142,7 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
         e = apmm::launch_gemm_valu(g, s);
         break;
     case APMM_ALGO_MFMA_INT8:
-        if (!apmm::gemm_mfma_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: no int8 MFMA kernel in this build");
-        e = apmm::launch_gemm_mfma(g, s);
-        break;
+        return fail(APMM_ERR_UNSUPPORTED, "gemm: no int8 MFMA kernel in this build");
     case APMM_ALGO_MFMA_FP4:
         if (!apmm::gemm_mfma_fp4_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: FP4 MFMA kernel covers p, q in 1..4 while 4 K (2^p - 1)(2^q - 1) < 2^24");
         e = apmm::launch_gemm_mfma_fp4(g, s);
@@ -151,6 +155,61 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
         return fail(APMM_ERR_INVALID_ARG, "gemm: unknown algo");
     }
     if (e != hipSuccess) return fail_hip(e, "apmm_gemm");
+    return APMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const void *a_packed,
+                         const void *w_packed, int32_t *c_i32, uint16_t *c_f16, const uint16_t *w_scale,
+                         const uint16_t *a_scale, void *workspace, size_t workspace_bytes, void *stream,
+                         int algo)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    if (algo < APMM_ALGO_AUTO || algo > APMM_ALGO_MFMA_FP4) return fail(APMM_ERR_INVALID_ARG, "gemm: unknown algo");
+    apmm::GemmArgs g;
+    bool empty;
+    const apmm_status st = check_gemm(M, N, K, p, q, a_packed, w_packed, c_i32, c_f16, w_scale, a_scale, g, empty);
+    if (st != APMM_OK || empty) return st;
+    return run_gemm(g, algo, static_cast<hipStream_t>(stream));
+}
+
+apmm_status apmm_gemm_grouped(int count, const apmm_problem *problems, int p, int q, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    if (count < 0 || (count > 0 && !problems)) return fail(APMM_ERR_INVALID_ARG, "gemm_grouped: bad problem list");
+    if (count > kMaxProblems) return fail(APMM_ERR_INVALID_ARG, "gemm_grouped: more than 256 problems");
+    // every entry is checked before anything is launched
+    static thread_local apmm::GemmArgs args[kMaxProblems];
+    int live = 0;
+    for (int i = 0; i < count; ++i) {
+        const apmm_problem &pr = problems[i];
+        bool empty;
+        const apmm_status st = check_gemm(pr.M, pr.N, pr.K, p, q, pr.a_packed, pr.w_packed, pr.c_i32, pr.c_f16,
+                                          pr.w_scale, pr.a_scale, args[live], empty);
+        if (st != APMM_OK) return st;
+        if (!empty) ++live;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int i = 0;
+    while (i < live) {
+        // longest run (up to kMaxGroup) that one small-M launch covers
+        int run = 1;
+        while (i + run < live && run < apmm::kMaxGroup && apmm::gemm_decode_group_supported(args + i, run + 1)) ++run;
+        if (run > 1 || (args[i].M <= 16 && apmm::gemm_decode_group_supported(args + i, 1))) {
+            hipError_t e = apmm::launch_gemm_decode_group(args + i, run, s);
+            if (e != hipSuccess) return fail_hip(e, "apmm_gemm_grouped");
+        } else {
+            const apmm_status st = run_gemm(args[i], APMM_ALGO_AUTO, s);
+            if (st != APMM_OK) return st;
+        }
+        i += run;
+    }
     return APMM_OK;
 }
 

@@ -67,13 +67,19 @@ __device__ __forceinline__ uint4 plane_half_words_reg(const uint4 (&slot)[Q], in
 }
 
 template <int MT, int Q>
-__global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GemmArgs g)
+__global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GroupArgs ga)
 {
+    // which problem of the launch this workgroup works on (uniform over the workgroup)
+    int idx = 0;
+    for (int i = 0; i + 1 < ga.count; ++i)
+        if ((int)blockIdx.x >= ga.wg_end[i]) idx = i + 1;
+    const GemmArgs g = ga.g[idx];
+    const int block = (int)blockIdx.x - (idx ? ga.wg_end[idx - 1] : 0);
     extern __shared__ __align__(16) uint8_t lds_raw[];
     uint4 *a_lds = reinterpret_cast<uint4 *>(lds_raw);  // [kb][m < MT][j < p][hh < 2] plane words, common form
     const int p = g.p;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t n0 = (int64_t)blockIdx.x * kRowsPerWg;
+    const int64_t n0 = (int64_t)block * kRowsPerWg;
 
     const int row = lane & 15, sub = lane >> 4;
     int64_t n = n0 + row;
@@ -179,32 +185,52 @@ size_t decode_lds_bytes(const GemmArgs &g, int mt)
 
 int decode_mt(int64_t M) { return M <= 1 ? 1 : M <= 2 ? 2 : M <= 4 ? 4 : M <= 8 ? 8 : 16; }
 
-template <int MT, int Q>
-hipError_t launch_mt_q(const GemmArgs &g, hipStream_t stream)
+// Builds the launch descriptor of `count` problems (16 output channels per workgroup each).
+bool make_group(const GemmArgs *gs, int count, GroupArgs &ga)
 {
-    const size_t lds = decode_lds_bytes(g, MT);
-    auto kernel = gemm_decode_kernel<MT, Q>;
-    static bool attr_set = false;  // idempotent; a race here is harmless
-    if (!attr_set) {
+    if (count < 1 || count > kMaxGroup) return false;
+    int64_t end = 0;
+    ga.count = count;
+    for (int i = 0; i < kMaxGroup; ++i) {
+        const GemmArgs &g = gs[i < count ? i : count - 1];
+        if (i < count) end += (g.N + kRowsPerWg - 1) / kRowsPerWg;
+        if (end > 0x7fffffffLL) return false;
+        ga.wg_end[i] = (int)end;
+        ga.g[i] = g;
+    }
+    return true;
+}
+
+template <class Kernel>
+hipError_t launch_group(Kernel kernel, bool &attr_set, const GroupArgs &ga, size_t lds, hipStream_t stream)
+{
+    if (!attr_set) {  // idempotent; a race here is harmless
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int64_t wgs = (g.N + kRowsPerWg - 1) / kRowsPerWg;
-    if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)wgs), dim3(kThreads), lds, stream, g);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)ga.wg_end[ga.count - 1]), dim3(kThreads), lds, stream, ga);
     return hipGetLastError();
 }
 
-template <int MT>
-hipError_t launch_mt(const GemmArgs &g, hipStream_t stream)
+template <int MT, int Q>
+hipError_t launch_mt_q(const GroupArgs &ga, hipStream_t stream)
 {
-    switch (g.q) {
-    case 1: return launch_mt_q<MT, 1>(g, stream);
-    case 2: return launch_mt_q<MT, 2>(g, stream);
-    case 3: return launch_mt_q<MT, 3>(g, stream);
-    case 4: return launch_mt_q<MT, 4>(g, stream);
+    size_t lds = 0;
+    for (int i = 0; i < ga.count; ++i) lds = lds > decode_lds_bytes(ga.g[i], MT) ? lds : decode_lds_bytes(ga.g[i], MT);
+    static bool attr_set = false;
+    return launch_group(gemm_decode_kernel<MT, Q>, attr_set, ga, lds, stream);
+}
+
+template <int MT>
+hipError_t launch_mt(const GroupArgs &ga, hipStream_t stream)
+{
+    switch (ga.g[0].q) {
+    case 1: return launch_mt_q<MT, 1>(ga, stream);
+    case 2: return launch_mt_q<MT, 2>(ga, stream);
+    case 3: return launch_mt_q<MT, 3>(ga, stream);
+    case 4: return launch_mt_q<MT, 4>(ga, stream);
     }
     return hipErrorInvalidValue;
 }
@@ -222,13 +248,19 @@ hipError_t launch_mt(const GemmArgs &g, hipStream_t stream)
 //   (the operand scales make acc = 4 S).
 // ---------------------------------------------------------------------------------------------
 template <int P, int Q>
-__global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GemmArgs g)
+__global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga)
 {
+    // which problem of the launch this workgroup works on (uniform over the workgroup)
+    int idx = 0;
+    for (int i = 0; i + 1 < ga.count; ++i)
+        if ((int)blockIdx.x >= ga.wg_end[i]) idx = i + 1;
+    const GemmArgs g = ga.g[idx];
+    const int block = (int)blockIdx.x - (idx ? ga.wg_end[idx - 1] : 0);
     static_assert(P <= 2 && Q <= 2, "one plane group per operand");
     extern __shared__ __align__(16) uint8_t lds_raw[];
     uint4 *a_lds = reinterpret_cast<uint4 *>(lds_raw);  // [kb][token < 16][slot < P]: packed words as they are
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t n0 = (int64_t)blockIdx.x * kRowsPerWg;
+    const int64_t n0 = (int64_t)block * kRowsPerWg;
     constexpr int kSlotVec = kPlaneWords / 4;
 
     const int r16 = lane & 15, kq = lane >> 4;
@@ -332,49 +364,59 @@ bool decode_mfma_supported(const GemmArgs &g)
 }
 
 template <int P, int Q>
-hipError_t launch_decode_mfma_pq(const GemmArgs &g, hipStream_t stream)
+hipError_t launch_decode_mfma_pq(const GroupArgs &ga, hipStream_t stream)
 {
-    auto kernel = gemm_decode_mfma_kernel<P, Q>;
-    static bool attr_set = false;  // idempotent; a race here is harmless
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    const int64_t wgs = (g.N + kRowsPerWg - 1) / kRowsPerWg;
-    if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)wgs), dim3(kThreads), decode_mfma_lds_bytes(g), stream, g);
-    return hipGetLastError();
+    size_t lds = 0;
+    for (int i = 0; i < ga.count; ++i) lds = lds > decode_mfma_lds_bytes(ga.g[i]) ? lds : decode_mfma_lds_bytes(ga.g[i]);
+    static bool attr_set = false;
+    return launch_group(gemm_decode_mfma_kernel<P, Q>, attr_set, ga, lds, stream);
 }
 
-hipError_t launch_decode_mfma(const GemmArgs &g, hipStream_t stream)
+hipError_t launch_decode_mfma(const GroupArgs &ga, hipStream_t stream)
 {
-    if (g.p == 1 && g.q == 1) return launch_decode_mfma_pq<1, 1>(g, stream);
-    if (g.p == 1 && g.q == 2) return launch_decode_mfma_pq<1, 2>(g, stream);
-    if (g.p == 2 && g.q == 1) return launch_decode_mfma_pq<2, 1>(g, stream);
-    return launch_decode_mfma_pq<2, 2>(g, stream);
+    const int p = ga.g[0].p, q = ga.g[0].q;
+    if (p == 1 && q == 1) return launch_decode_mfma_pq<1, 1>(ga, stream);
+    if (p == 1 && q == 2) return launch_decode_mfma_pq<1, 2>(ga, stream);
+    if (p == 2 && q == 1) return launch_decode_mfma_pq<2, 1>(ga, stream);
+    return launch_decode_mfma_pq<2, 2>(ga, stream);
+}
+
+// kernel variant that serves a problem: 0 = none, 100 = matrix unit, else the token tile of the XOR/popcount kernel
+int decode_variant(const GemmArgs &g)
+{
+    if (g.M < 1 || g.M > 16 || g.q < 1 || g.q > 4) return 0;
+    if (decode_mfma_supported(g)) return 100;
+    return decode_lds_bytes(g, decode_mt(g.M)) <= (size_t)kMaxLdsBytes ? decode_mt(g.M) : 0;
 }
 
 }  // namespace
 
 // M <= 16, q <= 4, and the activations of all K must fit the LDS budget.
-bool gemm_decode_supported(const GemmArgs &g)
+bool gemm_decode_supported(const GemmArgs &g) { return decode_variant(g) != 0; }
+
+bool gemm_decode_group_supported(const GemmArgs *gs, int count)
 {
-    if (g.M < 1 || g.M > 16 || g.q < 1 || g.q > 4) return false;
-    return decode_lds_bytes(g, decode_mt(g.M)) <= (size_t)kMaxLdsBytes;
+    if (count < 1 || count > kMaxGroup) return false;
+    const int v = decode_variant(gs[0]);
+    for (int i = 0; i < count; ++i)
+        if (decode_variant(gs[i]) != v || gs[i].p != gs[0].p || gs[i].q != gs[0].q) return false;
+    return v != 0;
 }
 
-hipError_t launch_gemm_decode(const GemmArgs &g, hipStream_t stream)
+hipError_t launch_gemm_decode_group(const GemmArgs *gs, int count, hipStream_t stream)
 {
-    if (decode_mfma_supported(g)) return launch_decode_mfma(g, stream);
-    switch (decode_mt(g.M)) {
-    case 1: return launch_mt<1>(g, stream);
-    case 2: return launch_mt<2>(g, stream);
-    case 4: return launch_mt<4>(g, stream);
-    case 8: return launch_mt<8>(g, stream);
-    default: return launch_mt<16>(g, stream);
+    GroupArgs ga;
+    if (!gemm_decode_group_supported(gs, count) || !make_group(gs, count, ga)) return hipErrorInvalidValue;
+    switch (decode_variant(gs[0])) {
+    case 100: return launch_decode_mfma(ga, stream);
+    case 1: return launch_mt<1>(ga, stream);
+    case 2: return launch_mt<2>(ga, stream);
+    case 4: return launch_mt<4>(ga, stream);
+    case 8: return launch_mt<8>(ga, stream);
+    default: return launch_mt<16>(ga, stream);
     }
 }
+
+hipError_t launch_gemm_decode(const GemmArgs &g, hipStream_t stream) { return launch_gemm_decode_group(&g, 1, stream); }
 
 }  // namespace apmm

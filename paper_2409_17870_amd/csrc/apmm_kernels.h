@@ -28,5 +28,9 @@ hipError_t launch_gemm_mfma_fp4(const GemmArgs &args, hipStream_t stream);
 // Small-M weight-streaming kernel (M <= 16).
 bool gemm_decode_supported(const GemmArgs &args);
 hipError_t launch_gemm_decode(const GemmArgs &args, hipStream_t stream);
+// Up to kMaxGroup small-M problems of equal p, q in one launch; they must all be covered by the same
+// kernel variant (gemm_decode_group_supported).
+bool gemm_decode_group_supported(const GemmArgs *args, int count);
+hipError_t launch_gemm_decode_group(const GemmArgs *args, int count, hipStream_t stream);
 
 }  // namespace apmm

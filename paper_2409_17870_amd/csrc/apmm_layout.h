@@ -81,7 +81,14 @@ struct GemmArgs {
     uint16_t *c_f16;      // may be null
     const uint16_t *w_scale;  // may be null
     const uint16_t *a_scale;  // may be null
-    int32_t pad_corr;     // (Kp - K) * (2^p - 1) * (2^q - 1)
+};
+
+// Several problems of one launch (decode kernels): workgroups wg_end[i-1] .. wg_end[i]-1 work on g[i].
+constexpr int kMaxGroup = 8;
+struct GroupArgs {
+    int count;
+    int wg_end[kMaxGroup];
+    GemmArgs g[kMaxGroup];
 };
 
 }  // namespace apmm

@@ -216,6 +216,38 @@ def test_quantized_activations_through_the_gemm(gpu, oracle):
     assert np.all(np.abs(got - f) <= 1e-3 * np.abs(f) + 1e-6)
 
 
+@pytest.mark.parametrize("M", [1, 2, 8, 16, 40])
+def test_grouped_launch_matches_single_calls_and_the_oracle(gpu, oracle, M):
+    """q/k/v-like (shared activations) and gate/up-like linears plus one of another K in one grouped call."""
+    torch, binding = gpu
+    dev = torch.device("cuda:0")
+    p, q = 2, 2
+    shapes = [(96, 512), (80, 512), (33, 512), (200, 512), (150, 512), (64, 1280), (16, 130), (48, 512), (40, 512), (24, 512)]
+    acts = {}
+    problems, wants = [], []
+    for i, (N, K) in enumerate(shapes):
+        if K not in acts:
+            a = inputs.bernoulli_codes(9000 + K, inputs.TAG_A, M, K, p)
+            sa = inputs.scales_f16(9000 + K, inputs.TAG_A_SCALE, M)
+            acts[K] = (a, binding.apmm_pack_activations(torch.from_numpy(a).to(dev), p), sa, torch.from_numpy(sa).to(dev))
+        a, ap, sa, sa_dev = acts[K]
+        w = inputs.bernoulli_codes(9100 + i, inputs.TAG_W, N, K, q)
+        sw = inputs.scales_f16(9100 + i, inputs.TAG_W_SCALE, N)
+        problems.append(dict(M=M, N=N, K=K, a_packed=ap, w_packed=binding.apmm_pack_weights(torch.from_numpy(w).to(dev), q),
+                             c_i32=torch.zeros((M, N), dtype=torch.int32, device=dev),
+                             c_f16=torch.zeros((M, N), dtype=torch.float16, device=dev),
+                             w_scale=torch.from_numpy(sw).to(dev), a_scale=sa_dev))
+        want = oracle.gemm_i64(a, w, p, q)
+        wants.append((want, oracle.scale_f64(want, sa.view(np.uint16), sw.view(np.uint16))))
+    binding.apmm_gemm_grouped(problems, p, q)
+    torch.cuda.synchronize()
+    for pr, (want, f) in zip(problems, wants):
+        assert np.array_equal(pr["c_i32"].cpu().numpy().astype(np.int64), want)
+        got = pr["c_f16"].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - f) <= 1e-3 * np.abs(f) + 1e-6)
+    binding.apmm_gemm_grouped([], p, q)                                 # nothing to do
+
+
 def test_extreme_values_hit_the_bound(gpu, oracle):
     """All-ones x all-ones and all-ones x all-zeros reach +-K(2^p-1)(2^q-1)."""
     torch, binding = gpu
