@@ -94,7 +94,7 @@ def main():
     a_codes = torch.from_numpy(data["a_codes"]).to(dev)
     w_codes = torch.from_numpy(data["w_codes"]).to(dev)
     w_packed = binding.apmm_pack_weights(w_codes, q)            # offline
-    a_packed = torch.empty(binding.apmm_packed_bytes(M, K, p), dtype=torch.uint8, device=dev)
+    a_packed = torch.empty(binding.apmm_packed_activation_bytes(M, K, p), dtype=torch.uint8, device=dev)
     c = torch.empty((M, N), dtype=torch.int32, device=dev)
     algo = ALGOS[args.algo]
     operand = "fp4"

@@ -18,8 +18,9 @@
  *    untouched.
  *  - Codes are one uint8 per element, row-major with K contiguous; only the low `bits`
  *    bits are significant, higher bits are ignored.
- *  - Packed buffers are opaque.  Their size is apmm_packed_bytes(); the only contractual
- *    property is apmm_unpack(apmm_pack_*(x)) == x on the low `bits` bits.  They must be
+ *  - Packed buffers are opaque.  Their size is apmm_packed_bytes() for weights and
+ *    apmm_packed_activation_bytes() for activations; the only contractual property is
+ *    apmm_unpack*(apmm_pack_*(x)) == x on the low `bits` bits.  They must be
  *    16-byte aligned (any hipMalloc / PyTorch allocation is).
  */
 #ifndef APMM_H
@@ -56,6 +57,11 @@ typedef enum {
  * to a multiple of 32 and K to a multiple of 512.  Returns 0 for invalid arguments. */
 size_t apmm_packed_bytes(int64_t rows, int64_t K, int bits);
 
+/* Bytes of the packed form of M x K activations of p bits.  Equal to apmm_packed_bytes(M, K, p) except
+ * for p = 3 and 4, whose codes are stored as 6-bit fields, the matrix unit's own operand form, so that
+ * the GEMM needs neither a second sweep of K nor an expansion for them. */
+size_t apmm_packed_activation_bytes(int64_t M, int64_t K, int p);
+
 /* Bytes of scratch apmm_gemm needs for this problem (may be 0). */
 size_t apmm_workspace_bytes(int64_t M, int64_t N, int64_t K, int p, int q);
 
@@ -67,7 +73,7 @@ apmm_status apmm_pack_weights(const uint8_t *w_codes, int64_t N, int64_t K, int 
                               void *w_packed, void *stream);
 
 /* Same transform for the activation matrix (M x K codes of p bits); meant to run online,
- * directly before apmm_gemm on the same stream. */
+ * directly before apmm_gemm on the same stream.  a_packed: apmm_packed_activation_bytes(M, K, p) bytes. */
 apmm_status apmm_pack_activations(const uint8_t *a_codes, int64_t M, int64_t K, int p,
                                   void *a_packed, void *stream);
 
@@ -80,14 +86,17 @@ apmm_status apmm_pack_activations(const uint8_t *a_codes, int64_t M, int64_t K, 
  * zero gets the code of +1 everywhere.  The result is the packed operand apmm_pack_activations would give
  * for those codes, and a_scale is the per-token scale for apmm_gemm's fp16 epilogue.
  *   x_f16    : device, M x K binary16 bit patterns, row-major, finite values
- *   a_packed : device, apmm_packed_bytes(M, K, p) bytes, written entirely
+ *   a_packed : device, apmm_packed_activation_bytes(M, K, p) bytes, written entirely
  *   a_scale  : device, M binary16 bit patterns, written */
 apmm_status apmm_quantize_pack_activations(const uint16_t *x_f16, int64_t M, int64_t K, int p,
                                            void *a_packed, uint16_t *a_scale, void *stream);
 
-/* Inverse of the pack transform (test aid): writes rows x K uint8 codes. */
+/* Inverse of apmm_pack_weights (test aid): writes rows x K uint8 codes. */
 apmm_status apmm_unpack(const void *packed, int64_t rows, int64_t K, int bits,
                         uint8_t *codes, void *stream);
+/* Inverse of apmm_pack_activations (test aid): writes M x K uint8 codes. */
+apmm_status apmm_unpack_activations(const void *a_packed, int64_t M, int64_t K, int p,
+                                    uint8_t *codes, void *stream);
 
 /* Paper Sec. 3.2 (bit-wise MatMul reconstitution) with the recovery of Sec. 4.2 kept on chip.
  *   a_packed : device, packed M x K activations of p bits (from apmm_pack_activations)

@@ -15,8 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libapmm.so")
 ALGO_AUTO, ALGO_VALU_POPCOUNT, ALGO_MFMA_INT8, ALGO_DECODE, ALGO_MFMA_FP4 = 0, 1, 2, 3, 4
 
 EXPORTS = [
-    "apmm_packed_bytes", "apmm_workspace_bytes", "apmm_pack_weights", "apmm_pack_activations",
-    "apmm_quantize_pack_activations", "apmm_unpack", "apmm_gemm", "apmm_gemm_ex", "apmm_gemm_grouped",
+    "apmm_packed_bytes", "apmm_packed_activation_bytes", "apmm_workspace_bytes", "apmm_pack_weights", "apmm_pack_activations",
+    "apmm_quantize_pack_activations", "apmm_unpack", "apmm_unpack_activations", "apmm_gemm", "apmm_gemm_ex", "apmm_gemm_grouped",
     "apmm_status_string", "apmm_last_error", "apmm_version",
 ]
 
@@ -51,6 +51,8 @@ def load():
     i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
     lib.apmm_packed_bytes.restype = ctypes.c_size_t
     lib.apmm_packed_bytes.argtypes = [i64, i64, ci]
+    lib.apmm_packed_activation_bytes.restype = ctypes.c_size_t
+    lib.apmm_packed_activation_bytes.argtypes = [i64, i64, ci]
     lib.apmm_workspace_bytes.restype = ctypes.c_size_t
     lib.apmm_workspace_bytes.argtypes = [i64, i64, i64, ci, ci]
     for name in ("apmm_pack_weights", "apmm_pack_activations"):
@@ -59,8 +61,10 @@ def load():
         fn.argtypes = [vp, i64, i64, ci, vp, vp]
     lib.apmm_quantize_pack_activations.restype = ci
     lib.apmm_quantize_pack_activations.argtypes = [vp, i64, i64, ci, vp, vp, vp]
-    lib.apmm_unpack.restype = ci
-    lib.apmm_unpack.argtypes = [vp, i64, i64, ci, vp, vp]
+    for name in ("apmm_unpack", "apmm_unpack_activations"):
+        fn = getattr(lib, name)
+        fn.restype = ci
+        fn.argtypes = [vp, i64, i64, ci, vp, vp]
     gemm_args = [i64, i64, i64, ci, ci, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.apmm_gemm.restype = ci
     lib.apmm_gemm.argtypes = gemm_args
@@ -102,6 +106,10 @@ def apmm_packed_bytes(rows, K, bits):
     return int(load().apmm_packed_bytes(rows, K, bits))
 
 
+def apmm_packed_activation_bytes(M, K, p):
+    return int(load().apmm_packed_activation_bytes(M, K, p))
+
+
 def apmm_workspace_bytes(M, N, K, p, q):
     return int(load().apmm_workspace_bytes(M, N, K, p, q))
 
@@ -109,7 +117,7 @@ def apmm_workspace_bytes(M, N, K, p, q):
 def _pack(fn_name, codes, bits, out):
     _dev_u8(codes, "codes")
     rows, K = codes.shape
-    nbytes = apmm_packed_bytes(rows, K, bits)
+    nbytes = (apmm_packed_activation_bytes if fn_name == "apmm_pack_activations" else apmm_packed_bytes)(rows, K, bits)
     if out is None:
         out = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=codes.device)
     elif out.numel() * out.element_size() < nbytes:
@@ -133,7 +141,7 @@ def apmm_quantize_pack_activations(x_f16, p, out=None, scale_out=None):
     if x_f16.dtype != torch.float16 or not x_f16.is_cuda or not x_f16.is_contiguous() or x_f16.dim() != 2:
         raise ValueError("x must be a contiguous 2-D float16 CUDA tensor")
     M, K = x_f16.shape
-    nbytes = apmm_packed_bytes(M, K, p)
+    nbytes = apmm_packed_activation_bytes(M, K, p)
     if out is None:
         out = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=x_f16.device)
     elif out.numel() * out.element_size() < nbytes:
@@ -147,8 +155,16 @@ def apmm_quantize_pack_activations(x_f16, p, out=None, scale_out=None):
 
 
 def apmm_unpack(packed, rows, K, bits):
+    """Packed weights -> N x K uint8 codes."""
     codes = torch.empty((rows, K), dtype=torch.uint8, device=packed.device)
     _check(load().apmm_unpack(_ptr(packed), rows, K, bits, _ptr(codes), _stream()))
+    return codes
+
+
+def apmm_unpack_activations(a_packed, M, K, p):
+    """Packed activations -> M x K uint8 codes."""
+    codes = torch.empty((M, K), dtype=torch.uint8, device=a_packed.device)
+    _check(load().apmm_unpack_activations(_ptr(a_packed), M, K, p, _ptr(codes), _stream()))
     return codes
 
 

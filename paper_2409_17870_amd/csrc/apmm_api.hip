@@ -25,14 +25,14 @@ apmm_status fail_hip(hipError_t e, const char *where)
 bool bits_ok(int bits) { return bits >= 1 && bits <= 8; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-apmm_status pack_common(const uint8_t *codes, int64_t rows, int64_t K, int bits, void *packed, void *stream,
-                        const char *what)
+apmm_status pack_common(const uint8_t *codes, int64_t rows, int64_t K, int bits, bool field, void *packed,
+                        void *stream, const char *what)
 {
     if (rows < 0 || K < 1 || !bits_ok(bits)) return fail(APMM_ERR_INVALID_ARG, "pack: rows < 0, K < 1 or bits outside [1, 8]");
     if (rows == 0) return APMM_OK;
     if (!codes || !packed) return fail(APMM_ERR_INVALID_ARG, "pack: null pointer");
     if (!aligned16(packed)) return fail(APMM_ERR_INVALID_ARG, "pack: packed buffer must be 16-byte aligned");
-    hipError_t e = apmm::launch_pack(codes, rows, K, bits, static_cast<uint32_t *>(packed),
+    hipError_t e = apmm::launch_pack(codes, rows, K, bits, field, static_cast<uint32_t *>(packed),
                                      static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail_hip(e, what);
     return APMM_OK;
@@ -50,17 +50,25 @@ size_t apmm_packed_bytes(int64_t rows, int64_t K, int bits)
     return (size_t)rows_p * (size_t)k_p / 8u * (size_t)bits + (size_t)rows_p * 4u;  // planes + row sums
 }
 
+size_t apmm_packed_activation_bytes(int64_t M, int64_t K, int p)
+{
+    if (M < 0 || K < 1 || !bits_ok(p)) return 0;
+    const int64_t rows_p = apmm::round_up(M, apmm::kRowBlock);
+    const int64_t k_p = apmm::round_up(K, apmm::kKPad);
+    return (size_t)rows_p * (size_t)k_p / 8u * (size_t)apmm::activation_slots(p) + (size_t)rows_p * 4u;
+}
+
 size_t apmm_workspace_bytes(int64_t, int64_t, int64_t, int, int) { return 0; }
 
 apmm_status apmm_pack_weights(const uint8_t *w_codes, int64_t N, int64_t K, int q, void *w_packed, void *stream)
 {
-    return pack_common(w_codes, N, K, q, w_packed, stream, "apmm_pack_weights");
+    return pack_common(w_codes, N, K, q, false, w_packed, stream, "apmm_pack_weights");
 }
 
 apmm_status apmm_pack_activations(const uint8_t *a_codes, int64_t M, int64_t K, int p, void *a_packed,
                                   void *stream)
 {
-    return pack_common(a_codes, M, K, p, a_packed, stream, "apmm_pack_activations");
+    return pack_common(a_codes, M, K, p, apmm::activation_field_form(p), a_packed, stream, "apmm_pack_activations");
 }
 
 apmm_status apmm_quantize_pack_activations(const uint16_t *x_f16, int64_t M, int64_t K, int p, void *a_packed,
@@ -72,22 +80,35 @@ apmm_status apmm_quantize_pack_activations(const uint16_t *x_f16, int64_t M, int
     if (!aligned16(a_packed)) return fail(APMM_ERR_INVALID_ARG, "quantize_pack: packed buffer must be 16-byte aligned");
     if ((reinterpret_cast<uintptr_t>(x_f16) & 1u) || (reinterpret_cast<uintptr_t>(a_scale) & 1u))
         return fail(APMM_ERR_INVALID_ARG, "quantize_pack: misaligned binary16 buffer");
-    hipError_t e = apmm::launch_quantize_pack(x_f16, M, K, p, static_cast<uint32_t *>(a_packed), a_scale,
+    hipError_t e = apmm::launch_quantize_pack(x_f16, M, K, p, apmm::activation_field_form(p),
+                                              static_cast<uint32_t *>(a_packed), a_scale,
                                               static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail_hip(e, "apmm_quantize_pack_activations");
     return APMM_OK;
 }
 
-apmm_status apmm_unpack(const void *packed, int64_t rows, int64_t K, int bits, uint8_t *codes, void *stream)
+namespace {
+apmm_status unpack_common(const void *packed, int64_t rows, int64_t K, int bits, bool field, uint8_t *codes, void *stream)
 {
     if (rows < 0 || K < 1 || !bits_ok(bits)) return fail(APMM_ERR_INVALID_ARG, "unpack: rows < 0, K < 1 or bits outside [1, 8]");
     if (rows == 0) return APMM_OK;
     if (!codes || !packed) return fail(APMM_ERR_INVALID_ARG, "unpack: null pointer");
     if (!aligned16(packed)) return fail(APMM_ERR_INVALID_ARG, "unpack: packed buffer must be 16-byte aligned");
-    hipError_t e = apmm::launch_unpack(static_cast<const uint32_t *>(packed), rows, K, bits, codes,
+    hipError_t e = apmm::launch_unpack(static_cast<const uint32_t *>(packed), rows, K, bits, field, codes,
                                        static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail_hip(e, "apmm_unpack");
     return APMM_OK;
+}
+}  // namespace
+
+apmm_status apmm_unpack(const void *packed, int64_t rows, int64_t K, int bits, uint8_t *codes, void *stream)
+{
+    return unpack_common(packed, rows, K, bits, false, codes, stream);
+}
+
+apmm_status apmm_unpack_activations(const void *a_packed, int64_t M, int64_t K, int p, uint8_t *codes, void *stream)
+{
+    return unpack_common(a_packed, M, K, p, apmm::activation_field_form(p), codes, stream);
 }
 
 }  // extern "C"
@@ -120,7 +141,8 @@ apmm_status check_gemm(int64_t M, int64_t N, int64_t K, int p, int q, const void
     g.p = p; g.q = q;
     g.a = static_cast<const uint32_t *>(a_packed);
     g.w = static_cast<const uint32_t *>(w_packed);
-    g.a_sum = reinterpret_cast<const int32_t *>(g.a + apmm::row_sum_word(apmm::round_up(M, apmm::kRowBlock), g.nkb, p));
+    g.a_sum = reinterpret_cast<const int32_t *>(
+        g.a + apmm::row_sum_word(apmm::round_up(M, apmm::kRowBlock), g.nkb, apmm::activation_slots(p)));
     g.w_sum = reinterpret_cast<const int32_t *>(g.w + apmm::row_sum_word(apmm::round_up(N, apmm::kRowBlock), g.nkb, q));
     g.c_i32 = c_i32; g.c_f16 = c_f16;
     g.w_scale = w_scale; g.a_scale = a_scale;

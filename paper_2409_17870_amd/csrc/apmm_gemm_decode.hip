@@ -385,6 +385,7 @@ hipError_t launch_decode_mfma(const GroupArgs &ga, hipStream_t stream)
 int decode_variant(const GemmArgs &g)
 {
     if (g.M < 1 || g.M > 16 || g.q < 1 || g.q > 4) return 0;
+    if (activation_field_form(g.p)) return 0;  // 3- and 4-bit activations are laid out for the large-tile MFMA kernel
     if (decode_mfma_supported(g)) return 100;
     return decode_lds_bytes(g, decode_mt(g.M)) <= (size_t)kMaxLdsBytes ? decode_mt(g.M) : 0;
 }

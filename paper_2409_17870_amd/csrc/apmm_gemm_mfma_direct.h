@@ -16,6 +16,10 @@
 // partial sum stays below 2^24 (checked on the host), hence exact in any order.  Nothing but C reaches
 // global memory (paper Sec. 4.2).
 //
+// Activations of 3 or 4 bits arrive in the field form (apmm_layout.h): their packed words ARE the E2M3 (fp6)
+// operand, a 4-bit code u being the number u / 8, and the matrix unit multiplies fp6 by fp4 at the fp4 rate.
+// They need no expansion and no sweep per activation group: K is swept once per weight group.
+//
 // Data movement: no LDS.  On gfx950 a wave that owns its SIMD alone has about 17 issue cycles per
 // 32-cycle MFMA for everything else; a ds_read_b128 costs ~20 and a ds_write_b128 ~40 of them, a VALU
 // instruction 4.  Staging expanded tiles through LDS therefore costs more issue time than letting each of
@@ -47,12 +51,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
 {
     static_assert(P >= 1 && P <= 4 && Q >= 1 && Q <= 4, "instantiated for codes of up to four bits");
     static_assert(SPLIT == 1 || SPLIT == 2, "one or two phases");
+    constexpr bool AF = activation_field_form(P);  // activations are ready-made fp6 operands
+    constexpr int SLOTS_A = activation_slots(P);
     constexpr int WMP = WM / SPLIT;          // row blocks per phase
     constexpr int BM = 64 * WM, BN = 64 * WN;
     constexpr int KS = 4;                    // MFMA k steps per stage
     constexpr int PER_KS = WMP * WN;         // MFMAs per k step
+    constexpr int FRAG0 = AF ? WMP : 0;      // first fragment that needs expanding (A blocks come first)
     constexpr int FRAGS = WMP + WN;          // operand fragments per k step
-    constexpr int TASKS = 4 * FRAGS;         // expansion dwords per k step
+    constexpr int TASKS = 4 * (FRAGS - FRAG0);  // expansion dwords per k step
     static_assert(TASKS % PER_KS == 0, "expansion tasks must spread evenly over the MFMAs of a k step");
     constexpr int TPM = TASKS / PER_KS;      // tasks per MFMA
     constexpr int PHASE_ELEMS = WMP * WN * 16;                  // outputs per lane and phase
@@ -78,7 +85,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
     for (int bi = 0; bi < WM; ++bi) {
         int64_t row = m0 + (wave_m * WM + bi) * 32 + r32;
         if (row >= rows_a) row = rows_a - 1;  // rows past the operand: read a valid row, never stored
-        pa_src[bi] = reinterpret_cast<const uint4 *>(g.a + tile_row_word(row, kh, g.nkb, P, 0));
+        pa_src[bi] = reinterpret_cast<const uint4 *>(g.a + tile_row_word(row, kh, g.nkb, SLOTS_A, 0));
     }
 #pragma unroll
     for (int bj = 0; bj < WN; ++bj) {
@@ -87,7 +94,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
         pb_src[bj] = reinterpret_cast<const uint4 *>(g.w + tile_row_word(row, kh, g.nkb, Q, 0));
     }
     constexpr int kSlotVec = kPlaneWords / 4;                                    // uint4 between slots of a tile
-    constexpr int kStageVecA = 2 * P * kSlotVec, kStageVecB = 2 * Q * kSlotVec;  // uint4 per stage (2 k blocks)
+    constexpr int kStageVecA = 2 * SLOTS_A * kSlotVec, kStageVecB = 2 * Q * kSlotVec;  // uint4 per stage (2 k blocks)
 
     // Accumulator layout of the 32x32 MFMA: lane l, register v holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
     const int64_t m_lane = m0 + wave_m * WM * 32 + kh * 4, n_lane = n0 + wave_n * WN * 32 + r32;
@@ -121,7 +128,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
         }
     };
 
-    uint4 ra[2][WMP][2], rb[2][WN][2];  // raw words of a group (a single group uses [0] only), by stage parity
+    uint4 ra[2][WMP][AF ? 6 : 2], rb[2][WN][2];  // raw words of a group (a single group uses [0] only; the field
+                                                 // form all six slots), by stage parity
     v4i af[2][WMP], bf[2][WN];          // expanded fragments, by k step parity
     const int64_t nst = g.nkb / 2;      // the packed K is a multiple of 512: an even number of whole stages
 
@@ -150,8 +158,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
 #pragma unroll
             for (int bi = 0; bi < WMP; ++bi) {
                 const uint4 *src = pa_src[ph * WMP + bi];
-                ra[buf][bi][0] = src[st * kStageVecA + slot_a * kSlotVec];
-                if constexpr (!AS) ra[buf][bi][1] = src[st * kStageVecA + (slot_a + 1) * kSlotVec];
+                if constexpr (AF) {
+#pragma unroll
+                    for (int sl = 0; sl < 6; ++sl) ra[buf][bi][sl] = src[st * kStageVecA + sl * kSlotVec];
+                } else {
+                    ra[buf][bi][0] = src[st * kStageVecA + slot_a * kSlotVec];
+                    if constexpr (!AS) ra[buf][bi][1] = src[st * kStageVecA + (slot_a + 1) * kSlotVec];
+                }
             }
 #pragma unroll
             for (int bj = 0; bj < WN; ++bj) {
@@ -164,8 +177,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
             constexpr int buf = decltype(buf_c)::value, ks = decltype(ks_c)::value, f = decltype(f_c)::value,
                           d = decltype(d_c)::value;
             if constexpr (f < WMP) {
-                if constexpr (AS) af[ks & 1][f][d] = (int)fp4_single_dword<ks, d>(ra[buf][f][0]);
-                else af[ks & 1][f][d] = (int)fp4_pair_dword<ks, d>(ra[buf][f][0], ra[buf][f][1]);
+                if constexpr (AF) {
+                    // nothing to expand
+                } else if constexpr (AS) {
+                    af[ks & 1][f][d] = (int)fp4_single_dword<ks, d>(ra[buf][f][0]);
+                } else {
+                    af[ks & 1][f][d] = (int)fp4_pair_dword<ks, d>(ra[buf][f][0], ra[buf][f][1]);
+                }
             } else {
                 if constexpr (BS) bf[ks & 1][f - WMP][d] = (int)fp4_single_dword<ks, d>(rb[buf][f - WMP][0]);
                 else bf[ks & 1][f - WMP][d] = (int)fp4_pair_dword<ks, d>(rb[buf][f - WMP][0], rb[buf][f - WMP][1]);
@@ -181,16 +199,31 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
             static_for<KS * PER_KS>([&](auto i_c) __attribute__((always_inline)) {
                 constexpr int i = decltype(i_c)::value;
                 constexpr int ks = i / PER_KS, j = i % PER_KS, bi = j / WN, bj = j % WN;
-                const v4i a = af[ks & 1][bi], b = bf[ks & 1][bj];
-                const v8i a8 = {a[0], a[1], a[2], a[3], 0, 0, 0, 0}, b8 = {b[0], b[1], b[2], b[3], 0, 0, 0, 0};
-                // formats 4 / 4 = E2M1 for both operands; the scales are E8M0 exponents (127 = 2^0)
-                acc[ph][bi][bj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                    a8, b8, acc[ph][bi][bj], 4, 4, 0, exp_a + (AS ? fp4_single_exponent(ks) : 0), 0,
-                    exp_b + (BS ? fp4_single_exponent(ks) : 0));
+                const v4i b = bf[ks & 1][bj];
+                const v8i b8 = {b[0], b[1], b[2], b[3], 0, 0, 0, 0};
+                // operand formats: 4 = E2M1, 2 = E2M3; the scales are E8M0 exponents (127 = 2^0)
+                if constexpr (AF) {
+                    // words 6 ks .. 6 ks + 5 of the lane's 24 raw words
+                    auto raw = [&](auto w_c) __attribute__((always_inline)) {
+                        constexpr int w = 6 * ks + decltype(w_c)::value;
+                        return (int)vec_word<w & 3>(ra[buf][bi][w >> 2]);
+                    };
+                    const v8i a8 = {raw(std::integral_constant<int, 0>{}), raw(std::integral_constant<int, 1>{}),
+                                    raw(std::integral_constant<int, 2>{}), raw(std::integral_constant<int, 3>{}),
+                                    raw(std::integral_constant<int, 4>{}), raw(std::integral_constant<int, 5>{}), 0, 0};
+                    acc[ph][bi][bj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        a8, b8, acc[ph][bi][bj], 2, 4, 0, exp_a, 0, exp_b + (BS ? fp4_single_exponent(ks) : 0));
+                } else {
+                    const v4i a = af[ks & 1][bi];
+                    const v8i a8 = {a[0], a[1], a[2], a[3], 0, 0, 0, 0};
+                    acc[ph][bi][bj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        a8, b8, acc[ph][bi][bj], 4, 4, 0, exp_a + (AS ? fp4_single_exponent(ks) : 0), 0,
+                        exp_b + (BS ? fp4_single_exponent(ks) : 0));
+                }
                 // this MFMA's share of the next k step's operands (after the last step: step 0 of stage st+1)
                 static_for<TPM>([&](auto t_c) __attribute__((always_inline)) {
                     constexpr int task = j * TPM + decltype(t_c)::value;
-                    using F = std::integral_constant<int, task / 4>;
+                    using F = std::integral_constant<int, FRAG0 + task / 4>;
                     using D = std::integral_constant<int, task % 4>;
                     if constexpr (ks + 1 < KS)
                         expand(buf_c, std::integral_constant<int, ks + 1>{}, F{}, D{});
@@ -205,8 +238,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
         };
         load_stage(I0{}, 0);
         // fragments of (stage 0, k step 0)
-        static_for<FRAGS>([&](auto f_c) __attribute__((always_inline)) {
-            static_for<4>([&](auto d_c) __attribute__((always_inline)) { expand(I0{}, I0{}, f_c, d_c); });
+        static_for<FRAGS - FRAG0>([&](auto f_c) __attribute__((always_inline)) {
+            using F = std::integral_constant<int, FRAG0 + decltype(f_c)::value>;
+            static_for<4>([&](auto d_c) __attribute__((always_inline)) { expand(I0{}, I0{}, F{}, d_c); });
         });
         int64_t st = 0;
         if constexpr (STORES) {
@@ -232,6 +266,16 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
             st_ptr = reinterpret_cast<char *>(g.c_i32 + (m_lane + (ph - 1) * WMP * 32) * g.N + n_lane);
         // the first sweep of a later phase carries the stores of the phase before it
         using First = std::integral_constant<bool, (ph > 0)>;
+        if constexpr (AF) {
+            // one sweep per weight group; (ua / 8)(uw / 2) 2^6 = 4 ua uw
+            if constexpr (pair_groups(Q) > 0) {
+                sweep(ph_c, First{}, F{}, F{}, 0, 0, 130, 130);
+                for (int hb = 1; hb < pair_groups(Q); ++hb) sweep(ph_c, F{}, F{}, F{}, 0, 2 * hb, 130, 130 + 2 * hb);
+                if constexpr (has_single_group(Q)) sweep(ph_c, F{}, F{}, T{}, 0, Q - 1, 130, 130 + Q - 1);
+            } else {
+                sweep(ph_c, First{}, F{}, T{}, 0, 0, 130, 130);
+            }
+        } else
         // pair x pair, pair x single, single x pair, single x single
         if constexpr (pair_groups(P) > 0) {
             if constexpr (pair_groups(Q) > 0) {
@@ -318,7 +362,7 @@ template <int P, int Q, int WM, int WN>
 inline bool direct_split_usable(const GemmArgs &g)
 {
     constexpr int store_stages = (WM / 2) * WN * 16 / (4 * (WM / 2) * WN / kStoreEvery);
-    constexpr int sweeps = ((P + 1) / 2) * ((Q + 1) / 2);
+    constexpr int sweeps = (activation_field_form(P) ? 1 : (P + 1) / 2) * ((Q + 1) / 2);
     const int64_t nst = g.nkb / 2;
     return g.c_i32 && !g.c_f16 && g.M % (64 * WM) == 0 && g.N % (64 * WN) == 0 && nst >= store_stages &&
            sweeps * nst <= 16;

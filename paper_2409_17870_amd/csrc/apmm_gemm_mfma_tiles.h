@@ -12,12 +12,16 @@ template <int P, int Q>
 hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream)
 {
     struct Cand { int bm, bn; double cost; };
-    const Cand cands[4] = {{256, 256, 1.0}, {256, 128, 1.2}, {128, 256, 1.2}, {128, 128, 1.2}};
+    // activations in the field form need 24 raw registers per row block: only the tiles with two row blocks
+    // per wave are built for them (the others are given a cost no choice survives)
+    constexpr bool AF = activation_field_form(P);
+    const Cand cands[4] = {{256, 256, AF ? 1e9 : 1.0}, {256, 128, AF ? 1e9 : 1.2}, {128, 256, AF ? 1.0 : 1.2},
+                           {128, 128, AF ? 1.15 : 1.2}};
     int best = 0;
     double best_t = 0;
     static const char *forced = std::getenv("APMM_MFMA_TILE");
     static const char *no_split = std::getenv("APMM_MFMA_SPLIT");
-    if (forced && forced[0] >= '0' && forced[0] <= '3') {
+    if (forced && forced[0] >= '0' && forced[0] <= '3' && !(AF && forced[0] < '2')) {
         best = forced[0] - '0';
     } else {
         for (int c = 0; c < 4; ++c) {
@@ -29,15 +33,21 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream)
             }
         }
     }
-    switch (best) {
-    case 0:
-        // APMM_MFMA_SPLIT=0 forces the one-phase kernel (debugging)
-        if (direct_split_usable<P, Q, 4, 4>(g) && !(no_split && no_split[0] == '0'))
-            return launch_direct_variant<P, Q, 4, 4, 2>(g, stream);
-        return launch_direct_variant<P, Q, 4, 4>(g, stream);
-    case 1: return launch_direct_variant<P, Q, 4, 2>(g, stream);
-    case 2: return launch_direct_variant<P, Q, 2, 4>(g, stream);
-    default: return launch_direct_variant<P, Q, 2, 2>(g, stream);
+    if constexpr (AF) {
+        (void)no_split;
+        if (best == 2) return launch_direct_variant<P, Q, 2, 4>(g, stream);
+        return launch_direct_variant<P, Q, 2, 2>(g, stream);
+    } else {
+        switch (best) {
+        case 0:
+            // APMM_MFMA_SPLIT=0 forces the one-phase kernel (debugging)
+            if (direct_split_usable<P, Q, 4, 4>(g) && !(no_split && no_split[0] == '0'))
+                return launch_direct_variant<P, Q, 4, 4, 2>(g, stream);
+            return launch_direct_variant<P, Q, 4, 4>(g, stream);
+        case 1: return launch_direct_variant<P, Q, 4, 2>(g, stream);
+        case 2: return launch_direct_variant<P, Q, 2, 4>(g, stream);
+        default: return launch_direct_variant<P, Q, 2, 2>(g, stream);
+        }
     }
 }
 

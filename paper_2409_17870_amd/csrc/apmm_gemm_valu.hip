@@ -34,6 +34,23 @@ __device__ __forceinline__ uint32_t plane_half_word(const uint32_t *tile_row, in
     return ((l[0] >> ks) & 0x11111111u) | (((l[1] >> ks) & 0x11111111u) << 2);
 }
 
+// The same from activations in the field form (3 and 4 bits): bit i of field 8 t + 2 c + jh of k step ks is
+// bit 6 (8 t + 2 c + jh) + i of the 192 bits in words 6 ks .. 6 ks + 5 of the row's 24.
+__device__ __forceinline__ uint32_t field_plane_half_word(const uint32_t *tile_row, int i, int w)
+{
+    const int ks = w >> 1, tp = w & 1;
+    uint32_t out = 0;
+    for (int tt = 0; tt < 2; ++tt)
+        for (int jh = 0; jh < 2; ++jh)
+            for (int c = 0; c < 4; ++c) {
+                const int bit = 6 * (8 * (2 * tp + tt) + 2 * c + jh) + i;
+                const int word = 6 * ks + (bit >> 5);
+                const uint32_t v = tile_row[(word >> 2) * kPlaneWords + (word & 3)];
+                out |= ((v >> (bit & 31)) & 1u) << (8 * c + 4 * jh + 2 * tt);
+            }
+    return out;
+}
+
 __global__ __launch_bounds__(kTile * kTile) void gemm_valu_kernel(GemmArgs g)
 {
     const int64_t n = (int64_t)blockIdx.x * kTile + threadIdx.x;
@@ -43,14 +60,15 @@ __global__ __launch_bounds__(kTile * kTile) void gemm_valu_kernel(GemmArgs g)
 
     uint32_t weighted = 0;  // sum_ij 2^(i+j) popcount, modulo 2^32 (the true C fits 32 bits)
     for (int64_t kb = 0; kb < g.nkb; ++kb) {
-        const uint32_t *arow = g.a + tile_row_word(m, kb, g.nkb, p, 0);
+        const uint32_t *arow = g.a + tile_row_word(m, kb, g.nkb, activation_slots(p), 0);
         const uint32_t *wrow = g.w + tile_row_word(n, kb, g.nkb, q, 0);
         for (int w = 0; w < 8; ++w) {
             uint32_t wp[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) wp[i] = i < q ? plane_half_word(wrow, q, i, w) : 0u;
             for (int j = 0; j < p; ++j) {
-                const uint32_t ap = plane_half_word(arow, p, j, w);
+                const uint32_t ap = activation_field_form(p) ? field_plane_half_word(arow, j, w)
+                                                              : plane_half_word(arow, p, j, w);
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
                     if (i < q) weighted += (uint32_t)__popc(ap ^ wp[i]) << (i + j);

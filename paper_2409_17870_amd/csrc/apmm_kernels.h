@@ -6,12 +6,13 @@
 namespace apmm {
 
 // Paper Sec. 4.1: decomposition into planes, reassembly into 32-bit words, concatenation.
-hipError_t launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits, uint32_t *packed,
+// `field`: the field form of 3- and 4-bit activations instead of the group form (apmm_layout.h).
+hipError_t launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits, bool field, uint32_t *packed,
                        hipStream_t stream);
 // Paper Sec. 3.1 + 4.1: per-row symmetric quantisation of binary16 features fused with the packing.
-hipError_t launch_quantize_pack(const uint16_t *x, int64_t rows, int64_t K, int bits, uint32_t *packed,
+hipError_t launch_quantize_pack(const uint16_t *x, int64_t rows, int64_t K, int bits, bool field, uint32_t *packed,
                                 uint16_t *scale, hipStream_t stream);
-hipError_t launch_unpack(const uint32_t *packed, int64_t rows, int64_t K, int bits, uint8_t *codes,
+hipError_t launch_unpack(const uint32_t *packed, int64_t rows, int64_t K, int bits, bool field, uint8_t *codes,
                          hipStream_t stream);
 
 // Design B: plane pairs by XOR + popcount on the vector ALU (any p, q in 1..8).

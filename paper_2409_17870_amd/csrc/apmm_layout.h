@@ -33,6 +33,14 @@
 //     the same 16 elements with two shift-and-mask steps, so any two planes can be compared.
 // Both operands of a GEMM use the same element -> (ks, t, jh, c) map, which is all a contraction needs.
 //
+// Activations of 3 or 4 bits use a second form, the FIELD form: six slots per (row, k block), i.e. 24
+// words, six per k step ks (words 6 ks .. 6 ks + 5 of the row's 24, slot w / 4, word w % 4).  The 192 bits
+// of a k step hold its 32 codes as 6-bit fields, field 8 t + 2 c + jh at bits 6 (8 t + 2 c + jh) ..., code in
+// the low bits: exactly the E2M3 (fp6) MFMA operand of that k step, in which a 4-bit code u is the number
+// u / 8.  The matrix unit multiplies fp6 and fp4 operands at the same rate, so 4-bit activations need no
+// second sweep of K and no expansion at all, at the price of 6 instead of 4 bits per element in a buffer
+// that lives for one GEMM (weights always keep the compact group form).
+//
 // Behind the tiles follows one int32 per (padded) row: the sum of the row's codes over the padded K.
 // The MFMA kernels multiply codes u instead of values 2u - (2^n - 1) and need these sums to recover C.
 //
@@ -55,6 +63,10 @@ inline __host__ __device__ int64_t round_up(int64_t x, int64_t m) { return (x + 
 // number of pair groups of an n-bit code, and whether a single group follows them
 inline __host__ __device__ constexpr int pair_groups(int n) { return n / 2; }
 inline __host__ __device__ constexpr bool has_single_group(int n) { return (n & 1) != 0; }
+
+// activations of 3 or 4 bits are stored in the field form (six slots), everything else in the group form
+inline __host__ __device__ constexpr bool activation_field_form(int p) { return p == 3 || p == 4; }
+inline __host__ __device__ constexpr int activation_slots(int p) { return activation_field_form(p) ? 6 : p; }
 
 // index of word g=0 of (row, slot s) in k block kb
 inline __host__ __device__ int64_t tile_row_word(int64_t row, int64_t kb, int64_t nkb, int n, int s)

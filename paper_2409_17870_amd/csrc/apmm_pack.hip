@@ -66,9 +66,41 @@ __device__ __forceinline__ void pack_group(uint32_t *__restrict__ packed, int64_
     }
 }
 
+// The same for the field form of 3- and 4-bit activations (apmm_layout.h): the 32 codes of the group
+// become the 192-bit E2M3 operand of k step ks, field 8 t + 2 c + jh at bit 6 (8 t + 2 c + jh).
+__device__ __forceinline__ uint64_t spread_bytes_12(uint32_t x)
+{
+    // byte c of x -> bits 12 c .. 12 c + 7
+    return (uint64_t)((x & 0xffu) | ((x & 0xff00u) << 4) | ((x & 0xff0000u) << 8)) | ((uint64_t)(x >> 24) << 36);
+}
+
+__device__ __forceinline__ void pack_group_fields(uint32_t *__restrict__ packed, int64_t row, int64_t nkb, int64_t kg,
+                                                  const uint32_t (&d)[8], uint32_t &sum)
+{
+#pragma unroll
+    for (int t4 = 0; t4 < 8; ++t4) sum = __builtin_amdgcn_sad_u8(d[t4], 0u, sum);
+    const int64_t kb = kg / kWordsPerRow;
+    const int ks = (int)(kg % kWordsPerRow);
+    uint64_t chunk[4];  // the 48 bits of t = 0..3
+#pragma unroll
+    for (int t = 0; t < 4; ++t) chunk[t] = spread_bytes_12(d[2 * t]) | (spread_bytes_12(d[2 * t + 1]) << 6);
+    const uint32_t dw0 = (uint32_t)chunk[0], dw1 = (uint32_t)(chunk[0] >> 32) | ((uint32_t)chunk[1] << 16),
+                   dw2 = (uint32_t)(chunk[1] >> 16), dw3 = (uint32_t)chunk[2],
+                   dw4 = (uint32_t)(chunk[2] >> 32) | ((uint32_t)chunk[3] << 16), dw5 = (uint32_t)(chunk[3] >> 16);
+    // words 6 ks .. 6 ks + 5 of the row's 24: slot w / 4, word w % 4
+    uint32_t *base = packed + tile_row_word(row, kb, nkb, 6, 0) + 3 * (ks >> 1) * kPlaneWords;
+    if ((ks & 1) == 0) {
+        *reinterpret_cast<uint4 *>(base) = make_uint4(dw0, dw1, dw2, dw3);
+        *reinterpret_cast<uint2 *>(base + kPlaneWords) = make_uint2(dw4, dw5);
+    } else {
+        *reinterpret_cast<uint2 *>(base + kPlaneWords + 2) = make_uint2(dw0, dw1);
+        *reinterpret_cast<uint4 *>(base + 2 * kPlaneWords) = make_uint4(dw2, dw3, dw4, dw5);
+    }
+}
+
 __global__ __launch_bounds__(kThreads) void pack_kernel(const uint8_t *__restrict__ codes, int64_t rows,
                                                         int64_t K, int bits, uint32_t *__restrict__ packed,
-                                                        int64_t rows_p, int64_t nkb)
+                                                        int64_t rows_p, int64_t nkb, bool field)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * kRowsPerWg + (threadIdx.x >> 6);
@@ -114,12 +146,17 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const uint8_t *__restric
         const bool second = kg + 64 < groups;
         load_group(kg, d0);
         if (second) load_group(kg + 64, d1);
-        pack_group(packed, row, nkb, bits, kg, d0, sum);
-        if (second) pack_group(packed, row, nkb, bits, kg + 64, d1, sum);
+        if (field) {
+            pack_group_fields(packed, row, nkb, kg, d0, sum);
+            if (second) pack_group_fields(packed, row, nkb, kg + 64, d1, sum);
+        } else {
+            pack_group(packed, row, nkb, bits, kg, d0, sum);
+            if (second) pack_group(packed, row, nkb, bits, kg + 64, d1, sum);
+        }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
-    if (lane == 0) packed[row_sum_word(rows_p, nkb, bits) + row] = sum;
+    if (lane == 0) packed[row_sum_word(rows_p, nkb, field ? 6 : bits) + row] = sum;
 }
 
 // Fused quantise + pack (paper Sec. 3.1: the feature matrix is quantised onto the symmetric bipolar-INT
@@ -138,7 +175,7 @@ __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(const uint16_t 
                                                                  int64_t K, int bits,
                                                                  uint32_t *__restrict__ packed,
                                                                  uint16_t *__restrict__ scale_out, int64_t rows_p,
-                                                                 int64_t nkb)
+                                                                 int64_t nkb, bool field)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * kRowsPerWg + (threadIdx.x >> 6);
@@ -225,7 +262,8 @@ __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(const uint16_t 
             }
             d[t4] = v;
         }
-        pack_group(packed, row, nkb, bits, kg, d, sum);
+        if (field) pack_group_fields(packed, row, nkb, kg, d, sum);
+        else pack_group(packed, row, nkb, bits, kg, d, sum);
     };
     auto fill_group = [&](int64_t kg) __attribute__((always_inline)) {
         // a whole group of padding (every plane bit set) or a padding row (zero words)
@@ -233,7 +271,8 @@ __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(const uint16_t 
         const uint32_t fill = live ? 0x01010101u * top : 0u;
 #pragma unroll
         for (int t4 = 0; t4 < 8; ++t4) d[t4] = fill;
-        pack_group(packed, row, nkb, bits, kg, d, sum);
+        if (field) pack_group_fields(packed, row, nkb, kg, d, sum);
+        else pack_group(packed, row, nkb, bits, kg, d, sum);
     };
     // The four lanes that pack a k block together must take the same call: a k block with any live group
     // quantises all four of its groups (elements past K become padding codes inside quantize_group).
@@ -264,12 +303,12 @@ __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(const uint16_t 
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
-    if (lane == 0) packed[row_sum_word(rows_p, nkb, bits) + row] = sum;
+    if (lane == 0) packed[row_sum_word(rows_p, nkb, field ? 6 : bits) + row] = sum;
 }
 
 __global__ __launch_bounds__(kThreads) void unpack_kernel(const uint32_t *__restrict__ packed, int64_t rows,
                                                           int64_t K, int bits, uint8_t *__restrict__ codes,
-                                                          int64_t nkb)
+                                                          int64_t nkb, bool field)
 {
     const int64_t groups = nkb * kWordsPerRow;
     const int64_t th = (int64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -282,7 +321,29 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(const uint32_t *__rest
     uint32_t d[8];
 #pragma unroll
     for (int t4 = 0; t4 < 8; ++t4) d[t4] = 0u;
-    for (int h = 0; h < pair_groups(bits); ++h) {
+    if (field) {
+        // words 6 ks .. 6 ks + 5 of the row's 24 hold the 32 six-bit fields of this group
+        const uint32_t *base = packed + tile_row_word(row, kb, nkb, 6, 0);
+        uint32_t dw[6];
+#pragma unroll
+        for (int i = 0; i < 6; ++i) {
+            const int w = 6 * ks + i;
+            dw[i] = base[(w >> 2) * kPlaneWords + (w & 3)];
+        }
+        const uint64_t chunk[4] = {(uint64_t)dw[0] | ((uint64_t)(dw[1] & 0xffffu) << 32),
+                                   (uint64_t)(dw[1] >> 16) | ((uint64_t)dw[2] << 16),
+                                   (uint64_t)dw[3] | ((uint64_t)(dw[4] & 0xffffu) << 32),
+                                   (uint64_t)(dw[4] >> 16) | ((uint64_t)dw[5] << 16)};
+        const uint32_t code_mask = (1u << bits) - 1u;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int jh = 0; jh < 2; ++jh)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    d[2 * t + jh] |= ((uint32_t)(chunk[t] >> (12 * c + 6 * jh)) & code_mask) << (8 * c);
+    }
+    for (int h = 0; !field && h < pair_groups(bits); ++h) {
         const uint32_t *src = packed + tile_row_word(row, kb, nkb, bits, 2 * h + (ks >> 1)) + 2 * (ks & 1);
 #pragma unroll
         for (int tp = 0; tp < 2; ++tp) {
@@ -294,7 +355,7 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(const uint32_t *__rest
                     d[2 * (2 * tp + tt) + jh] |= ((word >> (4 * jh + 2 * tt)) & 0x03030303u) << (2 * h);
         }
     }
-    if (has_single_group(bits)) {
+    if (!field && has_single_group(bits)) {
         const uint32_t *src = packed + tile_row_word(row, kb, nkb, bits, bits - 1);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -314,7 +375,7 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(const uint32_t *__rest
 
 }  // namespace
 
-hipError_t launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits, uint32_t *packed,
+hipError_t launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits, bool field, uint32_t *packed,
                        hipStream_t stream)
 {
     const int64_t rows_p = round_up(rows, kRowBlock);
@@ -323,11 +384,11 @@ hipError_t launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits, 
     const int64_t blocks = (rows_p + kRowsPerWg - 1) / kRowsPerWg;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(pack_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, codes, rows, K, bits,
-                       packed, rows_p, nkb);
+                       packed, rows_p, nkb, field);
     return hipGetLastError();
 }
 
-hipError_t launch_quantize_pack(const uint16_t *x, int64_t rows, int64_t K, int bits, uint32_t *packed,
+hipError_t launch_quantize_pack(const uint16_t *x, int64_t rows, int64_t K, int bits, bool field, uint32_t *packed,
                                 uint16_t *scale, hipStream_t stream)
 {
     const int64_t rows_p = round_up(rows, kRowBlock);
@@ -336,11 +397,11 @@ hipError_t launch_quantize_pack(const uint16_t *x, int64_t rows, int64_t K, int 
     const int64_t blocks = (rows_p + kRowsPerWg - 1) / kRowsPerWg;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(quantize_pack_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, x, rows, K, bits,
-                       packed, scale, rows_p, nkb);
+                       packed, scale, rows_p, nkb, field);
     return hipGetLastError();
 }
 
-hipError_t launch_unpack(const uint32_t *packed, int64_t rows, int64_t K, int bits, uint8_t *codes,
+hipError_t launch_unpack(const uint32_t *packed, int64_t rows, int64_t K, int bits, bool field, uint8_t *codes,
                          hipStream_t stream)
 {
     const int64_t nkb = round_up(K, kKPad) / kKBlock;
@@ -349,7 +410,7 @@ hipError_t launch_unpack(const uint32_t *packed, int64_t rows, int64_t K, int bi
     const int64_t blocks = (total + kThreads - 1) / kThreads;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, packed, rows, K, bits,
-                       codes, nkb);
+                       codes, nkb, field);
     return hipGetLastError();
 }
 

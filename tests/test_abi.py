@@ -48,6 +48,11 @@ def test_packed_bytes(lib):
     assert lib.apmm_packed_bytes(1, 1, 1) == 32 * 512 // 8 + 32 * 4  # padded to 32 rows x 512 k
     assert lib.apmm_packed_bytes(4096, 4096, 2) == 4096 * 4096 * 2 // 8 + 4096 * 4
     assert lib.apmm_packed_bytes(33, 129, 3) == 64 * 512 * 3 // 8 + 64 * 4
+    # activations of 3 and 4 bits are stored as 6-bit fields, all others like weights
+    assert lib.apmm_packed_activation_bytes(33, 129, 3) == 64 * 512 * 6 // 8 + 64 * 4
+    assert lib.apmm_packed_activation_bytes(33, 129, 4) == 64 * 512 * 6 // 8 + 64 * 4
+    for bits in (1, 2, 5, 8):
+        assert lib.apmm_packed_activation_bytes(33, 129, bits) == lib.apmm_packed_bytes(33, 129, bits)
     assert lib.apmm_packed_bytes(0, 128, 2) == 0
     assert lib.apmm_packed_bytes(8, 128, 0) == 0 and lib.apmm_packed_bytes(8, 128, 9) == 0
     assert lib.apmm_packed_bytes(-1, 128, 2) == 0 and lib.apmm_packed_bytes(8, 0, 2) == 0

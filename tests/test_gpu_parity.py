@@ -55,7 +55,7 @@ def algos_for(case):
     algos = [VALU]
     if case["p"] <= 4 and case["q"] <= 4:
         algos.append(FP4)
-    if case["M"] <= 16 and case["q"] <= 4:
+    if case["M"] <= 16 and case["q"] <= 4 and case["p"] not in (3, 4):
         algos.append(DECODE)
     return algos + [0]
 
@@ -68,10 +68,12 @@ def test_pack_unpack_roundtrip(gpu, rows, K, bits):
     rng = np.random.default_rng(rows * 7919 + K * 13 + bits)
     codes = rng.integers(0, 256, size=(rows, K), dtype=np.uint8)     # high bits are dirt
     dev_codes = torch.from_numpy(codes).to("cuda:0")
-    for pack in (binding.apmm_pack_weights, binding.apmm_pack_activations):
+    for pack, size, unpack in ((binding.apmm_pack_weights, binding.apmm_packed_bytes, binding.apmm_unpack),
+                               (binding.apmm_pack_activations, binding.apmm_packed_activation_bytes,
+                                binding.apmm_unpack_activations)):
         packed = pack(dev_codes, bits)
-        assert packed.numel() == binding.apmm_packed_bytes(rows, K, bits)
-        back = binding.apmm_unpack(packed, rows, K, bits).cpu().numpy()
+        assert packed.numel() == size(rows, K, bits)
+        back = unpack(packed, rows, K, bits).cpu().numpy()
         assert np.array_equal(back, codes & ((1 << bits) - 1))
 
 
@@ -129,7 +131,23 @@ def test_wide_codes(gpu, oracle, p, q):
     assert np.array_equal(c32.astype(np.int64), want)
 
 
-@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (3, 3), (4, 4), (8, 2), (1, 4)])
+@pytest.mark.parametrize("p,q", [(3, 3), (4, 4), (4, 1), (3, 2)])
+@pytest.mark.parametrize("M", [1, 7, 16])
+def test_few_tokens_with_field_form_activations(gpu, oracle, M, p, q):
+    """3- and 4-bit activations are laid out for the large-tile MFMA kernel: the decode kernels decline,
+    automatic selection still serves few tokens."""
+    torch, binding = gpu
+    case = dict(M=M, N=203, K=1100, p=p, q=q, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 5500 + 100 * M + 10 * p + q)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+    with pytest.raises(binding.ApmmError):
+        run_case(gpu, data, case, algo=DECODE)
+    c32, c16 = run_case(gpu, data, case, algo=0)
+    assert np.array_equal(c32.astype(np.int64), want)
+    check_f16(c16, want, data, oracle)
+
+
+@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (5, 3), (2, 4), (8, 2), (1, 4), (6, 4)])
 @pytest.mark.parametrize("M", [1, 2, 3, 5, 8, 13, 16])
 def test_decode_kernel_all_token_counts(gpu, oracle, M, p, q):
     """Small-M kernel: every token-count bucket, ragged N and K, odd plane counts."""
@@ -187,7 +205,7 @@ def test_quantize_pack_matches_the_oracle(gpu, oracle, M, K, p):
         x[3] = 0                                                       # a row of zeros: scale 0, code of +1
     want_codes, want_scale = oracle.quantize_rows(x, p)
     packed, scale = binding.apmm_quantize_pack_activations(torch.from_numpy(x).to("cuda:0"), p)
-    codes = binding.apmm_unpack(packed, M, K, p).cpu().numpy()
+    codes = binding.apmm_unpack_activations(packed, M, K, p).cpu().numpy()
     assert np.array_equal(scale.cpu().numpy().view(np.uint16), want_scale)
     assert np.array_equal(codes, want_codes)
     # the packed operand is the one apmm_pack_activations gives for those codes (row sums included)
