@@ -111,6 +111,30 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
         const float ct = (float)(int32_t)((uint32_t)g.K * ca * cw - 2u * ca * (uint32_t)g.w_sum[n]);
         b_init[bj] = kh == 0 ? 1.0f : ct;
     }
+    // Scales of the fp16 epilogue, requested now so that their latency is gone by the time they are needed:
+    // sw[bj] for this lane's columns; the token scales of the wave's 32 * WM rows one row per lane (row
+    // lane + 64 i in sa_rows[i]), handed to the lanes that need them by a lane permute in the epilogue.
+    // (kept as binary16 pairs through the k loop: registers are scarce there; 0x3c00 = 1.0)
+    uint32_t sw_raw[(WN + 1) / 2], sa_raw[(WM + 3) / 4];
+#pragma unroll
+    for (int i = 0; i < (WN + 1) / 2; ++i) sw_raw[i] = 0x3c003c00u;
+#pragma unroll
+    for (int i = 0; i < (WM + 3) / 4; ++i) sa_raw[i] = 0x3c003c00u;
+    if (g.c_f16) {
+#pragma unroll
+        for (int bj = 0; bj < WN; ++bj) {
+            const int64_t n = n_lane + bj * 32;
+            const uint32_t h = (g.w_scale && n < g.N) ? g.w_scale[n] : 0x3c00u;
+            sw_raw[bj / 2] = (bj & 1) ? (sw_raw[bj / 2] & 0xffffu) | (h << 16) : (sw_raw[bj / 2] & 0xffff0000u) | h;
+        }
+#pragma unroll
+        for (int i = 0; i < (WM + 1) / 2; ++i) {
+            const int64_t m = m0 + wave_m * WM * 32 + lane + 64 * i;
+            const uint32_t h = (g.a_scale && m < g.M && lane + 64 * i < 32 * WM) ? g.a_scale[m] : 0x3c00u;
+            sa_raw[i / 2] = (i & 1) ? (sa_raw[i / 2] & 0xffffu) | (h << 16) : (sa_raw[i / 2] & 0xffff0000u) | h;
+        }
+    }
+
     auto init_phase = [&](auto ph_c) __attribute__((always_inline)) {
         constexpr int ph = decltype(ph_c)::value;
         v16f zero;
@@ -306,51 +330,78 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
         }
     });
 
-    // Store of the last phase.  The output mode and the border test are uniform over the workgroup, so one
-    // of six straight-line store sequences is chosen instead of testing per element.
+    // Store of the last phase.  The output mode and the border test are uniform over the workgroup, so
+    // straight-line store sequences are chosen per output instead of testing per element.
     constexpr int LAST = SPLIT - 1;
     const int64_t m_last = m_lane + LAST * WMP * 32;
-    float sw[WN];
-#pragma unroll
-    for (int bj = 0; bj < WN; ++bj) {
-        const int64_t n = n_lane + bj * 32;
-        sw[bj] = (g.w_scale && n < g.N) ? half_bits_to_float(g.w_scale[n]) : 1.0f;
-    }
-    auto emit = [&](auto guard_c, auto i32_c, auto f16_c) __attribute__((always_inline)) {
-        constexpr bool GUARD = decltype(guard_c)::value, I32 = decltype(i32_c)::value, F16 = decltype(f16_c)::value;
+    // PAIR (interior tiles, even N, 4-byte aligned fp16 output): neighbouring lanes hold neighbouring columns,
+    // and a 2-byte store per lane writes 64-byte runs, which the memory system handles far worse than 128-byte
+    // runs (a 16 MiB fp16 output cost 7 us that way).  Rows are taken in pairs: the even lane of a lane pair
+    // collects both columns of the first row, the odd lane both columns of the second row (one lane exchange),
+    // and each stores one dword.
+    auto emit = [&](auto guard_c, auto i32_c, auto f16_c, auto pair_c) __attribute__((always_inline)) {
+        constexpr bool GUARD = decltype(guard_c)::value, I32 = decltype(i32_c)::value, F16 = decltype(f16_c)::value,
+                       PAIR = decltype(pair_c)::value;
         int32_t *ci = I32 ? g.c_i32 + m_last * g.N + n_lane : nullptr;
         uint16_t *ch = F16 ? g.c_f16 + m_last * g.N + n_lane : nullptr;
+        const bool odd = lane & 1;
+        // odd lanes write the row below at the column to the left
+        uint16_t *ch_pair = F16 ? ch + (odd ? g.N - 1 : 0) : nullptr;
+        // token scale of row (block bi of the last phase, register v) of this lane, from the lane that loaded it
+        auto token_scale = [&](int bi, int v) __attribute__((always_inline)) {
+            const int blk = LAST * WMP + bi;  // row block inside the wave tile: rows 64 (blk / 2) + lane were loaded
+            const int src = (blk & 1) * 32 + 8 * (v / 4) + 4 * kh + (v % 4);
+            const uint32_t both = (uint32_t)__shfl((int)sa_raw[blk / 4], src);
+            return half_bits_to_float((uint16_t)((blk / 2) & 1 ? both >> 16 : both & 0xffffu));
+        };
+        float sw[WN];
+#pragma unroll
+        for (int bj = 0; bj < WN; ++bj)
+            sw[bj] = half_bits_to_float((uint16_t)((bj & 1) ? sw_raw[bj / 2] >> 16 : sw_raw[bj / 2] & 0xffffu));
 #pragma unroll
         for (int bi = 0; bi < WMP; ++bi) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t row = (int64_t)(bi * 32 + 8 * (v / 4) + (v % 4));  // relative to m_last
+                // the lane permutes come before any lane leaves the iteration: a lane that has left supplies nothing
+                const float sa = F16 ? token_scale(bi, v) : 1.0f;
+                const float sa_next = (F16 && PAIR && v % 2 == 0) ? token_scale(bi, v + 1) : 1.0f;
                 if (GUARD && m_last + row >= g.M) continue;
-                float sa = 1.0f;
-                if constexpr (F16) sa = g.a_scale ? half_bits_to_float(g.a_scale[m_last + row]) : 1.0f;
 #pragma unroll
                 for (int bj = 0; bj < WN; ++bj) {
                     if (GUARD && n_lane + bj * 32 >= g.N) continue;
                     const float c = acc[LAST][bi][bj][v];  // = C, an integer
                     if constexpr (I32) ci[row * g.N + bj * 32] = (int32_t)c;
-                    if constexpr (F16) ch[row * g.N + bj * 32] = float_to_half_bits(c * sa * sw[bj]);
+                    if constexpr (F16 && !PAIR) ch[row * g.N + bj * 32] = float_to_half_bits(c * sa * sw[bj]);
+                    if constexpr (F16 && PAIR) {
+                        if (v % 2 == 0) {  // folds once the loop is unrolled
+                            const uint32_t h0 = float_to_half_bits(c * sa * sw[bj]);
+                            const uint32_t h1 = float_to_half_bits(acc[LAST][bi][bj][(v + 1) & 15] * sa_next * sw[bj]);
+                            const uint32_t give = odd ? h0 : h1, keep = odd ? h1 : h0;
+                            // quad_perm [1, 0, 3, 2]: the value of the other lane of the pair
+                            const uint32_t got = (uint32_t)__builtin_amdgcn_mov_dpp((int)give, 0xB1, 0xf, 0xf, true);
+                            const uint32_t word = odd ? (got | (keep << 16)) : (keep | (got << 16));
+                            *reinterpret_cast<uint32_t *>(ch_pair + row * g.N + bj * 32) = word;
+                        }
+                    }
                 }
             }
         }
     };
     if constexpr (SPLIT > 1) {
-        emit(F{}, T{}, F{});  // interior tiles, int32 output only (checked by the launcher)
+        emit(F{}, T{}, F{}, F{});  // interior tiles, int32 output only (checked by the launcher)
     } else {
         const bool interior = (m0 + BM <= g.M) && (n0 + BN <= g.N);
-        const bool i32 = g.c_i32 != nullptr, f16 = g.c_f16 != nullptr;
-        if (interior) {
-            if (i32 && !f16) emit(F{}, T{}, F{});
-            else if (!i32 && f16) emit(F{}, F{}, T{});
-            else emit(F{}, T{}, T{});
-        } else {
-            if (i32 && !f16) emit(T{}, T{}, F{});
-            else if (!i32 && f16) emit(T{}, F{}, T{});
-            else emit(T{}, T{}, T{});
+        const bool pair = (g.N & 1) == 0 && (reinterpret_cast<uintptr_t>(g.c_f16) & 3u) == 0;
+        // both outputs: one pass per output (a combined pass needs more registers than there are)
+        if (g.c_i32) {
+            if (interior) emit(F{}, T{}, F{}, F{});
+            else emit(T{}, T{}, F{}, F{});
+        }
+        if (g.c_f16) {
+            if (interior && pair) emit(F{}, F{}, T{}, T{});
+            else if (interior) emit(F{}, F{}, T{}, F{});
+            else emit(T{}, F{}, T{}, F{});
         }
     }
 }
