@@ -87,3 +87,35 @@ def test_argument_errors_come_before_any_launch(lib):
     assert lib.apmm_pack_activations(0x1000, 4, 128, 0, 0x2000, None) == INVALID
     assert lib.apmm_pack_weights(None, 0, 128, 2, None, None) == 0  # empty operand
     assert lib.apmm_unpack(None, 3, 128, 2, None, None) == INVALID
+
+
+def test_new_entry_points_check_their_arguments(lib):
+    """Fused quantise + pack, activation unpack and the grouped call reject bad arguments on the host."""
+    from paper_2409_17870_amd.binding import ApmmProblem
+    INVALID, OVERFLOW = 1, 3
+    q = lib.apmm_quantize_pack_activations
+    assert q(None, 4, 128, 2, 0x2000, 0x3000, None) == INVALID
+    assert q(0x1000, 4, 128, 2, None, 0x3000, None) == INVALID
+    assert q(0x1000, 4, 128, 2, 0x2000, None, None) == INVALID
+    assert q(0x1000, 4, 0, 2, 0x2000, 0x3000, None) == INVALID
+    assert q(0x1000, 4, 128, 9, 0x2000, 0x3000, None) == INVALID
+    assert q(0x1001, 4, 128, 2, 0x2000, 0x3000, None) == INVALID       # binary16 data at an odd address
+    assert q(0x1000, 0, 128, 2, 0x2000, 0x3000, None) == 0             # no rows: nothing to do
+    assert lib.apmm_unpack_activations(None, 3, 128, 4, None, None) == INVALID
+    grouped = lib.apmm_gemm_grouped
+    grouped.argtypes = [ctypes.c_int, ctypes.POINTER(ApmmProblem), ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                        ctypes.c_size_t, ctypes.c_void_p]
+    assert grouped(0, None, 2, 2, None, 0, None) == 0
+    assert grouped(2, None, 2, 2, None, 0, None) == INVALID
+    assert grouped(-1, None, 2, 2, None, 0, None) == INVALID
+    arr = (ApmmProblem * 2)()
+    for pr in arr:
+        pr.M, pr.N, pr.K, pr.a_packed, pr.w_packed, pr.c_i32 = 4, 8, 128, 0x1000, 0x2000, 0x3000
+    arr[1].c_i32 = None                                                 # second entry asks for no output
+    assert grouped(2, arr, 2, 2, None, 0, None) == INVALID              # nothing is launched for the first either
+    arr[1].c_i32, arr[1].K = 0x3000, 40000
+    assert grouped(2, arr, 8, 8, None, 0, None) == OVERFLOW
+    arr[1].K, arr[1].M = 128, 0                                         # an empty entry is skipped; the other would launch
+    big = (ApmmProblem * 300)()
+    assert grouped(300, big, 2, 2, None, 0, None) == INVALID            # more entries than one call takes
+
