@@ -47,7 +47,7 @@ typedef enum {
     APMM_ALGO_AUTO = 0,
     APMM_ALGO_VALU_POPCOUNT = 1, /* plane pairs by XOR + popcount on the vector ALU, D_ij = K - 2*popc */
     APMM_ALGO_MFMA_INT8 = 2,     /* reserved: the int8 MFMA kernel of earlier builds; this build answers APMM_ERR_UNSUPPORTED */
-    APMM_ALGO_DECODE = 3,        /* small-M (M <= 16) weight-streaming kernel */
+    APMM_ALGO_DECODE = 3,        /* small-M weight-streaming kernels: M <= 16, and M <= 64 for p, q <= 2 */
     APMM_ALGO_MFMA_FP4 = 4       /* plane groups recombined to E2M1 codes in registers, f8f6f4 MFMA, exact fp32 accumulate
                                     (p, q <= 4 and 4 * roundup(K,512) * (2^p-1)(2^q-1) < 2^24) */
 } apmm_algo;
@@ -140,7 +140,7 @@ typedef struct apmm_problem {
  * linears are small enough that the launch, not the data, bounds them: the q/k/v or gate/up
  * projections of one decoder layer at a few tokens share their activations and can go in one launch).
  * `problems` is a HOST array of `count` entries, read before the call returns.  Each entry obeys the
- * rules of apmm_gemm and gives the same result as apmm_gemm on it.  Problems with M <= 16 that the same
+ * rules of apmm_gemm and gives the same result as apmm_gemm on it.  Small-M problems that the same
  * small-M kernel covers are launched eight at a time; all others are launched one by one.  The outputs
  * of different entries must not overlap.  At most 256 entries.  On an argument error nothing is launched. */
 apmm_status apmm_gemm_grouped(int count, const apmm_problem *problems, int p, int q,

@@ -154,8 +154,8 @@ constexpr int kMaxProblems = 256;  // entries of one apmm_gemm_grouped call
 apmm_status run_gemm(const apmm::GemmArgs &g, int algo, hipStream_t s)
 {
     if (algo == APMM_ALGO_AUTO) {
-        if (g.M <= 16 && apmm::gemm_decode_supported(g)) algo = APMM_ALGO_DECODE;
-        else if (g.M > 16 && apmm::gemm_mfma_fp4_supported(g)) algo = APMM_ALGO_MFMA_FP4;
+        if (apmm::gemm_decode_supported(g)) algo = APMM_ALGO_DECODE;
+        else if (apmm::gemm_mfma_fp4_supported(g)) algo = APMM_ALGO_MFMA_FP4;
         else algo = APMM_ALGO_VALU_POPCOUNT;
     }
     hipError_t e;
@@ -223,7 +223,7 @@ apmm_status apmm_gemm_grouped(int count, const apmm_problem *problems, int p, in
         // longest run (up to kMaxGroup) that one small-M launch covers
         int run = 1;
         while (i + run < live && run < apmm::kMaxGroup && apmm::gemm_decode_group_supported(args + i, run + 1)) ++run;
-        if (run > 1 || (args[i].M <= 16 && apmm::gemm_decode_group_supported(args + i, 1))) {
+        if (run > 1 || apmm::gemm_decode_group_supported(args + i, 1)) {
             hipError_t e = apmm::launch_gemm_decode_group(args + i, run, s);
             if (e != hipSuccess) return fail_hip(e, "apmm_gemm_grouped");
         } else {

@@ -186,14 +186,14 @@ size_t decode_lds_bytes(const GemmArgs &g, int mt)
 int decode_mt(int64_t M) { return M <= 1 ? 1 : M <= 2 ? 2 : M <= 4 ? 4 : M <= 8 ? 8 : 16; }
 
 // Builds the launch descriptor of `count` problems (16 output channels per workgroup each).
-bool make_group(const GemmArgs *gs, int count, GroupArgs &ga)
+bool make_group(const GemmArgs *gs, int count, int rows_per_wg, GroupArgs &ga)
 {
     if (count < 1 || count > kMaxGroup) return false;
     int64_t end = 0;
     ga.count = count;
     for (int i = 0; i < kMaxGroup; ++i) {
         const GemmArgs &g = gs[i < count ? i : count - 1];
-        if (i < count) end += (g.N + kRowsPerWg - 1) / kRowsPerWg;
+        if (i < count) end += (g.N + rows_per_wg - 1) / rows_per_wg;
         if (end > 0x7fffffffLL) return false;
         ga.wg_end[i] = (int)end;
         ga.g[i] = g;
@@ -236,18 +236,21 @@ hipError_t launch_mt(const GroupArgs &ga, hipStream_t stream)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Small-M kernel on the matrix unit (3 <= M <= 16, p, q <= 2).  With more than a couple of tokens
+// Small-M kernel on the matrix unit (3 <= M <= 64, p, q <= 2).  With more than a couple of tokens
 // the XOR/popcount form needs 2 p q M lane-operations per weight word and becomes VALU bound; the
 // E2M1 MFMA needs one expansion of the weight words (1.25 - 1.5 operations per 8 codes) whatever M is.
-// Same split of the work (16 output channels per workgroup, 8 waves over K, lane = weight row l % 16
-// and k block l / 16 of four), same algebra as the large-M MFMA kernel:
+// Same split of the work (8 waves over K, lane = weight row l % 16 and k block l / 16 of four), same
+// algebra as the large-M MFMA kernel:
 //   v_mfma_scale_f32_16x16x128_f8f6f4: A = 16 weight rows x 128 k, B = 128 k x 16 tokens, codes as E2M1;
 //   MFMA ks of an iteration multiplies k step ks of the four k blocks held by the four lane groups;
+//   a workgroup owns RT tiles of 16 output channels and all TT tiles of 16 tokens: a weight fragment is
+//   expanded once and multiplied with TT token fragments, a token fragment with RT weight fragments;
 //   the packed activations of all K are copied once per workgroup into LDS as they are, [k block][token][slot],
 //   and expanded where they are used; C = acc - 2 cw PA[m] - 2 ca PW[n] + K ca cw with the packed row sums
 //   (the operand scales make acc = 4 S).
+// RT = 2 halves the number of workgroups (and of activation copies) when there are plenty of output channels.
 // ---------------------------------------------------------------------------------------------
-template <int P, int Q>
+template <int P, int Q, int TT, int RT>
 __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga)
 {
     // which problem of the launch this workgroup works on (uniform over the workgroup)
@@ -257,136 +260,207 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga
     const GemmArgs g = ga.g[idx];
     const int block = (int)blockIdx.x - (idx ? ga.wg_end[idx - 1] : 0);
     static_assert(P <= 2 && Q <= 2, "one plane group per operand");
+    constexpr int TOKENS = 16 * TT, ROWS = kRowsPerWg * RT;
+    constexpr int OUTS = (TT * RT * 256 + kThreads - 1) / kThreads;  // outputs per thread
+    constexpr uint32_t ca = (1u << P) - 1, cw = (1u << Q) - 1;
     extern __shared__ __align__(16) uint8_t lds_raw[];
-    uint4 *a_lds = reinterpret_cast<uint4 *>(lds_raw);  // [kb][token < 16][slot < P]: packed words as they are
+    uint4 *a_lds = reinterpret_cast<uint4 *>(lds_raw);  // [kb][token < TOKENS][slot < P]: packed words as they are
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t n0 = (int64_t)block * kRowsPerWg;
+    const int64_t n0 = (int64_t)block * ROWS;
     constexpr int kSlotVec = kPlaneWords / 4;
 
     const int r16 = lane & 15, kq = lane >> 4;
     const int64_t rows_b = round_up(g.N, kRowBlock);
-    const int64_t n_ld = n0 + r16 < rows_b ? n0 + r16 : rows_b - 1;
+    int64_t n_ld[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) n_ld[rt] = n0 + rt * 16 + r16 < rows_b ? n0 + rt * 16 + r16 : rows_b - 1;
 
-    // what the final store needs is requested first (see gemm_decode_kernel).
-    // 16x16 accumulator layout: lane l, register v holds row 4*(l/16) + v (weight row), column l%16 (token)
-    const int out_m = tid & 15;
-    const int64_t out_n = n0 + 4 * ((tid & 63) >> 4) + (tid >> 6);
-    const bool out_thread = tid < 256 && out_m < g.M && out_n < g.N;
-    float out_sa = 1.0f, out_sw = 1.0f;
-    uint32_t out_terms = 0;  // - 2 cw PA[m] - 2 ca PW[n] + K ca cw
-    if (out_thread) {
-        constexpr uint32_t ca = (1u << P) - 1, cw = (1u << Q) - 1;
-        out_terms = (uint32_t)g.K * ca * cw - 2u * cw * (uint32_t)g.a_sum[out_m] - 2u * ca * (uint32_t)g.w_sum[out_n];
-        if (g.c_f16) {
-            out_sa = load_scale(g.a_scale, out_m);
-            out_sw = load_scale(g.w_scale, out_n);
+    // What the final store needs is requested first (see gemm_decode_kernel).  Output o of this thread is
+    // element (tile t = (tid + o * kThreads) / 256, register v, lane l) of the accumulators, t = rt * TT + tt;
+    // 16x16 accumulator layout: lane l, register v holds row 4*(l/16) + v (weight row), column l%16 (token).
+    bool out_ok[OUTS];
+    int out_m[OUTS];
+    int64_t out_n[OUTS];
+    float out_sa[OUTS], out_sw[OUTS];
+    uint32_t out_terms[OUTS];  // - 2 cw PA[m] - 2 ca PW[n] + K ca cw
+#pragma unroll
+    for (int o = 0; o < OUTS; ++o) {
+        const int e = tid + o * kThreads, t = e >> 8, v = (e >> 6) & 3, l = e & 63;
+        out_m[o] = (t % TT) * 16 + (l & 15);
+        out_n[o] = n0 + (t / TT) * 16 + 4 * (l >> 4) + v;
+        out_ok[o] = t < TT * RT && out_m[o] < g.M && out_n[o] < g.N;
+        out_sa[o] = out_sw[o] = 1.0f;
+        out_terms[o] = 0;
+        if (out_ok[o]) {
+            out_terms[o] = (uint32_t)g.K * ca * cw - 2u * cw * (uint32_t)g.a_sum[out_m[o]] -
+                           2u * ca * (uint32_t)g.w_sum[out_n[o]];
+            if (g.c_f16) {
+                out_sa[o] = load_scale(g.a_scale, out_m[o]);
+                out_sw[o] = load_scale(g.w_scale, out_n[o]);
+            }
         }
     }
 
     // the weights of the first k block are requested before anything else: their latency is the
     // longest thing in this kernel and overlaps with the copy of the activations
     int64_t kb4 = wave;
-    uint4 wnext[2];
+    uint4 wnext[RT][2];
     if (kb4 * 4 < g.nkb) {
-        const uint4 *wsrc = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld, kb4 * 4 + kq, g.nkb, Q, 0));
 #pragma unroll
-        for (int s = 0; s < Q; ++s) wnext[s] = wsrc[s * kSlotVec];
+        for (int rt = 0; rt < RT; ++rt) {
+            const uint4 *wsrc = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld[rt], kb4 * 4 + kq, g.nkb, Q, 0));
+#pragma unroll
+            for (int s = 0; s < Q; ++s) wnext[rt][s] = wsrc[s * kSlotVec];
+        }
     }
 
-    // activations -> LDS; the 16 tokens of a slot are 256 contiguous bytes
-    const int64_t total_vecs = g.nkb * P * 16;
+    // activations -> LDS; 16 tokens of a slot are 256 contiguous bytes (tokens past M: the last padded row block
+    // holds zero words up to a multiple of 32, tokens beyond it are clamped and never stored)
+    const int64_t rows_a = round_up(g.M, kRowBlock);
+    const int64_t total_vecs = g.nkb * P * TOKENS;
     for (int64_t c = tid; c < total_vecs; c += kThreads) {
-        const int m = (int)(c & 15);
-        const int s = (int)((c >> 4) % P);
-        const int64_t ckb = (c >> 4) / P;
-        a_lds[(ckb * 16 + m) * P + s] = *reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, ckb, g.nkb, P, s));
+        const int m = (int)(c % TOKENS);
+        const int s = (int)((c / TOKENS) % P);
+        const int64_t ckb = (c / TOKENS) / P;
+        const int64_t m_ld = m < rows_a ? m : rows_a - 1;
+        a_lds[(ckb * TOKENS + m) * P + s] = *reinterpret_cast<const uint4 *>(g.a + tile_row_word(m_ld, ckb, g.nkb, P, s));
     }
     __syncthreads();
 
-    mfma::v4f acc = {0.f, 0.f, 0.f, 0.f};
+    mfma::v4f acc[RT][TT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = mfma::v4f{0.f, 0.f, 0.f, 0.f};
     // nkb is a multiple of 4 (K is padded to 512): whole groups of four k blocks
     for (; kb4 * 4 < g.nkb; kb4 += kWaves) {
         const int64_t kb = kb4 * 4 + kq;
-        uint4 wq[2], aq[2];
+        uint4 wq[RT][2], aq[TT][2];
 #pragma unroll
-        for (int s = 0; s < Q; ++s) wq[s] = wnext[s];
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int s = 0; s < Q; ++s) wq[rt][s] = wnext[rt][s];
         if ((kb4 + kWaves) * 4 < g.nkb) {  // next block of this lane
-            const uint4 *wsrc =
-                reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld, kb + 4 * kWaves, g.nkb, Q, 0));
 #pragma unroll
-            for (int s = 0; s < Q; ++s) wnext[s] = wsrc[s * kSlotVec];
+            for (int rt = 0; rt < RT; ++rt) {
+                const uint4 *wsrc =
+                    reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld[rt], kb + 4 * kWaves, g.nkb, Q, 0));
+#pragma unroll
+                for (int s = 0; s < Q; ++s) wnext[rt][s] = wsrc[s * kSlotVec];
+            }
         }
 #pragma unroll
-        for (int s = 0; s < P; ++s) aq[s] = a_lds[(kb * 16 + r16) * P + s];
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int s = 0; s < P; ++s) aq[tt][s] = a_lds[(kb * TOKENS + tt * 16 + r16) * P + s];
         mfma::static_for<4>([&](auto ks_c) __attribute__((always_inline)) {
             constexpr int ks = decltype(ks_c)::value;
-            mfma::v8i a8 = {0, 0, 0, 0, 0, 0, 0, 0}, b8 = {0, 0, 0, 0, 0, 0, 0, 0};
+            mfma::v8i a8[RT], b8[TT];
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) a8[rt] = mfma::v8i{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) b8[tt] = mfma::v8i{0, 0, 0, 0, 0, 0, 0, 0};
             mfma::static_for<4>([&](auto d_c) __attribute__((always_inline)) {
                 constexpr int d = decltype(d_c)::value;
-                if constexpr (Q == 1) a8[d] = (int)mfma::fp4_single_dword<ks, d>(wq[0]);
-                else a8[d] = (int)mfma::fp4_pair_dword<ks, d>(wq[0], wq[1]);
-                if constexpr (P == 1) b8[d] = (int)mfma::fp4_single_dword<ks, d>(aq[0]);
-                else b8[d] = (int)mfma::fp4_pair_dword<ks, d>(aq[0], aq[1]);
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    if constexpr (Q == 1) a8[rt][d] = (int)mfma::fp4_single_dword<ks, d>(wq[rt][0]);
+                    else a8[rt][d] = (int)mfma::fp4_pair_dword<ks, d>(wq[rt][0], wq[rt][1]);
+                }
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    if constexpr (P == 1) b8[tt][d] = (int)mfma::fp4_single_dword<ks, d>(aq[tt][0]);
+                    else b8[tt][d] = (int)mfma::fp4_pair_dword<ks, d>(aq[tt][0], aq[tt][1]);
+                }
             });
             // E8M0 exponents: 2^2 per operand turns (ua/2)(uw/2) into 4 ua uw
-            acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                a8, b8, acc, 4, 4, 0, 129 + (Q == 1 ? mfma::fp4_single_exponent(ks) : 0), 0,
-                129 + (P == 1 ? mfma::fp4_single_exponent(ks) : 0));
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+                    acc[rt][tt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                        a8[rt], b8[tt], acc[rt][tt], 4, 4, 0, 129 + (Q == 1 ? mfma::fp4_single_exponent(ks) : 0), 0,
+                        129 + (P == 1 ? mfma::fp4_single_exponent(ks) : 0));
         });
     }
 
-    // reduce over the waves through LDS: part[wave][v][lane]
+    // reduce over the waves through LDS: part[wave][tile t][v][lane]
     __syncthreads();  // every wave is done reading the activations
     float *part = reinterpret_cast<float *>(lds_raw);
 #pragma unroll
-    for (int v = 0; v < 4; ++v) part[(wave * 4 + v) * 64 + lane] = acc[v];
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) part[((wave * RT * TT + rt * TT + tt) * 4 + v) * 64 + lane] = acc[rt][tt][v];
     __syncthreads();
-    if (out_thread) {
-        const int l = tid & 63, v = tid >> 6;
+#pragma unroll
+    for (int o = 0; o < OUTS; ++o) {
+        if (!out_ok[o]) continue;
+        const int e = tid + o * kThreads;  // = (t * 4 + v) * 64 + l
         float s = 0.f;
 #pragma unroll
-        for (int w8 = 0; w8 < kWaves; ++w8) s += part[(w8 * 4 + v) * 64 + l];
-        store_output(g, out_m, out_n, (int32_t)((uint32_t)(int32_t)s + out_terms), out_sa, out_sw);
+        for (int w8 = 0; w8 < kWaves; ++w8) s += part[w8 * RT * TT * 256 + e];
+        store_output(g, out_m[o], out_n[o], (int32_t)((uint32_t)(int32_t)s + out_terms[o]), out_sa[o], out_sw[o]);
     }
 }
 
-size_t decode_mfma_lds_bytes(const GemmArgs &g)
+int decode_token_tiles(int64_t M) { return M <= 16 ? 1 : M <= 32 ? 2 : 4; }
+
+size_t decode_mfma_lds_bytes(const GemmArgs &g, int rt)
 {
-    const size_t a_bytes = (size_t)g.nkb * 16 * 16 * g.p;
-    const size_t part_bytes = (size_t)kWaves * 4 * 64 * 4;
+    const int tt = decode_token_tiles(g.M);
+    const size_t a_bytes = (size_t)g.nkb * 16 * tt * 16 * g.p;
+    const size_t part_bytes = (size_t)kWaves * rt * tt * 256 * 4;
     return a_bytes > part_bytes ? a_bytes : part_bytes;
 }
 
 bool decode_mfma_supported(const GemmArgs &g)
 {
-    return g.M >= 3 && g.M <= 16 && g.p <= 2 && g.q <= 2 && decode_mfma_lds_bytes(g) <= (size_t)kMaxLdsBytes &&
+    return g.M >= 3 && g.M <= 64 && g.p <= 2 && g.q <= 2 && decode_mfma_lds_bytes(g, 2) <= (size_t)kMaxLdsBytes &&
            4 * g.nkb * kKBlock * 9 < (1 << 24);
 }
 
-template <int P, int Q>
-hipError_t launch_decode_mfma_pq(const GroupArgs &ga, hipStream_t stream)
+template <int P, int Q, int TT, int RT>
+hipError_t launch_decode_mfma_v(const GroupArgs &ga, hipStream_t stream)
 {
     size_t lds = 0;
-    for (int i = 0; i < ga.count; ++i) lds = lds > decode_mfma_lds_bytes(ga.g[i]) ? lds : decode_mfma_lds_bytes(ga.g[i]);
+    for (int i = 0; i < ga.count; ++i)
+        lds = lds > decode_mfma_lds_bytes(ga.g[i], RT) ? lds : decode_mfma_lds_bytes(ga.g[i], RT);
     static bool attr_set = false;
-    return launch_group(gemm_decode_mfma_kernel<P, Q>, attr_set, ga, lds, stream);
+    return launch_group(gemm_decode_mfma_kernel<P, Q, TT, RT>, attr_set, ga, lds, stream);
 }
 
-hipError_t launch_decode_mfma(const GroupArgs &ga, hipStream_t stream)
+template <int P, int Q>
+hipError_t launch_decode_mfma_pq(const GroupArgs &ga, int tt, int rt, hipStream_t stream)
 {
-    const int p = ga.g[0].p, q = ga.g[0].q;
-    if (p == 1 && q == 1) return launch_decode_mfma_pq<1, 1>(ga, stream);
-    if (p == 1 && q == 2) return launch_decode_mfma_pq<1, 2>(ga, stream);
-    if (p == 2 && q == 1) return launch_decode_mfma_pq<2, 1>(ga, stream);
-    return launch_decode_mfma_pq<2, 2>(ga, stream);
+    if (rt == 2) {
+        if (tt == 1) return launch_decode_mfma_v<P, Q, 1, 2>(ga, stream);
+        if (tt == 2) return launch_decode_mfma_v<P, Q, 2, 2>(ga, stream);
+        return launch_decode_mfma_v<P, Q, 4, 2>(ga, stream);
+    }
+    if (tt == 1) return launch_decode_mfma_v<P, Q, 1, 1>(ga, stream);
+    if (tt == 2) return launch_decode_mfma_v<P, Q, 2, 1>(ga, stream);
+    return launch_decode_mfma_v<P, Q, 4, 1>(ga, stream);
 }
 
-// kernel variant that serves a problem: 0 = none, 100 = matrix unit, else the token tile of the XOR/popcount kernel
+hipError_t launch_decode_mfma(const GroupArgs &ga, int rt, hipStream_t stream)
+{
+    const int p = ga.g[0].p, q = ga.g[0].q, tt = decode_token_tiles(ga.g[0].M);
+    if (p == 1 && q == 1) return launch_decode_mfma_pq<1, 1>(ga, tt, rt, stream);
+    if (p == 1 && q == 2) return launch_decode_mfma_pq<1, 2>(ga, tt, rt, stream);
+    if (p == 2 && q == 1) return launch_decode_mfma_pq<2, 1>(ga, tt, rt, stream);
+    return launch_decode_mfma_pq<2, 2>(ga, tt, rt, stream);
+}
+
+// kernel variant that serves a problem: 0 = none, 100 + token tiles = matrix unit, else the token tile of the
+// XOR/popcount kernel
 int decode_variant(const GemmArgs &g)
 {
-    if (g.M < 1 || g.M > 16 || g.q < 1 || g.q > 4) return 0;
+    if (g.M < 1 || g.M > 64 || g.q < 1 || g.q > 4) return 0;
     if (activation_field_form(g.p)) return 0;  // 3- and 4-bit activations are laid out for the large-tile MFMA kernel
-    if (decode_mfma_supported(g)) return 100;
+    if (decode_mfma_supported(g)) return 100 + decode_token_tiles(g.M);
+    if (g.M > 16) return 0;
     return decode_lds_bytes(g, decode_mt(g.M)) <= (size_t)kMaxLdsBytes ? decode_mt(g.M) : 0;
 }
 
@@ -407,9 +481,18 @@ bool gemm_decode_group_supported(const GemmArgs *gs, int count)
 hipError_t launch_gemm_decode_group(const GemmArgs *gs, int count, hipStream_t stream)
 {
     GroupArgs ga;
-    if (!gemm_decode_group_supported(gs, count) || !make_group(gs, count, ga)) return hipErrorInvalidValue;
-    switch (decode_variant(gs[0])) {
-    case 100: return launch_decode_mfma(ga, stream);
+    if (!gemm_decode_group_supported(gs, count)) return hipErrorInvalidValue;
+    const int variant = decode_variant(gs[0]);
+    if (variant > 100) {
+        // two row tiles per workgroup once that still leaves two workgroups per CU
+        int64_t rows = 0;
+        for (int i = 0; i < count; ++i) rows += gs[i].N;
+        const int rt = rows >= 2 * 256 * 2 * kRowsPerWg ? 2 : 1;
+        if (!make_group(gs, count, kRowsPerWg * rt, ga)) return hipErrorInvalidValue;
+        return launch_decode_mfma(ga, rt, stream);
+    }
+    if (!make_group(gs, count, kRowsPerWg, ga)) return hipErrorInvalidValue;
+    switch (variant) {
     case 1: return launch_mt<1>(ga, stream);
     case 2: return launch_mt<2>(ga, stream);
     case 4: return launch_mt<4>(ga, stream);

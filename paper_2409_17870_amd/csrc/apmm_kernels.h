@@ -26,7 +26,7 @@ hipError_t launch_gemm_mfma(const GemmArgs &args, hipStream_t stream);
 bool gemm_mfma_fp4_supported(const GemmArgs &args);
 hipError_t launch_gemm_mfma_fp4(const GemmArgs &args, hipStream_t stream);
 
-// Small-M weight-streaming kernel (M <= 16).
+// Small-M weight-streaming kernels (M <= 16; M <= 64 on the matrix unit for p, q <= 2).
 bool gemm_decode_supported(const GemmArgs &args);
 hipError_t launch_gemm_decode(const GemmArgs &args, hipStream_t stream);
 // Up to kMaxGroup small-M problems of equal p, q in one launch; they must all be covered by the same

@@ -55,7 +55,8 @@ def algos_for(case):
     algos = [VALU]
     if case["p"] <= 4 and case["q"] <= 4:
         algos.append(FP4)
-    if case["M"] <= 16 and case["q"] <= 4 and case["p"] not in (3, 4):
+    if (case["M"] <= 16 and case["q"] <= 4 and case["p"] not in (3, 4)) or \
+            (case["M"] <= 64 and case["p"] <= 2 and case["q"] <= 2):
         algos.append(DECODE)
     return algos + [0]
 
@@ -154,6 +155,30 @@ def test_decode_kernel_all_token_counts(gpu, oracle, M, p, q):
     case = dict(M=M, N=203, K=1100, p=p, q=q, a_dist="bernoulli", scaled=True)
     data = inputs.make_case(case, 5000 + 100 * M + 10 * p + q)
     want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+    c32, c16 = run_case(gpu, data, case, algo=DECODE)
+    assert np.array_equal(c32.astype(np.int64), want)
+    check_f16(c16, want, data, oracle)
+
+
+@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (1, 2), (2, 2)])
+@pytest.mark.parametrize("M", [17, 24, 32, 33, 50, 64])
+def test_decode_kernel_token_tiles(gpu, oracle, M, p, q):
+    """Matrix-unit small-M kernel with two and four tiles of 16 tokens."""
+    case = dict(M=M, N=203, K=1100, p=p, q=q, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 5700 + 100 * M + 10 * p + q)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+    for algo in (DECODE, 0):
+        c32, c16 = run_case(gpu, data, case, algo=algo)
+        assert np.array_equal(c32.astype(np.int64), want)
+        check_f16(c16, want, data, oracle)
+
+
+@pytest.mark.parametrize("M", [5, 40])
+def test_decode_kernel_two_row_tiles_per_workgroup(gpu, oracle, M):
+    """Enough output channels for the variant whose workgroups own 32 channels; ragged N."""
+    case = dict(M=M, N=16421, K=300, p=2, q=2, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 5900 + M)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], 2, 2)
     c32, c16 = run_case(gpu, data, case, algo=DECODE)
     assert np.array_equal(c32.astype(np.int64), want)
     check_f16(c16, want, data, oracle)
