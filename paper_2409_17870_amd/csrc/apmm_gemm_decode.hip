@@ -4,15 +4,18 @@
 //   D_ij = K - 2 * popcount(a^(j) xor w^(i)),   C = sum_ij 2^(i+j) D_ij
 //        = K (2^p - 1)(2^q - 1) - 2 * sum_ij 2^(i+j) popcount(a^(j) xor w^(i)).
 // Padded k positions hold equal bits in both operands and drop out of the popcounts.  The
-// shift-and-add recovery runs in registers, the reduction over K in registers, DPP-free lane
-// shuffles and LDS; only C reaches global memory (paper Sec. 4.2).
+// shift-and-add recovery runs in registers, the reduction over K in registers, lane shuffles
+// and LDS; only C reaches global memory (paper Sec. 4.2).
+//
+// Every kernel of this file takes a group descriptor: several problems of equal p, q can share one launch
+// (a workgroup finds its problem from a prefix table of workgroup counts).
 //
 // Work split.  With M <= 16 tokens the weights (N*K*q/8 bytes) are the only real traffic, a few
 // MiB, i.e. a few KiB per CU: the kernel is latency bound, so everything is loaded up front with
 // as many waves as possible.
 //   workgroup : 16 output channels (half a packed row block), 8 waves
 //   wave      : k blocks 4*(w + 8*t) .. +3, t = 0, 1, ...
-//   lane l    : weight row l % 16, k block l / 16 of the wave's four; it loads the row's q planes
+//   lane l    : weight row l % 16, k block l / 16 of the wave's four; it loads the row's q slots
 //               of that block (q x 16 bytes, 256 contiguous bytes per 16 lanes) straight into registers
 // The activations (M rows, all K) are copied once per workgroup from their packed tiles into LDS with
 // every plane in the common form of the XOR/popcount kernels (16 elements per word at the even bit

@@ -9,9 +9,6 @@ hipError_t launch_gemm_mfma_fp4_p2(const GemmArgs &g, hipStream_t stream);
 hipError_t launch_gemm_mfma_fp4_p3(const GemmArgs &g, hipStream_t stream);
 hipError_t launch_gemm_mfma_fp4_p4(const GemmArgs &g, hipStream_t stream);
 
-bool gemm_mfma_supported(const GemmArgs &) { return false; }
-hipError_t launch_gemm_mfma(const GemmArgs &, hipStream_t) { return hipErrorInvalidValue; }
-
 // The fp32 accumulator runs from the recovery terms to C through integer partial sums; all of them are
 // below 4 K' (2^p - 1)(2^q - 1) in magnitude, which must stay below 2^24 for the sums to be exact.
 bool gemm_mfma_fp4_supported(const GemmArgs &g)

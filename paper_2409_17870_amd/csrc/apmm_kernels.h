@@ -18,11 +18,8 @@ hipError_t launch_unpack(const uint32_t *packed, int64_t rows, int64_t K, int bi
 // Design B: plane pairs by XOR + popcount on the vector ALU (any p, q in 1..8).
 hipError_t launch_gemm_valu(const GemmArgs &args, hipStream_t stream);
 
-// Design A: planes recombined into int8 codes, int8 MFMA (p, q in 1..4).
-bool gemm_mfma_supported(const GemmArgs &args);
-hipError_t launch_gemm_mfma(const GemmArgs &args, hipStream_t stream);
-
-// Design A with E2M1 operands on the f8f6f4 MFMA (p, q in 1..2), twice the int8 rate.
+// Design A: plane groups recombined into E2M1 / E2M3 codes in registers, f8f6f4 MFMA, exact fp32 accumulate
+// (p, q in 1..4 while 4 K (2^p - 1)(2^q - 1) < 2^24).
 bool gemm_mfma_fp4_supported(const GemmArgs &args);
 hipError_t launch_gemm_mfma_fp4(const GemmArgs &args, hipStream_t stream);
 

@@ -28,7 +28,6 @@
 //     every nibble is 00uu with the 2-bit code of the group: 1.5 operations per dword.  For a single
 //     group L[t] & (0x11111111 << ks): the bit stands at another place of the nibble in every k step,
 //     which the MFMA's power-of-two operand scale undoes (1.25 operations per dword).
-//   * int8 MFMA operand: (S[w] >> (4jh + 2tt)) & 0x03030303 leaves four 2-bit codes, one per byte.
 //   * XOR/popcount: (S[w] >> b) & 0x55555555 is plane 2h+b of 16 elements; two single-group words give
 //     the same 16 elements with two shift-and-mask steps, so any two planes can be compared.
 // Both operands of a GEMM use the same element -> (ks, t, jh, c) map, which is all a contraction needs.
