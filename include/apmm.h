@@ -146,6 +146,12 @@ typedef struct apmm_problem {
 apmm_status apmm_gemm_grouped(int count, const apmm_problem *problems, int p, int q,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/* Measurement aid.  The next apmm_gemm / apmm_gemm_ex call of the calling thread, if it runs the large-tile
+ * MFMA kernel, attaches the two hipEvent_t (created by the caller; either may be NULL) to that kernel's
+ * dispatch itself (hipExtLaunchKernel): afterwards they hold the kernel's own begin and end, without the
+ * dispatch gaps that events recorded before and after the call include.  Any other GEMM call drops them. */
+apmm_status apmm_time_next_gemm(void *start_event, void *stop_event);
+
 const char *apmm_status_string(apmm_status status);
 /* Text of the last error on the calling thread ("" if none). */
 const char *apmm_last_error(void);

@@ -17,7 +17,7 @@ ALGO_AUTO, ALGO_VALU_POPCOUNT, ALGO_MFMA_INT8, ALGO_DECODE, ALGO_MFMA_FP4 = 0, 1
 EXPORTS = [
     "apmm_packed_bytes", "apmm_packed_activation_bytes", "apmm_workspace_bytes", "apmm_pack_weights", "apmm_pack_activations",
     "apmm_quantize_pack_activations", "apmm_unpack", "apmm_unpack_activations", "apmm_gemm", "apmm_gemm_ex", "apmm_gemm_grouped",
-    "apmm_status_string", "apmm_last_error", "apmm_version",
+    "apmm_time_next_gemm", "apmm_status_string", "apmm_last_error", "apmm_version",
 ]
 
 
@@ -72,6 +72,8 @@ def load():
     lib.apmm_gemm_ex.argtypes = gemm_args + [ci]
     lib.apmm_gemm_grouped.restype = ci
     lib.apmm_gemm_grouped.argtypes = [ci, ctypes.POINTER(ApmmProblem), ci, ci, vp, ctypes.c_size_t, vp]
+    lib.apmm_time_next_gemm.restype = ci
+    lib.apmm_time_next_gemm.argtypes = [vp, vp]
     lib.apmm_status_string.restype = ctypes.c_char_p
     lib.apmm_status_string.argtypes = [ci]
     lib.apmm_last_error.restype = ctypes.c_char_p
@@ -207,4 +209,10 @@ def apmm_gemm_grouped(problems, p, q):
             t = pr.get(key)
             setattr(arr[i], key, t.data_ptr() if t is not None else None)
     _check(load().apmm_gemm_grouped(len(problems), arr, p, q, None, 0, _stream()))
+
+
+def apmm_time_next_gemm(start_event, stop_event):
+    """Attach two torch.cuda.Event (created with enable_timing=True and recorded once, so that their
+    handles exist) to the kernel dispatch of the next large-tile MFMA GEMM call of this thread."""
+    _check(load().apmm_time_next_gemm(ctypes.c_void_p(start_event.cuda_event), ctypes.c_void_p(stop_event.cuda_event)))
 

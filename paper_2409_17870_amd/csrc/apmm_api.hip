@@ -158,6 +158,7 @@ apmm_status run_gemm(const apmm::GemmArgs &g, int algo, hipStream_t s)
         else if (apmm::gemm_mfma_fp4_supported(g)) algo = APMM_ALGO_MFMA_FP4;
         else algo = APMM_ALGO_VALU_POPCOUNT;
     }
+    if (algo != APMM_ALGO_MFMA_FP4) (void)apmm::take_kernel_timing();  // only that kernel takes timing events
     hipError_t e;
     switch (algo) {
     case APMM_ALGO_VALU_POPCOUNT:
@@ -197,6 +198,12 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
     const apmm_status st = check_gemm(M, N, K, p, q, a_packed, w_packed, c_i32, c_f16, w_scale, a_scale, g, empty);
     if (st != APMM_OK || empty) return st;
     return run_gemm(g, algo, static_cast<hipStream_t>(stream));
+}
+
+apmm_status apmm_time_next_gemm(void *start_event, void *stop_event)
+{
+    apmm::set_kernel_timing(static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event));
+    return APMM_OK;
 }
 
 apmm_status apmm_gemm_grouped(int count, const apmm_problem *problems, int p, int q, void *workspace,

@@ -4,6 +4,17 @@
 
 namespace apmm {
 
+namespace {
+thread_local KernelTiming g_timing = {nullptr, nullptr};
+}
+void set_kernel_timing(hipEvent_t start, hipEvent_t stop) { g_timing = KernelTiming{start, stop}; }
+KernelTiming take_kernel_timing()
+{
+    const KernelTiming t = g_timing;
+    g_timing = KernelTiming{nullptr, nullptr};
+    return t;
+}
+
 hipError_t launch_gemm_mfma_fp4_p1(const GemmArgs &g, hipStream_t stream);
 hipError_t launch_gemm_mfma_fp4_p2(const GemmArgs &g, hipStream_t stream);
 hipError_t launch_gemm_mfma_fp4_p3(const GemmArgs &g, hipStream_t stream);

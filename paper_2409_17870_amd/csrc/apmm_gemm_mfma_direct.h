@@ -33,6 +33,8 @@
 // of the next stage) is interleaved with the MFMAs of step ks; the raw words of the next stage are loaded
 // at the start of the current one (double buffered in registers).
 #pragma once
+#include <hip/hip_ext.h>
+
 #include "apmm_mfma_common.h"
 
 namespace apmm {
@@ -41,9 +43,9 @@ namespace mfma {
 // SPLIT = 1: the wave tile is computed in one go and stored at the end.
 // SPLIT = 2: the wave tile is computed as two halves of WM / 2 row blocks, one after the other (each a full
 // sweep of K), and the int32 stores of the first half are interleaved with the MFMAs of the second half's
-// first kStoreStages stages, one element every other MFMA, so that half of the C traffic (which otherwise
+// first STORE_STAGES stages, one element every other MFMA, so that half of the C traffic (which otherwise
 // keeps the matrix unit idle for 6 - 7 us at 4096^2 outputs) runs under the k loop.  The price is less
-// reuse per expanded fragment.  Used for interior tiles with int32 output only and K >= kStoreStages stages.
+// reuse per expanded fragment.  Used for interior tiles with int32 output only and K of at least STORE_STAGES stages.
 constexpr int kStoreEvery = 2;
 
 template <int P, int Q, int WM, int WN, int SPLIT>
@@ -426,8 +428,13 @@ hipError_t launch_direct_variant(const GemmArgs &g, hipStream_t stream)
     const int64_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int64_t tiles = tiles_m * tiles_n;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((gemm_mfma_direct_kernel<P, Q, WM, WN, SPLIT>), dim3((unsigned)tiles), dim3(256), 0, stream,
-                       g, (int)tiles_n, (int)tiles);
+    const KernelTiming timing = take_kernel_timing();
+    if (timing.start || timing.stop)
+        hipExtLaunchKernelGGL((gemm_mfma_direct_kernel<P, Q, WM, WN, SPLIT>), dim3((unsigned)tiles), dim3(256), 0,
+                              stream, timing.start, timing.stop, 0, g, (int)tiles_n, (int)tiles);
+    else
+        hipLaunchKernelGGL((gemm_mfma_direct_kernel<P, Q, WM, WN, SPLIT>), dim3((unsigned)tiles), dim3(256), 0,
+                           stream, g, (int)tiles_n, (int)tiles);
     return hipGetLastError();
 }
 
