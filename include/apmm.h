@@ -125,6 +125,23 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q,
                          void *workspace, size_t workspace_bytes, void *stream,
                          int algo);
 
+/* apmm_gemm taking the activation codes as they are (paper Sec. 4.1 and 3.2 in one call): `a_codes` is
+ * the device M x K row-major uint8 matrix that apmm_pack_activations would take (bits above p are
+ * ignored, no alignment needed).  Result and all other arguments as in apmm_gemm.
+ *   - For a few tokens the small-M kernels regroup the codes into the packed form on their way into
+ *     on-chip memory: one launch, no packed buffer.  The separate packing launch costs as much as such a
+ *     GEMM.  Taken when the small-M kernels cover the shape (M <= 16 with q <= 4 and p not 3 or 4, or
+ *     M <= 64 with p, q <= 2; all of K must fit on chip) and M * N <= 65536.
+ *   - Otherwise the codes are packed into `workspace` (device, 16-byte aligned, at least
+ *     apmm_packed_activation_bytes(M, K, p) bytes, overwritten) and apmm_gemm runs on that: two launches.
+ * Without such a workspace the call still takes the one-launch path wherever the small-M kernels cover the
+ * shape, and returns APMM_ERR_WORKSPACE (nothing launched) where they do not. */
+apmm_status apmm_gemm_from_codes(int64_t M, int64_t N, int64_t K, int p, int q,
+                                 const uint8_t *a_codes, const void *w_packed,
+                                 int32_t *c_i32, uint16_t *c_f16,
+                                 const uint16_t *w_scale, const uint16_t *a_scale,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
 /* One linear of a grouped call: C = A * W^T with the arguments of apmm_gemm. */
 typedef struct apmm_problem {
     int64_t M, N, K;

@@ -16,7 +16,7 @@ ALGO_AUTO, ALGO_VALU_POPCOUNT, ALGO_MFMA_INT8, ALGO_DECODE, ALGO_MFMA_FP4 = 0, 1
 
 EXPORTS = [
     "apmm_packed_bytes", "apmm_packed_activation_bytes", "apmm_workspace_bytes", "apmm_pack_weights", "apmm_pack_activations",
-    "apmm_quantize_pack_activations", "apmm_unpack", "apmm_unpack_activations", "apmm_gemm", "apmm_gemm_ex", "apmm_gemm_grouped",
+    "apmm_quantize_pack_activations", "apmm_unpack", "apmm_unpack_activations", "apmm_gemm", "apmm_gemm_ex", "apmm_gemm_from_codes", "apmm_gemm_grouped",
     "apmm_time_next_gemm", "apmm_status_string", "apmm_last_error", "apmm_version",
 ]
 
@@ -70,6 +70,8 @@ def load():
     lib.apmm_gemm.argtypes = gemm_args
     lib.apmm_gemm_ex.restype = ci
     lib.apmm_gemm_ex.argtypes = gemm_args + [ci]
+    lib.apmm_gemm_from_codes.restype = ci
+    lib.apmm_gemm_from_codes.argtypes = gemm_args
     lib.apmm_gemm_grouped.restype = ci
     lib.apmm_gemm_grouped.argtypes = [ci, ctypes.POINTER(ApmmProblem), ci, ci, vp, ctypes.c_size_t, vp]
     lib.apmm_time_next_gemm.restype = ci
@@ -189,6 +191,23 @@ def apmm_gemm(M, N, K, p, q, a_packed, w_packed, want_i32=True, want_f16=False, 
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().apmm_gemm_ex(M, N, K, p, q, _ptr(a_packed), _ptr(w_packed), _ptr(c_i32), _ptr(c_f16),
                                _ptr(w_scale), _ptr(a_scale), _ptr(workspace), ws_bytes, _stream(), algo))
+    return c_i32, c_f16
+
+
+def apmm_gemm_from_codes(a_codes, N, p, q, w_packed, want_i32=True, want_f16=False, w_scale=None, a_scale=None,
+                         c_i32=None, c_f16=None, workspace=None):
+    """C = A W^T straight from the M x K uint8 activation codes: one launch for a few tokens, else packing
+    into `workspace` (uint8 tensor of apmm_packed_activation_bytes(M, K, p) bytes) followed by the GEMM."""
+    _dev_u8(a_codes, "a_codes")
+    M, K = a_codes.shape
+    dev = a_codes.device
+    if want_i32 and c_i32 is None:
+        c_i32 = torch.empty((M, N), dtype=torch.int32, device=dev)
+    if want_f16 and c_f16 is None:
+        c_f16 = torch.empty((M, N), dtype=torch.float16, device=dev)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().apmm_gemm_from_codes(M, N, K, p, q, _ptr(a_codes), _ptr(w_packed), _ptr(c_i32), _ptr(c_f16),
+                                       _ptr(w_scale), _ptr(a_scale), _ptr(workspace), ws_bytes, _stream()))
     return c_i32, c_f16
 
 

@@ -118,7 +118,7 @@ namespace {
 // Argument checks of one GEMM; fills `g`.  `empty` is set when M == 0 or N == 0 (nothing to launch).
 apmm_status check_gemm(int64_t M, int64_t N, int64_t K, int p, int q, const void *a_packed, const void *w_packed,
                        int32_t *c_i32, uint16_t *c_f16, const uint16_t *w_scale, const uint16_t *a_scale,
-                       apmm::GemmArgs &g, bool &empty)
+                       apmm::GemmArgs &g, bool &empty, bool a_is_codes = false)
 {
     empty = false;
     if (M < 0 || N < 0 || K < 1 || !bits_ok(p) || !bits_ok(q))
@@ -132,17 +132,24 @@ apmm_status check_gemm(int64_t M, int64_t N, int64_t K, int p, int q, const void
     }
     if (!a_packed || !w_packed) return fail(APMM_ERR_INVALID_ARG, "gemm: null operand");
     if (!c_i32 && !c_f16) return fail(APMM_ERR_INVALID_ARG, "gemm: no output requested");
-    if (!aligned16(a_packed) || !aligned16(w_packed))
+    if ((!a_is_codes && !aligned16(a_packed)) || !aligned16(w_packed))
         return fail(APMM_ERR_INVALID_ARG, "gemm: packed operands must be 16-byte aligned");
     if ((c_i32 && (reinterpret_cast<uintptr_t>(c_i32) & 3u)) || (c_f16 && (reinterpret_cast<uintptr_t>(c_f16) & 1u)))
         return fail(APMM_ERR_INVALID_ARG, "gemm: misaligned output");
     g.M = M; g.N = N; g.K = K;
     g.nkb = k_p / apmm::kKBlock;
     g.p = p; g.q = q;
-    g.a = static_cast<const uint32_t *>(a_packed);
     g.w = static_cast<const uint32_t *>(w_packed);
-    g.a_sum = reinterpret_cast<const int32_t *>(
-        g.a + apmm::row_sum_word(apmm::round_up(M, apmm::kRowBlock), g.nkb, apmm::activation_slots(p)));
+    if (a_is_codes) {  // the small-M kernels pack the codes themselves and take the row sums on the way
+        g.a = nullptr;
+        g.a_sum = nullptr;
+        g.a_codes = static_cast<const uint8_t *>(a_packed);
+    } else {
+        g.a = static_cast<const uint32_t *>(a_packed);
+        g.a_sum = reinterpret_cast<const int32_t *>(
+            g.a + apmm::row_sum_word(apmm::round_up(M, apmm::kRowBlock), g.nkb, apmm::activation_slots(p)));
+        g.a_codes = nullptr;
+    }
     g.w_sum = reinterpret_cast<const int32_t *>(g.w + apmm::row_sum_word(apmm::round_up(N, apmm::kRowBlock), g.nkb, q));
     g.c_i32 = c_i32; g.c_f16 = c_f16;
     g.w_scale = w_scale; g.a_scale = a_scale;
@@ -198,6 +205,37 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
     const apmm_status st = check_gemm(M, N, K, p, q, a_packed, w_packed, c_i32, c_f16, w_scale, a_scale, g, empty);
     if (st != APMM_OK || empty) return st;
     return run_gemm(g, algo, static_cast<hipStream_t>(stream));
+}
+
+apmm_status apmm_gemm_from_codes(int64_t M, int64_t N, int64_t K, int p, int q, const uint8_t *a_codes,
+                                 const void *w_packed, int32_t *c_i32, uint16_t *c_f16, const uint16_t *w_scale,
+                                 const uint16_t *a_scale, void *workspace, size_t workspace_bytes, void *stream)
+{
+    apmm::GemmArgs g;
+    bool empty;
+    const apmm_status st =
+        check_gemm(M, N, K, p, q, a_codes, w_packed, c_i32, c_f16, w_scale, a_scale, g, empty, /*a_is_codes=*/true);
+    if (st != APMM_OK || empty) return st;
+    if (workspace && !aligned16(workspace)) return fail(APMM_ERR_INVALID_ARG, "gemm_from_codes: workspace must be 16-byte aligned");
+    const bool fused_ok = apmm::gemm_decode_supported(g);
+    const bool room = workspace && workspace_bytes >= apmm_packed_activation_bytes(M, K, p);
+    // Every workgroup of the small-M kernels regroups all M x K codes for itself: that beats a packing launch
+    // (about 3 us) while M x N is small, and loses to it beyond (measured: break-even near 16 tokens x 4096 channels).
+    const bool fused_pays = M * N <= 65536;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (fused_ok && (fused_pays || !room)) {
+        (void)apmm::take_kernel_timing();
+        const hipError_t e = apmm::launch_gemm_decode(g, s);
+        if (e != hipSuccess) return fail_hip(e, "apmm_gemm_from_codes");
+        return APMM_OK;
+    }
+    if (!room)
+        return fail(APMM_ERR_WORKSPACE, "gemm_from_codes: this shape needs a workspace of apmm_packed_activation_bytes(M, K, p) bytes");
+    const apmm_status ps = pack_common(a_codes, M, K, p, apmm::activation_field_form(p), workspace, stream, "apmm_gemm_from_codes");
+    if (ps != APMM_OK) return ps;
+    const apmm_status cs = check_gemm(M, N, K, p, q, workspace, w_packed, c_i32, c_f16, w_scale, a_scale, g, empty);
+    if (cs != APMM_OK) return cs;
+    return run_gemm(g, APMM_ALGO_AUTO, s);
 }
 
 apmm_status apmm_time_next_gemm(void *start_event, void *stop_event)

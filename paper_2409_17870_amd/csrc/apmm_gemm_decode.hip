@@ -69,7 +69,47 @@ __device__ __forceinline__ uint4 plane_half_words_reg(const uint4 (&slot)[Q], in
                       ((l.z >> k1) & 0x11111111u) | (((l.w >> k1) & 0x11111111u) << 2));
 }
 
-template <int MT, int Q>
+// The 128 codes of k block kb of activation row m as bytes: d[8 ks + 2 t + jh] holds the codes of elements
+// 32 ks + 8 t + 4 jh + (0..3) of the block, masked to `bits` bits; elements past K are the all-ones padding code,
+// rows past M are zero.  All loads of a block are issued together (one round trip to memory per block).
+__device__ __forceinline__ void load_code_block(const uint8_t *__restrict__ codes, int64_t M, int64_t K, int bits,
+                                                int64_t m, int64_t kb, uint32_t (&d)[32])
+{
+    if (m >= M) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) d[i] = 0u;
+        return;
+    }
+    const int64_t k0 = kb * kKBlock;
+    const uint8_t *src = codes + m * K + k0;
+    if (k0 + kKBlock <= K && ((reinterpret_cast<uintptr_t>(src)) & 15) == 0) {
+        uint4 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = reinterpret_cast<const uint4 *>(src)[i];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            d[4 * i] = v[i].x; d[4 * i + 1] = v[i].y; d[4 * i + 2] = v[i].z; d[4 * i + 3] = v[i].w;
+        }
+    } else {  // ragged end of a row, or a row that does not start at a multiple of 16 bytes: byte by byte
+#pragma unroll
+        for (int i = 0; i < 32; ++i) d[i] = 0xffffffffu;
+        const int64_t left = K - k0;
+        const int count = left >= kKBlock ? kKBlock : (left > 0 ? (int)left : 0);
+#pragma unroll 1
+        for (int e = 0; e < count; ++e) {
+            const uint32_t flip = (uint32_t)(src[e] ^ 0xffu) << (8 * (e & 3));
+#pragma unroll
+            for (int i = 0; i < 32; ++i)
+                if (i == (e >> 2)) d[i] ^= flip;
+        }
+    }
+    const uint32_t code_mask = 0x01010101u * ((1u << bits) - 1u);
+#pragma unroll
+    for (int i = 0; i < 32; ++i) d[i] &= code_mask;
+}
+
+// CODES: the activations come as unpacked codes (GemmArgs::a_codes) instead of packed tiles
+template <int MT, int Q, bool CODES>
 __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GroupArgs ga)
 {
     // which problem of the launch this workgroup works on (uniform over the workgroup)
@@ -113,11 +153,38 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GroupArgs ga)
     // activations -> LDS: chunk (kb, m, j, hh) = four words of plane j of row m in k block kb
     const int chunks_per_kb = MT * p * 2;
     const int64_t total_chunks = g.nkb * chunks_per_kb;
-    for (int64_t c = tid; c < total_chunks; c += kThreads) {
-        const int64_t ckb = c / chunks_per_kb;
-        const int rem = (int)(c % chunks_per_kb), m = rem / (2 * p), j = (rem >> 1) % p, hh = rem & 1;
-        const uint4 *slots = reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, ckb, g.nkb, p, 0));
-        a_lds[c] = plane_half_words(slots, p, j, hh);
+    if constexpr (CODES) {
+        // straight from the codes: a thread takes the 128 codes of (row m, k block) and writes every plane j in
+        // the common form: word w = 2 ks + tp holds elements (ks, t = 2 tp + tt, jh, c) at bit 8c + 4jh + 2tt
+        const int64_t total_blocks = g.nkb * MT;
+        for (int64_t c = tid; c < total_blocks; c += kThreads) {  // consecutive lanes: consecutive 128 bytes of a row
+            const int m = (int)(c / g.nkb);
+            const int64_t ckb = c % g.nkb;
+            uint32_t d[32];
+            load_code_block(g.a_codes, g.M, g.K, p, m, ckb, d);
+            for (int j = 0; j < p; ++j) {
+                uint32_t word[8];
+#pragma unroll
+                for (int w = 0; w < 8; ++w) {
+                    word[w] = 0;
+#pragma unroll
+                    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                        for (int jh = 0; jh < 2; ++jh)
+                            word[w] |= ((d[8 * (w >> 1) + 2 * (2 * (w & 1) + tt) + jh] >> j) & 0x01010101u) << (4 * jh + 2 * tt);
+                }
+                uint4 *dst = a_lds + ckb * chunks_per_kb + (m * p + j) * 2;
+                dst[0] = make_uint4(word[0], word[1], word[2], word[3]);
+                dst[1] = make_uint4(word[4], word[5], word[6], word[7]);
+            }
+        }
+    } else {
+        for (int64_t c = tid; c < total_chunks; c += kThreads) {
+            const int64_t ckb = c / chunks_per_kb;
+            const int rem = (int)(c % chunks_per_kb), m = rem / (2 * p), j = (rem >> 1) % p, hh = rem & 1;
+            const uint4 *slots = reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, ckb, g.nkb, p, 0));
+            a_lds[c] = plane_half_words(slots, p, j, hh);
+        }
     }
     __syncthreads();
 
@@ -222,8 +289,9 @@ hipError_t launch_mt_q(const GroupArgs &ga, hipStream_t stream)
 {
     size_t lds = 0;
     for (int i = 0; i < ga.count; ++i) lds = lds > decode_lds_bytes(ga.g[i], MT) ? lds : decode_lds_bytes(ga.g[i], MT);
-    static bool attr_set = false;
-    return launch_group(gemm_decode_kernel<MT, Q>, attr_set, ga, lds, stream);
+    static bool attr_set[2] = {false, false};
+    if (ga.g[0].a_codes) return launch_group(gemm_decode_kernel<MT, Q, true>, attr_set[1], ga, lds, stream);
+    return launch_group(gemm_decode_kernel<MT, Q, false>, attr_set[0], ga, lds, stream);
 }
 
 template <int MT>
@@ -253,7 +321,7 @@ hipError_t launch_mt(const GroupArgs &ga, hipStream_t stream)
 //   (the operand scales make acc = 4 S).
 // RT = 2 halves the number of workgroups (and of activation copies) when there are plenty of output channels.
 // ---------------------------------------------------------------------------------------------
-template <int P, int Q, int TT, int RT>
+template <int P, int Q, int TT, int RT, bool CODES>
 __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga)
 {
     // which problem of the launch this workgroup works on (uniform over the workgroup)
@@ -295,7 +363,8 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga
         out_sa[o] = out_sw[o] = 1.0f;
         out_terms[o] = 0;
         if (out_ok[o]) {
-            out_terms[o] = (uint32_t)g.K * ca * cw - 2u * cw * (uint32_t)g.a_sum[out_m[o]] -
+            // (with activation codes as input the row sum PA[m] is taken while packing and added below)
+            out_terms[o] = (uint32_t)g.K * ca * cw - (CODES ? 0u : 2u * cw * (uint32_t)g.a_sum[out_m[o]]) -
                            2u * ca * (uint32_t)g.w_sum[out_n[o]];
             if (g.c_f16) {
                 out_sa[o] = load_scale(g.a_scale, out_m[o]);
@@ -319,14 +388,66 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga
 
     // activations -> LDS; 16 tokens of a slot are 256 contiguous bytes (tokens past M: the last padded row block
     // holds zero words up to a multiple of 32, tokens beyond it are clamped and never stored)
-    const int64_t rows_a = round_up(g.M, kRowBlock);
-    const int64_t total_vecs = g.nkb * P * TOKENS;
-    for (int64_t c = tid; c < total_vecs; c += kThreads) {
-        const int m = (int)(c % TOKENS);
-        const int s = (int)((c / TOKENS) % P);
-        const int64_t ckb = (c / TOKENS) / P;
-        const int64_t m_ld = m < rows_a ? m : rows_a - 1;
-        a_lds[(ckb * TOKENS + m) * P + s] = *reinterpret_cast<const uint4 *>(g.a + tile_row_word(m_ld, ckb, g.nkb, P, s));
+    if constexpr (CODES) {
+        // Straight from the codes: a thread takes the 128 codes of (token m, k block), writes them as the packed
+        // words of that row and block (apmm_layout.h) and adds them to the token's code sum.
+        uint32_t *pa_lds = reinterpret_cast<uint32_t *>(lds_raw) + g.nkb * TOKENS * P * 4;  // behind the packed words
+        if (tid < TOKENS) pa_lds[tid] = 0u;
+        __syncthreads();
+        const int64_t total_blocks = g.nkb * TOKENS;
+        for (int64_t c = tid; c < total_blocks; c += kThreads) {  // consecutive lanes: consecutive 128 bytes of a row
+            const int m = (int)(c / g.nkb);
+            const int64_t ckb = c % g.nkb;
+            uint32_t d[32];
+            load_code_block(g.a_codes, g.M, g.K, P, m, ckb, d);
+            uint32_t sum = 0;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) sum = __builtin_amdgcn_sad_u8(d[i], 0u, sum);
+            // nkb is a multiple of 4: the four lanes of an aligned quad hold blocks of the same token
+            sum += __shfl_xor(sum, 1);
+            sum += __shfl_xor(sum, 2);
+            if ((lane & 3) == 0) atomicAdd(&pa_lds[m], sum);
+            uint4 *dst = a_lds + (ckb * TOKENS + m) * P;
+            if (P == 2) {
+                uint32_t word[8];  // S[w], w = 2 ks + tp: bit b of element (ks, t = 2 tp + tt, jh, c) at 8c + 4jh + 2tt + b
+#pragma unroll
+                for (int w = 0; w < 8; ++w) {
+                    word[w] = 0;
+#pragma unroll
+                    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                        for (int jh = 0; jh < 2; ++jh)
+                            word[w] |= d[8 * (w >> 1) + 2 * (2 * (w & 1) + tt) + jh] << (4 * jh + 2 * tt);
+                }
+                dst[0] = make_uint4(word[0], word[1], word[2], word[3]);
+                dst[1] = make_uint4(word[4], word[5], word[6], word[7]);
+            } else {
+                uint32_t word[4];  // L[t]: the bit of element (ks, t, jh, c) at 8c + 4jh + ks
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    word[t] = 0;
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)
+                        word[t] |= (d[8 * ks + 2 * t] | (d[8 * ks + 2 * t + 1] << 4)) << ks;
+                }
+                dst[0] = make_uint4(word[0], word[1], word[2], word[3]);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int o = 0; o < OUTS; ++o)
+            if (out_ok[o]) out_terms[o] -= 2u * cw * pa_lds[out_m[o]];
+    } else {
+        const int64_t rows_a = round_up(g.M, kRowBlock);
+        const int64_t total_vecs = g.nkb * P * TOKENS;
+        for (int64_t c = tid; c < total_vecs; c += kThreads) {
+            const int m = (int)(c % TOKENS);
+            const int s = (int)((c / TOKENS) % P);
+            const int64_t ckb = (c / TOKENS) / P;
+            const int64_t m_ld = m < rows_a ? m : rows_a - 1;
+            a_lds[(ckb * TOKENS + m) * P + s] =
+                *reinterpret_cast<const uint4 *>(g.a + tile_row_word(m_ld, ckb, g.nkb, P, s));
+        }
     }
     __syncthreads();
 
@@ -413,7 +534,7 @@ int decode_token_tiles(int64_t M) { return M <= 16 ? 1 : M <= 32 ? 2 : 4; }
 size_t decode_mfma_lds_bytes(const GemmArgs &g, int rt)
 {
     const int tt = decode_token_tiles(g.M);
-    const size_t a_bytes = (size_t)g.nkb * 16 * tt * 16 * g.p;
+    const size_t a_bytes = (size_t)g.nkb * 16 * tt * 16 * g.p + 16 * tt * 4;  // packed words + code sums
     const size_t part_bytes = (size_t)kWaves * rt * tt * 256 * 4;
     return a_bytes > part_bytes ? a_bytes : part_bytes;
 }
@@ -430,8 +551,9 @@ hipError_t launch_decode_mfma_v(const GroupArgs &ga, hipStream_t stream)
     size_t lds = 0;
     for (int i = 0; i < ga.count; ++i)
         lds = lds > decode_mfma_lds_bytes(ga.g[i], RT) ? lds : decode_mfma_lds_bytes(ga.g[i], RT);
-    static bool attr_set = false;
-    return launch_group(gemm_decode_mfma_kernel<P, Q, TT, RT>, attr_set, ga, lds, stream);
+    static bool attr_set[2] = {false, false};
+    if (ga.g[0].a_codes) return launch_group(gemm_decode_mfma_kernel<P, Q, TT, RT, true>, attr_set[1], ga, lds, stream);
+    return launch_group(gemm_decode_mfma_kernel<P, Q, TT, RT, false>, attr_set[0], ga, lds, stream);
 }
 
 template <int P, int Q>
@@ -477,7 +599,9 @@ bool gemm_decode_group_supported(const GemmArgs *gs, int count)
     if (count < 1 || count > kMaxGroup) return false;
     const int v = decode_variant(gs[0]);
     for (int i = 0; i < count; ++i)
-        if (decode_variant(gs[i]) != v || gs[i].p != gs[0].p || gs[i].q != gs[0].q) return false;
+        if (decode_variant(gs[i]) != v || gs[i].p != gs[0].p || gs[i].q != gs[0].q ||
+            (gs[i].a_codes != nullptr) != (gs[0].a_codes != nullptr))
+            return false;
     return v != 0;
 }
 

@@ -84,7 +84,8 @@ struct GemmArgs {
     int64_t M, N, K;
     int64_t nkb;          // roundup(K,512)/128
     int p, q;
-    const uint32_t *a;    // packed activations
+    const uint32_t *a;    // packed activations (null when a_codes is given)
+    const uint8_t *a_codes;  // small-M kernels only: M x K activation codes, packed by the kernel itself; else null
     const uint32_t *w;    // packed weights
     const int32_t *a_sum; // per activation row: sum of its codes over the padded K
     const int32_t *w_sum; // per weight row: the same

@@ -102,6 +102,23 @@ def test_new_entry_points_check_their_arguments(lib):
     assert q(0x1001, 4, 128, 2, 0x2000, 0x3000, None) == INVALID       # binary16 data at an odd address
     assert q(0x1000, 0, 128, 2, 0x2000, 0x3000, None) == 0             # no rows: nothing to do
     assert lib.apmm_unpack_activations(None, 3, 128, 4, None, None) == INVALID
+    fc = lib.apmm_gemm_from_codes
+    fc.argtypes = [ctypes.c_int64] * 3 + [ctypes.c_int] * 2 + [ctypes.c_void_p] * 7 + [ctypes.c_size_t, ctypes.c_void_p]
+    assert fc(4, 8, 128, 2, 2, None, 0x2000, 0x3000, None, None, None, None, 0, None) == INVALID      # no codes
+    assert fc(4, 8, 128, 2, 2, 0x1001, 0x2001, 0x3000, None, None, None, None, 0, None) == INVALID    # weights misaligned
+    assert fc(4, 8, 128, 2, 2, 0x1001, 0x2000, None, None, None, None, None, 0, None) == INVALID      # no output
+    assert fc(4, 8, 40000, 8, 8, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == OVERFLOW
+    assert fc(0, 8, 128, 2, 2, None, None, None, None, None, None, None, 0, None) == 0                # no tokens
+    # shapes outside the small-M kernels need a workspace for the packed activations: refused before any launch
+    WORKSPACE = 4
+    assert fc(65, 8, 128, 2, 2, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE
+    assert fc(17, 8, 128, 5, 2, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE
+    assert fc(4, 8, 128, 4, 2, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE
+    assert fc(4, 8, 128, 2, 5, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE
+    assert fc(16, 8, 1 << 20, 2, 2, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE
+    need = lib.apmm_packed_activation_bytes(65, 128, 2)
+    assert fc(65, 8, 128, 2, 2, 0x1001, 0x2000, 0x3000, None, None, None, 0x4000, need - 1, None) == WORKSPACE
+    assert fc(65, 8, 128, 2, 2, 0x1001, 0x2000, 0x3000, None, None, None, 0x4004, need, None) == INVALID   # misaligned
     grouped = lib.apmm_gemm_grouped
     grouped.argtypes = [ctypes.c_int, ctypes.POINTER(ApmmProblem), ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
                         ctypes.c_size_t, ctypes.c_void_p]

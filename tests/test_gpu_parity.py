@@ -184,6 +184,84 @@ def test_decode_kernel_two_row_tiles_per_workgroup(gpu, oracle, M):
     check_f16(c16, want, data, oracle)
 
 
+def run_from_codes(gpu, data, case, dirty_high_bits=False, workspace=False):
+    torch, binding = gpu
+    dev = torch.device("cuda:0")
+    p, q = case["p"], case["q"]
+    a_np = data["a_codes"]
+    if dirty_high_bits and p < 8:  # bits above p must be ignored
+        a_np = a_np | np.uint8((0xff << p) & 0xff)
+    a = torch.from_numpy(a_np).to(dev)
+    w = torch.from_numpy(data["w_codes"]).to(dev)
+    sa = torch.from_numpy(data["a_scale"]).to(dev) if data["a_scale"] is not None else None
+    sw = torch.from_numpy(data["w_scale"]).to(dev) if data["w_scale"] is not None else None
+    wp = binding.apmm_pack_weights(w, q)
+    ws = None
+    if workspace:
+        ws = torch.empty(binding.apmm_packed_activation_bytes(case["M"], case["K"], p), dtype=torch.uint8, device=dev)
+    c32, c16 = binding.apmm_gemm_from_codes(a, case["N"], p, q, wp, want_i32=True, want_f16=True, w_scale=sw, a_scale=sa,
+                                            workspace=ws)
+    torch.cuda.synchronize()
+    return c32.cpu().numpy(), c16.cpu().numpy()
+
+
+@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (1, 2), (2, 2), (5, 3), (2, 4), (8, 2), (1, 4), (6, 4)])
+@pytest.mark.parametrize("M", [1, 2, 3, 5, 8, 13, 16])
+def test_gemm_from_codes_few_tokens(gpu, oracle, M, p, q):
+    """GEMM straight from the activation codes, both small-M kernels, ragged N and K (K = 1100 is neither a
+    multiple of 32 nor of 16: whole groups, a partial group and padded groups all occur)."""
+    case = dict(M=M, N=203, K=1100, p=p, q=q, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 6100 + 100 * M + 10 * p + q)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+    c32, c16 = run_from_codes(gpu, data, case, dirty_high_bits=(M % 2 == 1))
+    assert np.array_equal(c32.astype(np.int64), want)
+    check_f16(c16, want, data, oracle)
+
+
+@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (1, 2), (2, 2)])
+@pytest.mark.parametrize("M,N,K", [(17, 203, 1100), (32, 64, 4096), (50, 203, 1111), (64, 16421, 300), (5, 16421, 300)])
+def test_gemm_from_codes_token_tiles(gpu, oracle, M, N, K, p, q):
+    """The same on the matrix-unit small-M kernel with one, two and four token tiles and both row-tile counts."""
+    case = dict(M=M, N=N, K=K, p=p, q=q, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 6900 + M + 10 * p + q)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+    c32, c16 = run_from_codes(gpu, data, case)
+    assert np.array_equal(c32.astype(np.int64), want)
+    check_f16(c16, want, data, oracle)
+
+
+def test_gemm_from_codes_unaligned_rows_and_refusals(gpu, oracle):
+    """Rows that start at odd addresses (K odd) take the byte-wise loads; shapes outside the small-M kernels
+    are refused when there is no workspace to pack into, not computed some other way."""
+    torch, binding = gpu
+    case = dict(M=7, N=90, K=1023, p=2, q=2, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 7001)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], 2, 2)
+    c32, c16 = run_from_codes(gpu, data, case)
+    assert np.array_equal(c32.astype(np.int64), want)
+    check_f16(c16, want, data, oracle)
+    dev = torch.device("cuda:0")
+    for (M, p, q) in ((65, 2, 2), (17, 5, 2), (4, 4, 2), (4, 2, 5)):
+        a = torch.zeros((M, 256), dtype=torch.uint8, device=dev)
+        wp = binding.apmm_pack_weights(torch.zeros((32, 256), dtype=torch.uint8, device=dev), q)
+        with pytest.raises(binding.ApmmError) as err:
+            binding.apmm_gemm_from_codes(a, 32, p, q, wp)
+        assert err.value.status == 4
+
+
+@pytest.mark.parametrize("M,N,K,p,q", [(65, 203, 1100, 2, 2), (300, 130, 700, 4, 2), (4, 77, 260, 3, 3), (17, 64, 512, 5, 2),
+                                       (16, 8192, 256, 2, 2), (3, 50, 200, 2, 2)])
+def test_gemm_from_codes_through_the_workspace(gpu, oracle, M, N, K, p, q):
+    """With a workspace every shape is served: packed there and multiplied by the kernel apmm_gemm would take
+    (field-form activations, many tokens, wide codes), or still in one launch where that is the faster way."""
+    case = dict(M=M, N=N, K=K, p=p, q=q, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 7100 + M + p)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+    c32, c16 = run_from_codes(gpu, data, case, dirty_high_bits=True, workspace=True)
+    assert np.array_equal(c32.astype(np.int64), want)
+    check_f16(c16, want, data, oracle)
+
+
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (1, 257, 128), (16, 1, 4096), (3, 7, 127), (17, 33, 129)])
 def test_degenerate_shapes(gpu, oracle, M, N, K):
     case = dict(M=M, N=N, K=K, p=2, q=2, a_dist="bernoulli", scaled=True)
@@ -193,6 +271,9 @@ def test_degenerate_shapes(gpu, oracle, M, N, K):
         c32, c16 = run_case(gpu, data, case, algo=algo)
         assert np.array_equal(c32.astype(np.int64), want), "algo %d" % algo
         check_f16(c16, want, data, oracle)
+    c32, c16 = run_from_codes(gpu, data, case)
+    assert np.array_equal(c32.astype(np.int64), want)
+    check_f16(c16, want, data, oracle)
 
 
 @pytest.mark.parametrize("p,q,K", [(2, 1, 2048), (1, 1, 4096), (2, 2, 2560), (3, 1, 2048), (4, 2, 2048)])
