@@ -131,7 +131,7 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q,
  *   - For a few tokens the small-M kernels regroup the codes into the packed form on their way into
  *     on-chip memory: one launch, no packed buffer.  The separate packing launch costs as much as such a
  *     GEMM.  Taken when the small-M kernels cover the shape (M <= 16 with q <= 4 and p not 3 or 4, or
- *     M <= 64 with p, q <= 2; all of K must fit on chip) and M * N <= 65536.
+ *     M <= 64 with p, q <= 2) and M * N <= 65536.
  *   - Otherwise the codes are packed into `workspace` (device, 16-byte aligned, at least
  *     apmm_packed_activation_bytes(M, K, p) bytes, overwritten) and apmm_gemm runs on that: two launches.
  * Without such a workspace the call still takes the one-launch path wherever the small-M kernels cover the

@@ -17,8 +17,8 @@
 //   wave      : k blocks 4*(w + 8*t) .. +3, t = 0, 1, ...
 //   lane l    : weight row l % 16, k block l / 16 of the wave's four; it loads the row's q slots
 //               of that block (q x 16 bytes, 256 contiguous bytes per 16 lanes) straight into registers
-// The activations (M rows, all K) are copied once per workgroup from their packed tiles into LDS with
-// every plane in the common form of the XOR/popcount kernels (16 elements per word at the even bit
+// The activations (M rows, all K; in passes of a multiple of 32 k blocks when all K does not fit) are copied
+// once per workgroup from their packed tiles into LDS with every plane in the common form of the XOR/popcount kernels (16 elements per word at the even bit
 // positions, apmm_layout.h); a weight plane is brought to the same form after loading, so that any
 // activation plane can be XOR-ed with any weight plane.
 #include "apmm_mfma_common.h"
@@ -150,75 +150,82 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GroupArgs ga)
         for (int s = 0; s < Q; ++s) wnext[s] = wsrc[s * kSlotVec];
     }
 
-    // activations -> LDS: chunk (kb, m, j, hh) = four words of plane j of row m in k block kb
-    const int chunks_per_kb = MT * p * 2;
-    const int64_t total_chunks = g.nkb * chunks_per_kb;
-    if constexpr (CODES) {
-        // straight from the codes: a thread takes the 128 codes of (row m, k block) and writes every plane j in
-        // the common form: word w = 2 ks + tp holds elements (ks, t = 2 tp + tt, jh, c) at bit 8c + 4jh + 2tt
-        const int64_t total_blocks = g.nkb * MT;
-        for (int64_t c = tid; c < total_blocks; c += kThreads) {  // consecutive lanes: consecutive 128 bytes of a row
-            const int m = (int)(c / g.nkb);
-            const int64_t ckb = c % g.nkb;
-            uint32_t d[32];
-            load_code_block(g.a_codes, g.M, g.K, p, m, ckb, d);
-            for (int j = 0; j < p; ++j) {
-                uint32_t word[8];
-#pragma unroll
-                for (int w = 0; w < 8; ++w) {
-                    word[w] = 0;
-#pragma unroll
-                    for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                        for (int jh = 0; jh < 2; ++jh)
-                            word[w] |= ((d[8 * (w >> 1) + 2 * (2 * (w & 1) + tt) + jh] >> j) & 0x01010101u) << (4 * jh + 2 * tt);
-                }
-                uint4 *dst = a_lds + ckb * chunks_per_kb + (m * p + j) * 2;
-                dst[0] = make_uint4(word[0], word[1], word[2], word[3]);
-                dst[1] = make_uint4(word[4], word[5], word[6], word[7]);
-            }
-        }
-    } else {
-        for (int64_t c = tid; c < total_chunks; c += kThreads) {
-            const int64_t ckb = c / chunks_per_kb;
-            const int rem = (int)(c % chunks_per_kb), m = rem / (2 * p), j = (rem >> 1) % p, hh = rem & 1;
-            const uint4 *slots = reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, ckb, g.nkb, p, 0));
-            a_lds[c] = plane_half_words(slots, p, j, hh);
-        }
-    }
-    __syncthreads();
-
     uint32_t acc[MT];  // sum_ij 2^(i+j) popcount, modulo 2^32
 #pragma unroll
     for (int m = 0; m < MT; ++m) acc[m] = 0;
 
-    for (; kb < g.nkb; kb += 4 * kWaves) {
-        uint4 wraw[Q];
+    // The activations of chunk_kb k blocks at a time sit in LDS (all of K when it fits, which is the usual
+    // case): chunk (kb, m, j, hh) = four words of plane j of row m in k block kb.  A pass boundary is a multiple
+    // of 32 k blocks, i.e. of the stride of the lanes' k blocks.
+    const int chunks_per_kb = MT * p * 2;
+    const int64_t chunk_kb = ga.chunk_kb[idx];
+    for (int64_t kb0 = 0; kb0 < g.nkb; kb0 += chunk_kb) {
+        const int64_t kb_end = kb0 + chunk_kb < g.nkb ? kb0 + chunk_kb : g.nkb;
+        if (kb0) __syncthreads();  // every wave is done with the previous pass
+        if constexpr (CODES) {
+            // straight from the codes: a thread takes the 128 codes of (row m, k block) and writes every plane j in
+            // the common form: word w = 2 ks + tp holds elements (ks, t = 2 tp + tt, jh, c) at bit 8c + 4jh + 2tt
+            const int64_t pass_kb = kb_end - kb0, total_blocks = pass_kb * MT;
+            for (int64_t c = tid; c < total_blocks; c += kThreads) {  // consecutive lanes: consecutive 128 bytes of a row
+                const int m = (int)(c / pass_kb);
+                const int64_t ckb = c % pass_kb;
+                uint32_t d[32];
+                load_code_block(g.a_codes, g.M, g.K, p, m, kb0 + ckb, d);
+                for (int j = 0; j < p; ++j) {
+                    uint32_t word[8];
 #pragma unroll
-        for (int s = 0; s < Q; ++s) wraw[s] = wnext[s];
-        if (kb + 4 * kWaves < g.nkb) {  // next block of this lane
-            const uint4 *wsrc =
-                reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld, kb + 4 * kWaves, g.nkb, Q, 0));
+                    for (int w = 0; w < 8; ++w) {
+                        word[w] = 0;
 #pragma unroll
-            for (int s = 0; s < Q; ++s) wnext[s] = wsrc[s * kSlotVec];
+                        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                            for (int jh = 0; jh < 2; ++jh)
+                                word[w] |= ((d[8 * (w >> 1) + 2 * (2 * (w & 1) + tt) + jh] >> j) & 0x01010101u) << (4 * jh + 2 * tt);
+                    }
+                    uint4 *dst = a_lds + ckb * chunks_per_kb + (m * p + j) * 2;
+                    dst[0] = make_uint4(word[0], word[1], word[2], word[3]);
+                    dst[1] = make_uint4(word[4], word[5], word[6], word[7]);
+                }
+            }
+        } else {
+            const int64_t total_chunks = (kb_end - kb0) * chunks_per_kb;
+            for (int64_t c = tid; c < total_chunks; c += kThreads) {
+                const int64_t ckb = c / chunks_per_kb;
+                const int rem = (int)(c % chunks_per_kb), m = rem / (2 * p), j = (rem >> 1) % p, hh = rem & 1;
+                const uint4 *slots = reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, kb0 + ckb, g.nkb, p, 0));
+                a_lds[c] = plane_half_words(slots, p, j, hh);
+            }
         }
-        uint4 w[Q][2];
+        __syncthreads();
+
+        for (; kb < kb_end; kb += 4 * kWaves) {
+            uint4 wraw[Q];
 #pragma unroll
-        for (int i = 0; i < Q; ++i)
+            for (int s = 0; s < Q; ++s) wraw[s] = wnext[s];
+            if (kb + 4 * kWaves < g.nkb) {  // next block of this lane
+                const uint4 *wsrc =
+                    reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld, kb + 4 * kWaves, g.nkb, Q, 0));
 #pragma unroll
-            for (int hh = 0; hh < 2; ++hh) w[i][hh] = plane_half_words_reg<Q>(wraw, i, hh);
-        const uint4 *arow = a_lds + kb * chunks_per_kb;
+                for (int s = 0; s < Q; ++s) wnext[s] = wsrc[s * kSlotVec];
+            }
+            uint4 w[Q][2];
 #pragma unroll
-        for (int m = 0; m < MT; ++m) {
-            for (int j = 0; j < p; ++j) {
-                const uint4 a0 = arow[(m * p + j) * 2], a1 = arow[(m * p + j) * 2 + 1];
+            for (int i = 0; i < Q; ++i)
 #pragma unroll
-                for (int i = 0; i < Q; ++i) {
-                    const uint32_t pc = __popc(a0.x ^ w[i][0].x) + __popc(a0.y ^ w[i][0].y) +
-                                        __popc(a0.z ^ w[i][0].z) + __popc(a0.w ^ w[i][0].w) +
-                                        __popc(a1.x ^ w[i][1].x) + __popc(a1.y ^ w[i][1].y) +
-                                        __popc(a1.z ^ w[i][1].z) + __popc(a1.w ^ w[i][1].w);
-                    acc[m] += pc << (i + j);
+                for (int hh = 0; hh < 2; ++hh) w[i][hh] = plane_half_words_reg<Q>(wraw, i, hh);
+            const uint4 *arow = a_lds + (kb - kb0) * chunks_per_kb;
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                for (int j = 0; j < p; ++j) {
+                    const uint4 a0 = arow[(m * p + j) * 2], a1 = arow[(m * p + j) * 2 + 1];
+#pragma unroll
+                    for (int i = 0; i < Q; ++i) {
+                        const uint32_t pc = __popc(a0.x ^ w[i][0].x) + __popc(a0.y ^ w[i][0].y) +
+                                            __popc(a0.z ^ w[i][0].z) + __popc(a0.w ^ w[i][0].w) +
+                                            __popc(a1.x ^ w[i][1].x) + __popc(a1.y ^ w[i][1].y) +
+                                            __popc(a1.z ^ w[i][1].z) + __popc(a1.w ^ w[i][1].w);
+                        acc[m] += pc << (i + j);
+                    }
                 }
             }
         }
@@ -246,9 +253,20 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GroupArgs ga)
     }
 }
 
+// k blocks of activations per pass: all of K when that fits the LDS budget, else the largest multiple of 32
+// (the k-block stride of the lanes) that does; `per_kb` = LDS bytes of one k block, `extra` = bytes beside them.
+int64_t pass_k_blocks(int64_t nkb, size_t per_kb, size_t extra)
+{
+    const int64_t fit = (int64_t)((kMaxLdsBytes - extra) / per_kb);
+    if (nkb <= fit) return nkb;
+    return fit / (4 * kWaves) * (4 * kWaves);  // 0: not even one stride fits
+}
+
+int64_t decode_pass_kb(const GemmArgs &g, int mt) { return pass_k_blocks(g.nkb, (size_t)mt * g.p * 32, 0); }
+
 size_t decode_lds_bytes(const GemmArgs &g, int mt)
 {
-    const size_t a_bytes = (size_t)g.nkb * mt * g.p * 32;
+    const size_t a_bytes = (size_t)decode_pass_kb(g, mt) * mt * g.p * 32;
     const size_t part_bytes = (size_t)kWaves * mt * kRowsPerWg * 4;
     return a_bytes > part_bytes ? a_bytes : part_bytes;
 }
@@ -256,7 +274,8 @@ size_t decode_lds_bytes(const GemmArgs &g, int mt)
 int decode_mt(int64_t M) { return M <= 1 ? 1 : M <= 2 ? 2 : M <= 4 ? 4 : M <= 8 ? 8 : 16; }
 
 // Builds the launch descriptor of `count` problems (16 output channels per workgroup each).
-bool make_group(const GemmArgs *gs, int count, int rows_per_wg, GroupArgs &ga)
+template <class PassKb>
+bool make_group(const GemmArgs *gs, int count, int rows_per_wg, PassKb pass_kb, GroupArgs &ga)
 {
     if (count < 1 || count > kMaxGroup) return false;
     int64_t end = 0;
@@ -267,6 +286,8 @@ bool make_group(const GemmArgs *gs, int count, int rows_per_wg, GroupArgs &ga)
         if (end > 0x7fffffffLL) return false;
         ga.wg_end[i] = (int)end;
         ga.g[i] = g;
+        ga.chunk_kb[i] = (int)pass_kb(g);
+        if (ga.chunk_kb[i] < 1) return false;
     }
     return true;
 }
@@ -386,126 +407,139 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga
         }
     }
 
-    // activations -> LDS; 16 tokens of a slot are 256 contiguous bytes (tokens past M: the last padded row block
-    // holds zero words up to a multiple of 32, tokens beyond it are clamped and never stored)
-    if constexpr (CODES) {
-        // Straight from the codes: a thread takes the 128 codes of (token m, k block), writes them as the packed
-        // words of that row and block (apmm_layout.h) and adds them to the token's code sum.
-        uint32_t *pa_lds = reinterpret_cast<uint32_t *>(lds_raw) + g.nkb * TOKENS * P * 4;  // behind the packed words
-        if (tid < TOKENS) pa_lds[tid] = 0u;
-        __syncthreads();
-        const int64_t total_blocks = g.nkb * TOKENS;
-        for (int64_t c = tid; c < total_blocks; c += kThreads) {  // consecutive lanes: consecutive 128 bytes of a row
-            const int m = (int)(c / g.nkb);
-            const int64_t ckb = c % g.nkb;
-            uint32_t d[32];
-            load_code_block(g.a_codes, g.M, g.K, P, m, ckb, d);
-            uint32_t sum = 0;
-#pragma unroll
-            for (int i = 0; i < 32; ++i) sum = __builtin_amdgcn_sad_u8(d[i], 0u, sum);
-            // nkb is a multiple of 4: the four lanes of an aligned quad hold blocks of the same token
-            sum += __shfl_xor(sum, 1);
-            sum += __shfl_xor(sum, 2);
-            if ((lane & 3) == 0) atomicAdd(&pa_lds[m], sum);
-            uint4 *dst = a_lds + (ckb * TOKENS + m) * P;
-            if (P == 2) {
-                uint32_t word[8];  // S[w], w = 2 ks + tp: bit b of element (ks, t = 2 tp + tt, jh, c) at 8c + 4jh + 2tt + b
-#pragma unroll
-                for (int w = 0; w < 8; ++w) {
-                    word[w] = 0;
-#pragma unroll
-                    for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                        for (int jh = 0; jh < 2; ++jh)
-                            word[w] |= d[8 * (w >> 1) + 2 * (2 * (w & 1) + tt) + jh] << (4 * jh + 2 * tt);
-                }
-                dst[0] = make_uint4(word[0], word[1], word[2], word[3]);
-                dst[1] = make_uint4(word[4], word[5], word[6], word[7]);
-            } else {
-                uint32_t word[4];  // L[t]: the bit of element (ks, t, jh, c) at 8c + 4jh + ks
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    word[t] = 0;
-#pragma unroll
-                    for (int ks = 0; ks < 4; ++ks)
-                        word[t] |= (d[8 * ks + 2 * t] | (d[8 * ks + 2 * t + 1] << 4)) << ks;
-                }
-                dst[0] = make_uint4(word[0], word[1], word[2], word[3]);
-            }
-        }
-        __syncthreads();
-#pragma unroll
-        for (int o = 0; o < OUTS; ++o)
-            if (out_ok[o]) out_terms[o] -= 2u * cw * pa_lds[out_m[o]];
-    } else {
-        const int64_t rows_a = round_up(g.M, kRowBlock);
-        const int64_t total_vecs = g.nkb * P * TOKENS;
-        for (int64_t c = tid; c < total_vecs; c += kThreads) {
-            const int m = (int)(c % TOKENS);
-            const int s = (int)((c / TOKENS) % P);
-            const int64_t ckb = (c / TOKENS) / P;
-            const int64_t m_ld = m < rows_a ? m : rows_a - 1;
-            a_lds[(ckb * TOKENS + m) * P + s] =
-                *reinterpret_cast<const uint4 *>(g.a + tile_row_word(m_ld, ckb, g.nkb, P, s));
-        }
-    }
-    __syncthreads();
-
     mfma::v4f acc[RT][TT];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = mfma::v4f{0.f, 0.f, 0.f, 0.f};
-    // nkb is a multiple of 4 (K is padded to 512): whole groups of four k blocks
-    for (; kb4 * 4 < g.nkb; kb4 += kWaves) {
-        const int64_t kb = kb4 * 4 + kq;
-        uint4 wq[RT][2], aq[TT][2];
+
+    // The activations of chunk_kb k blocks at a time sit in LDS (all of K when it fits, the usual case); a pass
+    // boundary is a multiple of 32 k blocks, the stride of the waves' groups of four k blocks.
+    const int64_t chunk_kb = ga.chunk_kb[idx];
+    uint32_t *pa_lds = reinterpret_cast<uint32_t *>(lds_raw) + chunk_kb * TOKENS * P * 4;  // behind the words
+    if constexpr (CODES) {
+        if (tid < TOKENS) pa_lds[tid] = 0u;  // token code sums, taken while packing (made visible by the barriers below)
+    }
+    for (int64_t kb0 = 0; kb0 < g.nkb; kb0 += chunk_kb) {
+        const int64_t kb_end = kb0 + chunk_kb < g.nkb ? kb0 + chunk_kb : g.nkb;
+        const int64_t pass_kb = kb_end - kb0;
+        __syncthreads();  // every wave is done with the previous pass (first pass: the sums are zero)
+        if constexpr (CODES) {
+            // Straight from the codes: a thread takes the 128 codes of (token m, k block), writes them as the packed
+            // words of that row and block (apmm_layout.h) and adds them to the token's code sum.
+            const int64_t total_blocks = pass_kb * TOKENS;
+            for (int64_t c = tid; c < total_blocks; c += kThreads) {  // consecutive lanes: consecutive 128 bytes of a row
+                const int m = (int)(c / pass_kb);
+                const int64_t ckb = c % pass_kb;
+                uint32_t d[32];
+                load_code_block(g.a_codes, g.M, g.K, P, m, kb0 + ckb, d);
+                uint32_t sum = 0;
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
+                for (int i = 0; i < 32; ++i) sum = __builtin_amdgcn_sad_u8(d[i], 0u, sum);
+                // a pass has a multiple of 4 k blocks: the four lanes of an aligned quad hold blocks of the same token
+                sum += __shfl_xor(sum, 1);
+                sum += __shfl_xor(sum, 2);
+                if ((lane & 3) == 0) atomicAdd(&pa_lds[m], sum);
+                uint4 *dst = a_lds + (ckb * TOKENS + m) * P;
+                if (P == 2) {
+                    uint32_t word[8];  // S[w], w = 2 ks + tp: bit b of element (ks, t = 2 tp + tt, jh, c) at 8c + 4jh + 2tt + b
 #pragma unroll
-            for (int s = 0; s < Q; ++s) wq[rt][s] = wnext[rt][s];
-        if ((kb4 + kWaves) * 4 < g.nkb) {  // next block of this lane
+                    for (int w = 0; w < 8; ++w) {
+                        word[w] = 0;
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt) {
-                const uint4 *wsrc =
-                    reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld[rt], kb + 4 * kWaves, g.nkb, Q, 0));
+                        for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-                for (int s = 0; s < Q; ++s) wnext[rt][s] = wsrc[s * kSlotVec];
+                            for (int jh = 0; jh < 2; ++jh)
+                                word[w] |= d[8 * (w >> 1) + 2 * (2 * (w & 1) + tt) + jh] << (4 * jh + 2 * tt);
+                    }
+                    dst[0] = make_uint4(word[0], word[1], word[2], word[3]);
+                    dst[1] = make_uint4(word[4], word[5], word[6], word[7]);
+                } else {
+                    uint32_t word[4];  // L[t]: the bit of element (ks, t, jh, c) at 8c + 4jh + ks
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        word[t] = 0;
+#pragma unroll
+                        for (int ks = 0; ks < 4; ++ks)
+                            word[t] |= (d[8 * ks + 2 * t] | (d[8 * ks + 2 * t + 1] << 4)) << ks;
+                    }
+                    dst[0] = make_uint4(word[0], word[1], word[2], word[3]);
+                }
+            }
+        } else {
+            // 16 tokens of a slot are 256 contiguous bytes (tokens past M: the last padded row block holds zero
+            // words up to a multiple of 32, tokens beyond it are clamped and never stored)
+            const int64_t rows_a = round_up(g.M, kRowBlock);
+            const int64_t total_vecs = pass_kb * P * TOKENS;
+            for (int64_t c = tid; c < total_vecs; c += kThreads) {
+                const int m = (int)(c % TOKENS);
+                const int s = (int)((c / TOKENS) % P);
+                const int64_t ckb = (c / TOKENS) / P;
+                const int64_t m_ld = m < rows_a ? m : rows_a - 1;
+                a_lds[(ckb * TOKENS + m) * P + s] =
+                    *reinterpret_cast<const uint4 *>(g.a + tile_row_word(m_ld, kb0 + ckb, g.nkb, P, s));
             }
         }
+        __syncthreads();
+        if constexpr (CODES) {
+            if (kb_end == g.nkb) {  // the code sums are complete
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-            for (int s = 0; s < P; ++s) aq[tt][s] = a_lds[(kb * TOKENS + tt * 16 + r16) * P + s];
-        mfma::static_for<4>([&](auto ks_c) __attribute__((always_inline)) {
-            constexpr int ks = decltype(ks_c)::value;
-            mfma::v8i a8[RT], b8[TT];
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt) a8[rt] = mfma::v8i{0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt) b8[tt] = mfma::v8i{0, 0, 0, 0, 0, 0, 0, 0};
-            mfma::static_for<4>([&](auto d_c) __attribute__((always_inline)) {
-                constexpr int d = decltype(d_c)::value;
-#pragma unroll
-                for (int rt = 0; rt < RT; ++rt) {
-                    if constexpr (Q == 1) a8[rt][d] = (int)mfma::fp4_single_dword<ks, d>(wq[rt][0]);
-                    else a8[rt][d] = (int)mfma::fp4_pair_dword<ks, d>(wq[rt][0], wq[rt][1]);
-                }
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) {
-                    if constexpr (P == 1) b8[tt][d] = (int)mfma::fp4_single_dword<ks, d>(aq[tt][0]);
-                    else b8[tt][d] = (int)mfma::fp4_pair_dword<ks, d>(aq[tt][0], aq[tt][1]);
-                }
-            });
-            // E8M0 exponents: 2^2 per operand turns (ua/2)(uw/2) into 4 ua uw
+                for (int o = 0; o < OUTS; ++o)
+                    if (out_ok[o]) out_terms[o] -= 2u * cw * pa_lds[out_m[o]];
+            }
+        }
+
+        // nkb and the pass boundaries are multiples of 4: whole groups of four k blocks
+        for (; kb4 * 4 < kb_end; kb4 += kWaves) {
+            const int64_t kb = kb4 * 4 + kq;
+            uint4 wq[RT][2], aq[TT][2];
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
-                    acc[rt][tt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                        a8[rt], b8[tt], acc[rt][tt], 4, 4, 0, 129 + (Q == 1 ? mfma::fp4_single_exponent(ks) : 0), 0,
-                        129 + (P == 1 ? mfma::fp4_single_exponent(ks) : 0));
-        });
+                for (int s = 0; s < Q; ++s) wq[rt][s] = wnext[rt][s];
+            if ((kb4 + kWaves) * 4 < g.nkb) {  // next block of this lane
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    const uint4 *wsrc =
+                        reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld[rt], kb + 4 * kWaves, g.nkb, Q, 0));
+#pragma unroll
+                    for (int s = 0; s < Q; ++s) wnext[rt][s] = wsrc[s * kSlotVec];
+                }
+            }
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int s = 0; s < P; ++s) aq[tt][s] = a_lds[((kb - kb0) * TOKENS + tt * 16 + r16) * P + s];
+            mfma::static_for<4>([&](auto ks_c) __attribute__((always_inline)) {
+                constexpr int ks = decltype(ks_c)::value;
+                mfma::v8i a8[RT], b8[TT];
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) a8[rt] = mfma::v8i{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) b8[tt] = mfma::v8i{0, 0, 0, 0, 0, 0, 0, 0};
+                mfma::static_for<4>([&](auto d_c) __attribute__((always_inline)) {
+                    constexpr int d = decltype(d_c)::value;
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt) {
+                        if constexpr (Q == 1) a8[rt][d] = (int)mfma::fp4_single_dword<ks, d>(wq[rt][0]);
+                        else a8[rt][d] = (int)mfma::fp4_pair_dword<ks, d>(wq[rt][0], wq[rt][1]);
+                    }
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) {
+                        if constexpr (P == 1) b8[tt][d] = (int)mfma::fp4_single_dword<ks, d>(aq[tt][0]);
+                        else b8[tt][d] = (int)mfma::fp4_pair_dword<ks, d>(aq[tt][0], aq[tt][1]);
+                    }
+                });
+                // E8M0 exponents: 2^2 per operand turns (ua/2)(uw/2) into 4 ua uw
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+                        acc[rt][tt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                            a8[rt], b8[tt], acc[rt][tt], 4, 4, 0, 129 + (Q == 1 ? mfma::fp4_single_exponent(ks) : 0), 0,
+                            129 + (P == 1 ? mfma::fp4_single_exponent(ks) : 0));
+            });
+        }
     }
 
     // reduce over the waves through LDS: part[wave][tile t][v][lane]
@@ -531,17 +565,23 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga
 
 int decode_token_tiles(int64_t M) { return M <= 16 ? 1 : M <= 32 ? 2 : 4; }
 
+int64_t decode_mfma_pass_kb(const GemmArgs &g)
+{
+    const int tt = decode_token_tiles(g.M);
+    return pass_k_blocks(g.nkb, (size_t)16 * tt * 16 * g.p, (size_t)16 * tt * 4);
+}
+
 size_t decode_mfma_lds_bytes(const GemmArgs &g, int rt)
 {
     const int tt = decode_token_tiles(g.M);
-    const size_t a_bytes = (size_t)g.nkb * 16 * tt * 16 * g.p + 16 * tt * 4;  // packed words + code sums
+    const size_t a_bytes = (size_t)decode_mfma_pass_kb(g) * 16 * tt * 16 * g.p + 16 * tt * 4;  // packed words + code sums
     const size_t part_bytes = (size_t)kWaves * rt * tt * 256 * 4;
     return a_bytes > part_bytes ? a_bytes : part_bytes;
 }
 
 bool decode_mfma_supported(const GemmArgs &g)
 {
-    return g.M >= 3 && g.M <= 64 && g.p <= 2 && g.q <= 2 && decode_mfma_lds_bytes(g, 2) <= (size_t)kMaxLdsBytes &&
+    return g.M >= 3 && g.M <= 64 && g.p <= 2 && g.q <= 2 && decode_mfma_pass_kb(g) > 0 &&
            4 * g.nkb * kKBlock * 9 < (1 << 24);
 }
 
@@ -586,12 +626,12 @@ int decode_variant(const GemmArgs &g)
     if (activation_field_form(g.p)) return 0;  // 3- and 4-bit activations are laid out for the large-tile MFMA kernel
     if (decode_mfma_supported(g)) return 100 + decode_token_tiles(g.M);
     if (g.M > 16) return 0;
-    return decode_lds_bytes(g, decode_mt(g.M)) <= (size_t)kMaxLdsBytes ? decode_mt(g.M) : 0;
+    return decode_pass_kb(g, decode_mt(g.M)) > 0 ? decode_mt(g.M) : 0;
 }
 
 }  // namespace
 
-// M <= 16, q <= 4, and the activations of all K must fit the LDS budget.
+// M <= 16 with q <= 4, or M <= 64 with p, q <= 2; never activations in the field form (p = 3, 4).
 bool gemm_decode_supported(const GemmArgs &g) { return decode_variant(g) != 0; }
 
 bool gemm_decode_group_supported(const GemmArgs *gs, int count)
@@ -615,10 +655,12 @@ hipError_t launch_gemm_decode_group(const GemmArgs *gs, int count, hipStream_t s
         int64_t rows = 0;
         for (int i = 0; i < count; ++i) rows += gs[i].N;
         const int rt = rows >= 2 * 256 * 2 * kRowsPerWg ? 2 : 1;
-        if (!make_group(gs, count, kRowsPerWg * rt, ga)) return hipErrorInvalidValue;
+        if (!make_group(gs, count, kRowsPerWg * rt, [](const GemmArgs &g) { return decode_mfma_pass_kb(g); }, ga))
+            return hipErrorInvalidValue;
         return launch_decode_mfma(ga, rt, stream);
     }
-    if (!make_group(gs, count, kRowsPerWg, ga)) return hipErrorInvalidValue;
+    if (!make_group(gs, count, kRowsPerWg, [variant](const GemmArgs &g) { return decode_pass_kb(g, variant); }, ga))
+        return hipErrorInvalidValue;
     switch (variant) {
     case 1: return launch_mt<1>(ga, stream);
     case 2: return launch_mt<2>(ga, stream);

@@ -99,6 +99,7 @@ struct GemmArgs {
 constexpr int kMaxGroup = 8;
 struct GroupArgs {
     int count;
+    int chunk_kb[kMaxGroup];  // per problem: k blocks of activations held on chip at a time (a multiple of 32, or all)
     int wg_end[kMaxGroup];
     GemmArgs g[kMaxGroup];
 };

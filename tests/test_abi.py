@@ -115,7 +115,7 @@ def test_new_entry_points_check_their_arguments(lib):
     assert fc(17, 8, 128, 5, 2, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE
     assert fc(4, 8, 128, 4, 2, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE
     assert fc(4, 8, 128, 2, 5, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE
-    assert fc(16, 8, 1 << 20, 2, 2, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE
+    assert fc(40, 8, 1 << 20, 2, 2, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE   # K beyond the exact fp32 range
     need = lib.apmm_packed_activation_bytes(65, 128, 2)
     assert fc(65, 8, 128, 2, 2, 0x1001, 0x2000, 0x3000, None, None, None, 0x4000, need - 1, None) == WORKSPACE
     assert fc(65, 8, 128, 2, 2, 0x1001, 0x2000, 0x3000, None, None, None, 0x4004, need, None) == INVALID   # misaligned

@@ -262,6 +262,22 @@ def test_gemm_from_codes_through_the_workspace(gpu, oracle, M, N, K, p, q):
     check_f16(c16, want, data, oracle)
 
 
+@pytest.mark.parametrize("M,K,p,q", [(16, 11008, 8, 4), (8, 9000, 8, 2), (13, 20000, 5, 3), (64, 11008, 2, 2),
+                                     (33, 20000, 2, 1), (48, 8200, 1, 2), (16, 40000, 2, 2), (2, 70000, 2, 2)])
+def test_decode_kernels_with_k_beyond_one_pass(gpu, oracle, M, K, p, q):
+    """Activations that do not fit on chip at once: the small-M kernels take K in passes of 32 k blocks (ragged
+    last pass), from packed tiles and from codes alike."""
+    case = dict(M=M, N=77, K=K, p=p, q=q, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 7300 + M + p)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+    c32, c16 = run_case(gpu, data, case, algo=DECODE)
+    assert np.array_equal(c32.astype(np.int64), want)
+    check_f16(c16, want, data, oracle)
+    c32, c16 = run_from_codes(gpu, data, case)
+    assert np.array_equal(c32.astype(np.int64), want)
+    check_f16(c16, want, data, oracle)
+
+
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (1, 257, 128), (16, 1, 4096), (3, 7, 127), (17, 33, 129)])
 def test_degenerate_shapes(gpu, oracle, M, N, K):
     case = dict(M=M, N=N, K=K, p=2, q=2, a_dist="bernoulli", scaled=True)
@@ -342,11 +358,12 @@ def test_quantized_activations_through_the_gemm(gpu, oracle):
 
 @pytest.mark.parametrize("M", [1, 2, 8, 16, 40])
 def test_grouped_launch_matches_single_calls_and_the_oracle(gpu, oracle, M):
-    """q/k/v-like (shared activations) and gate/up-like linears plus one of another K in one grouped call."""
+    """q/k/v-like (shared activations) and gate/up-like linears plus some of another K (one of them too long for
+    a single on-chip pass at the larger token counts) in one grouped call."""
     torch, binding = gpu
     dev = torch.device("cuda:0")
     p, q = 2, 2
-    shapes = [(96, 512), (80, 512), (33, 512), (200, 512), (150, 512), (64, 1280), (16, 130), (48, 512), (40, 512), (24, 512)]
+    shapes = [(96, 512), (80, 512), (33, 512), (200, 512), (150, 512), (64, 1280), (16, 130), (48, 512), (40, 40000), (24, 512)]
     acts = {}
     problems, wants = [], []
     for i, (N, K) in enumerate(shapes):
