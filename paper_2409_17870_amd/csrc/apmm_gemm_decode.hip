@@ -18,9 +18,9 @@
 //   lane l    : weight row l % 16, k block l / 16 of the wave's four; it loads the row's q slots
 //               of that block (q x 16 bytes, 256 contiguous bytes per 16 lanes) straight into registers
 // The activations (M rows, all K; in passes of a multiple of 32 k blocks when all K does not fit) are copied
-// once per workgroup from their packed tiles into LDS with every plane in the common form of the XOR/popcount kernels (16 elements per word at the even bit
-// positions, apmm_layout.h); a weight plane is brought to the same form after loading, so that any
-// activation plane can be XOR-ed with any weight plane.
+// once per workgroup from their packed tiles into LDS with every plane in the common form of the XOR/popcount
+// kernels (16 elements per word at the even bit positions, apmm_layout.h); a weight plane is brought to the
+// same form after loading, so that any activation plane can be XOR-ed with any weight plane.
 #include "apmm_mfma_common.h"
 
 namespace apmm {
