@@ -30,10 +30,10 @@ PAPER_W1A2_4096_TOPS = 2 * 4096 ** 3 / 160e-6 / 1e12   # paper Table 1: 160 us o
 
 # HBM bytes per GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command,
 # each scaled by what the same counter reads for a plain 64 MiB copy (profiles/ holds the runs).
-# FETCH_SIZE 16146.4 KiB x 1.9989 (copy calibration) + WRITE_SIZE 65536 KiB x 1.0
-MEASURED_TRAFFIC_BYTES = {"auto": 100158000, "fp4": 100158000}
+# FETCH_SIZE 10539.1 KiB x 1.9989 (copy calibration) + WRITE_SIZE 65540.5 KiB x 1.0
+MEASURED_TRAFFIC_BYTES = {"auto": 88686000, "fp4": 88686000}
 
-KERNEL = "gemm_mfma_direct_kernel<2,1,4,4,2> (E2M1 operands expanded in registers, 256x256 tile, two phases)"
+KERNEL = "gemm_mfma_direct_kernel<2,1,4,4,3> (E2M1 operands expanded in registers, 256x256 tile, two uneven phases)"
 
 ALGOS = {"auto": 0, "valu": 1, "fp4": 4}
 

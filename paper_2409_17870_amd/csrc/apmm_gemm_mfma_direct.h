@@ -43,31 +43,38 @@ namespace mfma {
 // SPLIT = 1: the wave tile is computed in one go and stored at the end.
 // SPLIT = 2: the wave tile is computed as two halves of WM / 2 row blocks, one after the other (each a full
 // sweep of K), and the int32 stores of the first half are interleaved with the MFMAs of the second half's
-// first STORE_STAGES stages, one element every other MFMA, so that half of the C traffic (which otherwise
-// keeps the matrix unit idle for 6 - 7 us at 4096^2 outputs) runs under the k loop.  The price is less
-// reuse per expanded fragment.  Used for interior tiles with int32 output only and K of at least STORE_STAGES stages.
-constexpr int kStoreEvery = 2;
+// first stages, one element every other MFMA, so that half of the C traffic (which otherwise keeps the
+// matrix unit idle for 6 - 7 us at 4096^2 outputs) runs under the k loop.  The price is less reuse per
+// expanded fragment.
+// SPLIT = 3: the same with an uneven cut, WM - 1 row blocks first and one row block second: three quarters of
+// the output go out under the k loop (one element per MFMA of the second phase), the first phase keeps nearly
+// the operand reuse of the whole tile, and only the short second phase pays for the stores and the low reuse.
+// Both are used for interior tiles with int32 output only and K long enough to carry the stores.
+constexpr int split_phases(int split) { return split == 1 ? 1 : 2; }
+constexpr int split_rows(int wm, int split, int ph) { return split == 1 ? wm : split == 2 ? wm / 2 : (ph == 0 ? wm - 1 : 1); }
+constexpr int split_row0(int wm, int split, int ph) { return ph == 0 ? 0 : split_rows(wm, split, 0); }
+constexpr int split_store_every(int split) { return split == 3 ? 1 : 2; }  // MFMAs per stored element
+// stages of phase 1 that carry the stores of phase 0 (KS = 4 k steps per stage)
+constexpr int split_store_stages(int wm, int wn, int split)
+{
+    return split == 1 ? 0 : split_rows(wm, split, 0) * wn * 16 / (4 * split_rows(wm, split, 1) * wn / split_store_every(split));
+}
 
 template <int P, int Q, int WM, int WN, int SPLIT>
 __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int tiles_n, int tiles_total)
 {
     static_assert(P >= 1 && P <= 4 && Q >= 1 && Q <= 4, "instantiated for codes of up to four bits");
-    static_assert(SPLIT == 1 || SPLIT == 2, "one or two phases");
+    static_assert(SPLIT >= 1 && SPLIT <= 3, "one phase, two even phases, or two uneven phases");
+    static_assert(SPLIT == 1 || WM % 2 == 0, "the row blocks of a wave are cut in two");
     constexpr bool AF = activation_field_form(P);  // activations are ready-made fp6 operands
     constexpr int SLOTS_A = activation_slots(P);
-    constexpr int WMP = WM / SPLIT;          // row blocks per phase
+    constexpr int PHASES = split_phases(SPLIT);
+    constexpr int WMX = split_rows(WM, SPLIT, 0);  // row blocks of the largest phase (the first)
     constexpr int BM = 64 * WM, BN = 64 * WN;
     constexpr int KS = 4;                    // MFMA k steps per stage
-    constexpr int PER_KS = WMP * WN;         // MFMAs per k step
-    constexpr int FRAG0 = AF ? WMP : 0;      // first fragment that needs expanding (A blocks come first)
-    constexpr int FRAGS = WMP + WN;          // operand fragments per k step
-    constexpr int TASKS = 4 * (FRAGS - FRAG0);  // expansion dwords per k step
-    static_assert(TASKS % PER_KS == 0, "expansion tasks must spread evenly over the MFMAs of a k step");
-    constexpr int TPM = TASKS / PER_KS;      // tasks per MFMA
-    constexpr int PHASE_ELEMS = WMP * WN * 16;                  // outputs per lane and phase
-    constexpr int STAGE_ELEMS = KS * PER_KS / kStoreEvery;      // outputs stored under one stage
-    constexpr int STORE_STAGES = PHASE_ELEMS / STAGE_ELEMS;     // stages that carry stores
-    static_assert(STORE_STAGES % 2 == 0 && STORE_STAGES * STAGE_ELEMS == PHASE_ELEMS, "store schedule");
+    constexpr int STORE_EVERY = split_store_every(SPLIT);
+    constexpr int STORE_STAGES = split_store_stages(WM, WN, SPLIT);  // stages of phase 1 that carry stores
+    static_assert(STORE_STAGES % 2 == 0, "store schedule");
     constexpr uint32_t ca = (1u << P) - 1, cw = (1u << Q) - 1;
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
@@ -101,7 +108,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
     // Accumulator layout of the 32x32 MFMA: lane l, register v holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
     const int64_t m_lane = m0 + wave_m * WM * 32 + kh * 4, n_lane = n0 + wave_n * WN * 32 + r32;
 
-    v16f acc[SPLIT][WMP][WN];
+    v16f acc[WM][WN];  // by row block of the wave tile; phase ph owns blocks split_row0(ph) ...
     // The accumulators start at the recovery terms rt[m] + ct[n], rt = -2 cw PA, ct = K ca cw - 2 ca PW: a
     // rank-2 matrix, written by one fp32 MFMA with k = 2 per block: A = (rt[m], 1), B = (1, ct[n]).
     // Lane l supplies row resp. column l % 32 of k index l / 32.  All values are integers below 2^24.
@@ -139,24 +146,25 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
 
     auto init_phase = [&](auto ph_c) __attribute__((always_inline)) {
         constexpr int ph = decltype(ph_c)::value;
+        constexpr int WMP = split_rows(WM, SPLIT, ph), ROW0 = split_row0(WM, SPLIT, ph);
         v16f zero;
 #pragma unroll
         for (int v = 0; v < 16; ++v) zero[v] = 0.f;
 #pragma unroll
         for (int bi = 0; bi < WMP; ++bi) {
-            int64_t m = m0 + (wave_m * WM + ph * WMP + bi) * 32 + r32;
+            int64_t m = m0 + (wave_m * WM + ROW0 + bi) * 32 + r32;
             if (m >= rows_a) m = rows_a - 1;
             const float rt = -(float)(2u * cw * (uint32_t)g.a_sum[m]);
             const float a_init = kh == 0 ? rt : 1.0f;
 #pragma unroll
             for (int bj = 0; bj < WN; ++bj)
-                acc[ph][bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_init, b_init[bj], zero, 0, 0, 0);
+                acc[ROW0 + bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_init, b_init[bj], zero, 0, 0, 0);
         }
     };
 
-    uint4 ra[2][WMP][AF ? 6 : 2], rb[2][WN][2];  // raw words of a group (a single group uses [0] only; the field
+    uint4 ra[2][WMX][AF ? 6 : 2], rb[2][WN][2];  // raw words of a group (a single group uses [0] only; the field
                                                  // form all six slots), by stage parity
-    v4i af[2][WMP], bf[2][WN];          // expanded fragments, by k step parity
+    v4i af[2][WMX], bf[2][WN];          // expanded fragments, by k step parity
     const int64_t nst = g.nkb / 2;      // the packed K is a multiple of 512: an even number of whole stages
 
     // int32 store of element e of phase ph under the k loop of the next phase: elements run along the row
@@ -165,10 +173,12 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
     char *st_ptr = nullptr;
     auto store_elem = [&](auto ph_c, auto e_c) __attribute__((always_inline)) {
         constexpr int ph = decltype(ph_c)::value, e = decltype(e_c)::value;
-        constexpr int bi = e / (16 * WN), v = (e / WN) % 16, bj = e % WN;
+        constexpr int bi = split_row0(WM, SPLIT, ph) + e / (16 * WN), v = (e / WN) % 16, bj = e % WN;
         // rows of consecutive registers: +1, +1, +1, +5 (the next group of four rows, or the next row block)
         if constexpr (bj == 0 && e > 0) st_ptr += (v % 4 == 0 ? 5 : 1) * row_bytes;
-        *reinterpret_cast<int32_t *>(st_ptr + bj * 128) = (int32_t)acc[ph][bi][bj][v];
+        // streaming store: the output is not read again, and keeping it out of the way of the operand tiles in
+        // L2 (and written back early rather than at the end of the kernel) is worth about 5 % at 4096^2 outputs
+        __builtin_nontemporal_store((int32_t)acc[bi][bj][v], reinterpret_cast<int32_t *>(st_ptr + bj * 128));
     };
 
     // One sweep of K for phase ph, the activation group at slot slot_a and the weight group at slot slot_b
@@ -179,11 +189,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
         constexpr int ph = decltype(ph_c)::value;
         constexpr bool STORES = decltype(stores_c)::value;
         constexpr bool AS = decltype(as_c)::value, BS = decltype(bs_c)::value;
+        constexpr int WMP = split_rows(WM, SPLIT, ph), ROW0 = split_row0(WM, SPLIT, ph);  // this phase's row blocks
+        constexpr int PER_KS = WMP * WN;         // MFMAs per k step
+        constexpr int FRAG0 = AF ? WMP : 0;      // first fragment that needs expanding (A blocks come first)
+        constexpr int FRAGS = WMP + WN;          // operand fragments per k step
+        constexpr int TASKS = 4 * (FRAGS - FRAG0);  // expansion dwords per k step
+        constexpr int TPM = (TASKS + PER_KS - 1) / PER_KS;  // tasks per MFMA (the last MFMAs of a step may get fewer)
+        constexpr int STAGE_ELEMS = KS * PER_KS / STORE_EVERY;  // outputs of the previous phase stored under one stage
         auto load_stage = [&](auto buf_c, int64_t st) __attribute__((always_inline)) {
             constexpr int buf = decltype(buf_c)::value;
 #pragma unroll
             for (int bi = 0; bi < WMP; ++bi) {
-                const uint4 *src = pa_src[ph * WMP + bi];
+                const uint4 *src = pa_src[ROW0 + bi];
                 if constexpr (AF) {
 #pragma unroll
                     for (int sl = 0; sl < 6; ++sl) ra[buf][bi][sl] = src[st * kStageVecA + sl * kSlotVec];
@@ -237,28 +254,30 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
                     const v8i a8 = {raw(std::integral_constant<int, 0>{}), raw(std::integral_constant<int, 1>{}),
                                     raw(std::integral_constant<int, 2>{}), raw(std::integral_constant<int, 3>{}),
                                     raw(std::integral_constant<int, 4>{}), raw(std::integral_constant<int, 5>{}), 0, 0};
-                    acc[ph][bi][bj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                        a8, b8, acc[ph][bi][bj], 2, 4, 0, exp_a, 0, exp_b + (BS ? fp4_single_exponent(ks) : 0));
+                    acc[ROW0 + bi][bj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        a8, b8, acc[ROW0 + bi][bj], 2, 4, 0, exp_a, 0, exp_b + (BS ? fp4_single_exponent(ks) : 0));
                 } else {
                     const v4i a = af[ks & 1][bi];
                     const v8i a8 = {a[0], a[1], a[2], a[3], 0, 0, 0, 0};
-                    acc[ph][bi][bj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                        a8, b8, acc[ph][bi][bj], 4, 4, 0, exp_a + (AS ? fp4_single_exponent(ks) : 0), 0,
+                    acc[ROW0 + bi][bj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        a8, b8, acc[ROW0 + bi][bj], 4, 4, 0, exp_a + (AS ? fp4_single_exponent(ks) : 0), 0,
                         exp_b + (BS ? fp4_single_exponent(ks) : 0));
                 }
                 // this MFMA's share of the next k step's operands (after the last step: step 0 of stage st+1)
                 static_for<TPM>([&](auto t_c) __attribute__((always_inline)) {
                     constexpr int task = j * TPM + decltype(t_c)::value;
-                    using F = std::integral_constant<int, FRAG0 + task / 4>;
-                    using D = std::integral_constant<int, task % 4>;
-                    if constexpr (ks + 1 < KS)
-                        expand(buf_c, std::integral_constant<int, ks + 1>{}, F{}, D{});
-                    else
-                        expand(Other{}, I0{}, F{}, D{});
+                    if constexpr (task < TASKS) {
+                        using F = std::integral_constant<int, FRAG0 + task / 4>;
+                        using D = std::integral_constant<int, task % 4>;
+                        if constexpr (ks + 1 < KS)
+                            expand(buf_c, std::integral_constant<int, ks + 1>{}, F{}, D{});
+                        else
+                            expand(Other{}, I0{}, F{}, D{});
+                    }
                 });
-                if constexpr (chunk >= 0 && i % kStoreEvery == 0)
+                if constexpr (chunk >= 0 && i % STORE_EVERY == 0)
                     store_elem(std::integral_constant<int, (ph > 0 ? ph - 1 : 0)>{},
-                               std::integral_constant<int, chunk * STAGE_ELEMS + i / kStoreEvery>{});
+                               std::integral_constant<int, chunk * STAGE_ELEMS + i / STORE_EVERY>{});
                 __builtin_amdgcn_sched_barrier(0);
             });
         };
@@ -285,11 +304,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
 
     using T = std::true_type;
     using F = std::false_type;
-    static_for<SPLIT>([&](auto ph_c) __attribute__((always_inline)) {
+    static_for<PHASES>([&](auto ph_c) __attribute__((always_inline)) {
         constexpr int ph = decltype(ph_c)::value;
         init_phase(ph_c);
         if constexpr (ph > 0)  // row pointer of element 0 of the previous phase
-            st_ptr = reinterpret_cast<char *>(g.c_i32 + (m_lane + (ph - 1) * WMP * 32) * g.N + n_lane);
+            st_ptr = reinterpret_cast<char *>(g.c_i32 + (m_lane + split_row0(WM, SPLIT, ph - 1) * 32) * g.N + n_lane);
         // the first sweep of a later phase carries the stores of the phase before it
         using First = std::integral_constant<bool, (ph > 0)>;
         if constexpr (AF) {
@@ -334,16 +353,19 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
 
     // Store of the last phase.  The output mode and the border test are uniform over the workgroup, so
     // straight-line store sequences are chosen per output instead of testing per element.
-    constexpr int LAST = SPLIT - 1;
-    const int64_t m_last = m_lane + LAST * WMP * 32;
+    constexpr int LAST = PHASES - 1;
+    constexpr int WML = split_rows(WM, SPLIT, LAST), ROWL = split_row0(WM, SPLIT, LAST);  // row blocks of the last phase
+    const int64_t m_last = m_lane + ROWL * 32;
     // PAIR (interior tiles, even N, 4-byte aligned fp16 output): neighbouring lanes hold neighbouring columns,
     // and a 2-byte store per lane writes 64-byte runs, which the memory system handles far worse than 128-byte
     // runs (a 16 MiB fp16 output cost 7 us that way).  Rows are taken in pairs: the even lane of a lane pair
     // collects both columns of the first row, the odd lane both columns of the second row (one lane exchange),
     // and each stores one dword.
-    auto emit = [&](auto guard_c, auto i32_c, auto f16_c, auto pair_c) __attribute__((always_inline)) {
+    // NT (interior tiles, a single output): streaming stores.  They gain 3 - 15 % when one output is written (more
+    // the larger the output), and lose as much when the int32 and the fp16 pass follow each other.
+    auto emit = [&](auto guard_c, auto i32_c, auto f16_c, auto pair_c, auto nt_c) __attribute__((always_inline)) {
         constexpr bool GUARD = decltype(guard_c)::value, I32 = decltype(i32_c)::value, F16 = decltype(f16_c)::value,
-                       PAIR = decltype(pair_c)::value;
+                       PAIR = decltype(pair_c)::value, NT = decltype(nt_c)::value;
         int32_t *ci = I32 ? g.c_i32 + m_last * g.N + n_lane : nullptr;
         uint16_t *ch = F16 ? g.c_f16 + m_last * g.N + n_lane : nullptr;
         const bool odd = lane & 1;
@@ -351,7 +373,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
         uint16_t *ch_pair = F16 ? ch + (odd ? g.N - 1 : 0) : nullptr;
         // token scale of row (block bi of the last phase, register v) of this lane, from the lane that loaded it
         auto token_scale = [&](int bi, int v) __attribute__((always_inline)) {
-            const int blk = LAST * WMP + bi;  // row block inside the wave tile: rows 64 (blk / 2) + lane were loaded
+            const int blk = ROWL + bi;  // row block inside the wave tile: rows 64 (blk / 2) + lane were loaded
             const int src = (blk & 1) * 32 + 8 * (v / 4) + 4 * kh + (v % 4);
             const uint32_t both = (uint32_t)__shfl((int)sa_raw[blk / 4], src);
             return half_bits_to_float((uint16_t)((blk / 2) & 1 ? both >> 16 : both & 0xffffu));
@@ -361,7 +383,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
         for (int bj = 0; bj < WN; ++bj)
             sw[bj] = half_bits_to_float((uint16_t)((bj & 1) ? sw_raw[bj / 2] >> 16 : sw_raw[bj / 2] & 0xffffu));
 #pragma unroll
-        for (int bi = 0; bi < WMP; ++bi) {
+        for (int bi = 0; bi < WML; ++bi) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t row = (int64_t)(bi * 32 + 8 * (v / 4) + (v % 4));  // relative to m_last
@@ -372,53 +394,55 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
 #pragma unroll
                 for (int bj = 0; bj < WN; ++bj) {
                     if (GUARD && n_lane + bj * 32 >= g.N) continue;
-                    const float c = acc[LAST][bi][bj][v];  // = C, an integer
-                    if constexpr (I32) ci[row * g.N + bj * 32] = (int32_t)c;
+                    const float c = acc[ROWL + bi][bj][v];  // = C, an integer
+                    if constexpr (I32 && NT) __builtin_nontemporal_store((int32_t)c, &ci[row * g.N + bj * 32]);
+                    if constexpr (I32 && !NT) ci[row * g.N + bj * 32] = (int32_t)c;
                     if constexpr (F16 && !PAIR) ch[row * g.N + bj * 32] = float_to_half_bits(c * sa * sw[bj]);
                     if constexpr (F16 && PAIR) {
                         if (v % 2 == 0) {  // folds once the loop is unrolled
                             const uint32_t h0 = float_to_half_bits(c * sa * sw[bj]);
-                            const uint32_t h1 = float_to_half_bits(acc[LAST][bi][bj][(v + 1) & 15] * sa_next * sw[bj]);
+                            const uint32_t h1 = float_to_half_bits(acc[ROWL + bi][bj][(v + 1) & 15] * sa_next * sw[bj]);
                             const uint32_t give = odd ? h0 : h1, keep = odd ? h1 : h0;
                             // quad_perm [1, 0, 3, 2]: the value of the other lane of the pair
                             const uint32_t got = (uint32_t)__builtin_amdgcn_mov_dpp((int)give, 0xB1, 0xf, 0xf, true);
                             const uint32_t word = odd ? (got | (keep << 16)) : (keep | (got << 16));
-                            *reinterpret_cast<uint32_t *>(ch_pair + row * g.N + bj * 32) = word;
+                            uint32_t *dst = reinterpret_cast<uint32_t *>(ch_pair + row * g.N + bj * 32);
+                            if constexpr (NT) __builtin_nontemporal_store(word, dst);
+                            else *dst = word;
                         }
                     }
                 }
             }
         }
     };
-    if constexpr (SPLIT > 1) {
-        emit(F{}, T{}, F{}, F{});  // interior tiles, int32 output only (checked by the launcher)
+    if constexpr (PHASES > 1) {
+        emit(F{}, T{}, F{}, F{}, T{});  // interior tiles, int32 output only (checked by the launcher)
     } else {
         const bool interior = (m0 + BM <= g.M) && (n0 + BN <= g.N);
         const bool pair = (g.N & 1) == 0 && (reinterpret_cast<uintptr_t>(g.c_f16) & 3u) == 0;
+        const bool single = !(g.c_i32 && g.c_f16);
         // both outputs: one pass per output (a combined pass needs more registers than there are)
         if (g.c_i32) {
-            if (interior) emit(F{}, T{}, F{}, F{});
-            else emit(T{}, T{}, F{}, F{});
+            if (interior && single) emit(F{}, T{}, F{}, F{}, T{});
+            else if (interior) emit(F{}, T{}, F{}, F{}, F{});
+            else emit(T{}, T{}, F{}, F{}, F{});
         }
         if (g.c_f16) {
-            if (interior && pair) emit(F{}, F{}, T{}, T{});
-            else if (interior) emit(F{}, F{}, T{}, F{});
-            else emit(T{}, F{}, T{}, F{});
+            if (interior && pair && single) emit(F{}, F{}, T{}, T{}, T{});
+            else if (interior && pair) emit(F{}, F{}, T{}, T{}, F{});
+            else if (interior) emit(F{}, F{}, T{}, F{}, F{});
+            else emit(T{}, F{}, T{}, F{}, F{});
         }
     }
 }
 
-// The split kernel stores int32 only and needs whole tiles and at least STORE_STAGES stages of K.  It pays
-// where the hidden half of the store (about 3 us for 256 x 256 tiles on all CUs) outweighs the slower
-// k loop (about 2.7 ns per MFMA, measured): up to 16 stages over all sweeps (K <= 4096 with one sweep).
-template <int P, int Q, int WM, int WN>
+// The split kernels store int32 only and need whole tiles and enough stages of K to carry the stores.
+template <int P, int Q, int WM, int WN, int SPLIT>
 inline bool direct_split_usable(const GemmArgs &g)
 {
-    constexpr int store_stages = (WM / 2) * WN * 16 / (4 * (WM / 2) * WN / kStoreEvery);
-    constexpr int sweeps = (activation_field_form(P) ? 1 : (P + 1) / 2) * ((Q + 1) / 2);
     const int64_t nst = g.nkb / 2;
-    return g.c_i32 && !g.c_f16 && g.M % (64 * WM) == 0 && g.N % (64 * WN) == 0 && nst >= store_stages &&
-           sweeps * nst <= 16;
+    return g.c_i32 && !g.c_f16 && g.M % (64 * WM) == 0 && g.N % (64 * WN) == 0 &&
+           nst >= split_store_stages(WM, WN, SPLIT);
 }
 
 template <int P, int Q, int WM, int WN, int SPLIT = 1>

@@ -39,11 +39,27 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream)
         return launch_direct_variant<P, Q, 2, 2>(g, stream);
     } else {
         switch (best) {
-        case 0:
-            // APMM_MFMA_SPLIT=0 forces the one-phase kernel (debugging)
-            if (direct_split_usable<P, Q, 4, 4>(g) && !(no_split && no_split[0] == '0'))
-                return launch_direct_variant<P, Q, 4, 4, 2>(g, stream);
+        case 0: {
+            // Two-phase kernels (part of the store under the k loop).  APMM_MFMA_SPLIT=0, 2, 3 forces the one-phase,
+            // the even or the uneven one where usable (debugging); otherwise the measured rule.  A split pays when
+            // the store is exposed and the memory system is the limit: one round of tiles on most of the chip
+            // (with more rounds the next tile's k loop already covers the store, with few tiles the store is
+            // fast), one sweep, K of at most 16 stages (beyond, the slower k loop costs what the store saves).
+            // The uneven cut wins over the even one when the weight group is a single plane (cheapest expansion,
+            // which the short second phase repeats per row block).
+            constexpr int sweeps = ((P + 1) / 2) * ((Q + 1) / 2);
+            const int64_t nst = g.nkb / 2;
+            const int64_t tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256);
+            const bool pays = sweeps * nst <= 16 && tiles > 128 && tiles <= 256;
+            const char want = no_split ? no_split[0] : 0;
+            if constexpr (Q == 1) {
+                const bool ok3 = direct_split_usable<P, Q, 4, 4, 3>(g);
+                if (ok3 && (want == '3' || (want == 0 && pays))) return launch_direct_variant<P, Q, 4, 4, 3>(g, stream);
+            }
+            const bool ok2 = direct_split_usable<P, Q, 4, 4, 2>(g);
+            if (ok2 && (want == '2' || (want == 0 && pays))) return launch_direct_variant<P, Q, 4, 4, 2>(g, stream);
             return launch_direct_variant<P, Q, 4, 4>(g, stream);
+        }
         case 1: return launch_direct_variant<P, Q, 4, 2>(g, stream);
         case 2: return launch_direct_variant<P, Q, 2, 4>(g, stream);
         default: return launch_direct_variant<P, Q, 2, 2>(g, stream);

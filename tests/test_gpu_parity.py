@@ -292,16 +292,14 @@ def test_degenerate_shapes(gpu, oracle, M, N, K):
     check_f16(c16, want, data, oracle)
 
 
-@pytest.mark.parametrize("p,q,K", [(2, 1, 2048), (1, 1, 4096), (2, 2, 2560), (3, 1, 2048), (4, 2, 2048)])
-def test_two_phase_kernel_whole_tiles(gpu, oracle, p, q, K):
-    """Whole 256 x 256 tiles, int32 output only and a short K: the MFMA kernel that stores its first
-    half under the k loop of the second is the one that runs."""
-    case = dict(M=512, N=768, K=K, p=p, q=q, a_dist="bernoulli", scaled=False)
-    data = inputs.make_case(case, 7000 + 10 * p + q)
-    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
-    for algo in (FP4, 0):
-        c32, _ = run_case(gpu, data, case, algo=algo, want_f16=False)
-        assert np.array_equal(c32.astype(np.int64), want), "algo %d" % algo
+@pytest.mark.parametrize("p,q,K", [(2, 1, 2048), (1, 1, 4096), (2, 2, 2560), (2, 1, 3072), (2, 2, 4096), (1, 2, 3500),
+                                   (2, 1, 3584)])
+def test_two_phase_kernels(gpu, oracle, p, q, K):
+    """130 whole 256 x 256 tiles, int32 output only, one sweep of at most 4096 k: the launch rule picks the MFMA
+    kernels that store the first part of a tile under the k loop of the second (the uneven cut for 1-bit weights
+    from K = 3072 on, else the even one).  Sampled rows x columns against the oracle, checksums over every output."""
+    case = dict(M=3328, N=2560, K=K, p=p, q=q, a_dist="bernoulli", scaled=False)
+    sampled_check(gpu, oracle, case, 7000 + 10 * p + q)
 
 
 def test_long_k_beyond_the_fp32_exactness_bound(gpu, oracle):
