@@ -145,12 +145,13 @@ apmm_status apmm_gemm_from_codes(int64_t M, int64_t N, int64_t K, int p, int q,
 /* One linear of a grouped call: C = A * W^T with the arguments of apmm_gemm. */
 typedef struct apmm_problem {
     int64_t M, N, K;
-    const void *a_packed;     /* device, packed M x K activations of p bits */
+    const void *a_packed;     /* device, packed M x K activations of p bits; ignored when a_codes is given */
     const void *w_packed;     /* device, packed N x K weights of q bits */
     int32_t *c_i32;           /* device, M x N, or NULL */
     uint16_t *c_f16;          /* device, M x N binary16 bit patterns, or NULL */
     const uint16_t *w_scale;  /* device, N, or NULL */
     const uint16_t *a_scale;  /* device, M, or NULL */
+    const uint8_t *a_codes;   /* device, M x K unpacked activation codes as for apmm_gemm_from_codes, or NULL */
 } apmm_problem;
 
 /* Several independent GEMMs of equal p and q with as few launches as possible (for callers whose
@@ -159,7 +160,10 @@ typedef struct apmm_problem {
  * `problems` is a HOST array of `count` entries, read before the call returns.  Each entry obeys the
  * rules of apmm_gemm and gives the same result as apmm_gemm on it.  Small-M problems that the same
  * small-M kernel covers are launched eight at a time; all others are launched one by one.  The outputs
- * of different entries must not overlap.  At most 256 entries.  On an argument error nothing is launched. */
+ * of different entries must not overlap.  At most 256 entries.  On an argument error nothing is launched.
+ * An entry with a_codes takes its activations unpacked, as apmm_gemm_from_codes does in its one-launch
+ * form (no packing launch, no packed buffer); such an entry must be a shape the small-M kernels cover,
+ * else the call returns APMM_ERR_UNSUPPORTED.  Entries with and without a_codes do not share a launch. */
 apmm_status apmm_gemm_grouped(int count, const apmm_problem *problems, int p, int q,
                               void *workspace, size_t workspace_bytes, void *stream);
 

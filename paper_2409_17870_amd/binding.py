@@ -27,7 +27,7 @@ class ApmmProblem(ctypes.Structure):
     _fields_ = [("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
                 ("a_packed", ctypes.c_void_p), ("w_packed", ctypes.c_void_p),
                 ("c_i32", ctypes.c_void_p), ("c_f16", ctypes.c_void_p),
-                ("w_scale", ctypes.c_void_p), ("a_scale", ctypes.c_void_p)]
+                ("w_scale", ctypes.c_void_p), ("a_scale", ctypes.c_void_p), ("a_codes", ctypes.c_void_p)]
 
 
 _lib = None
@@ -218,13 +218,14 @@ def apmm_version():
 def apmm_gemm_grouped(problems, p, q):
     """Several GEMMs of equal p, q with as few launches as possible.
 
-    problems: list of dicts with keys M, N, K, a_packed, w_packed and optionally c_i32, c_f16 (output
-    tensors), w_scale, a_scale.  Outputs must be preallocated by the caller.
+    problems: list of dicts with keys M, N, K, w_packed, a_packed or a_codes (unpacked uint8 codes, small-M
+    shapes only) and optionally c_i32, c_f16 (output tensors), w_scale, a_scale.  Outputs must be preallocated
+    by the caller.
     """
     arr = (ApmmProblem * max(len(problems), 1))()
     for i, pr in enumerate(problems):
         arr[i].M, arr[i].N, arr[i].K = pr["M"], pr["N"], pr["K"]
-        for key in ("a_packed", "w_packed", "c_i32", "c_f16", "w_scale", "a_scale"):
+        for key in ("a_packed", "w_packed", "c_i32", "c_f16", "w_scale", "a_scale", "a_codes"):
             t = pr.get(key)
             setattr(arr[i], key, t.data_ptr() if t is not None else None)
     _check(load().apmm_gemm_grouped(len(problems), arr, p, q, None, 0, _stream()))

@@ -257,9 +257,12 @@ apmm_status apmm_gemm_grouped(int count, const apmm_problem *problems, int p, in
     for (int i = 0; i < count; ++i) {
         const apmm_problem &pr = problems[i];
         bool empty;
-        const apmm_status st = check_gemm(pr.M, pr.N, pr.K, p, q, pr.a_packed, pr.w_packed, pr.c_i32, pr.c_f16,
-                                          pr.w_scale, pr.a_scale, args[live], empty);
+        const bool codes = pr.a_codes != nullptr;
+        const apmm_status st = check_gemm(pr.M, pr.N, pr.K, p, q, codes ? static_cast<const void *>(pr.a_codes) : pr.a_packed,
+                                          pr.w_packed, pr.c_i32, pr.c_f16, pr.w_scale, pr.a_scale, args[live], empty, codes);
         if (st != APMM_OK) return st;
+        if (codes && !empty && !apmm::gemm_decode_supported(args[live]))
+            return fail(APMM_ERR_UNSUPPORTED, "gemm_grouped: an entry with a_codes must be a shape the small-M kernels cover");
         if (!empty) ++live;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);

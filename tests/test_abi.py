@@ -132,7 +132,9 @@ def test_new_entry_points_check_their_arguments(lib):
     assert grouped(2, arr, 2, 2, None, 0, None) == INVALID              # nothing is launched for the first either
     arr[1].c_i32, arr[1].K = 0x3000, 40000
     assert grouped(2, arr, 8, 8, None, 0, None) == OVERFLOW
-    arr[1].K, arr[1].M = 128, 0                                         # an empty entry is skipped; the other would launch
+    arr[1].K = 128
+    arr[0].a_codes, arr[0].a_packed, arr[0].M = 0x5001, None, 100      # unpacked codes: only shapes of the small-M kernels
+    assert grouped(2, arr, 2, 2, None, 0, None) == 2
     big = (ApmmProblem * 300)()
     assert grouped(300, big, 2, 2, None, 0, None) == INVALID            # more entries than one call takes
 

@@ -368,11 +368,13 @@ def test_grouped_launch_matches_single_calls_and_the_oracle(gpu, oracle, M):
         if K not in acts:
             a = inputs.bernoulli_codes(9000 + K, inputs.TAG_A, M, K, p)
             sa = inputs.scales_f16(9000 + K, inputs.TAG_A_SCALE, M)
-            acts[K] = (a, binding.apmm_pack_activations(torch.from_numpy(a).to(dev), p), sa, torch.from_numpy(sa).to(dev))
-        a, ap, sa, sa_dev = acts[K]
+            a_dev = torch.from_numpy(a).to(dev)
+            acts[K] = (a, binding.apmm_pack_activations(a_dev, p), sa, torch.from_numpy(sa).to(dev), a_dev)
+        a, ap, sa, sa_dev, a_dev = acts[K]
         w = inputs.bernoulli_codes(9100 + i, inputs.TAG_W, N, K, q)
         sw = inputs.scales_f16(9100 + i, inputs.TAG_W_SCALE, N)
-        problems.append(dict(M=M, N=N, K=K, a_packed=ap, w_packed=binding.apmm_pack_weights(torch.from_numpy(w).to(dev), q),
+        problems.append(dict(M=M, N=N, K=K, a_packed=ap, a_dev=a_dev,
+                             w_packed=binding.apmm_pack_weights(torch.from_numpy(w).to(dev), q),
                              c_i32=torch.zeros((M, N), dtype=torch.int32, device=dev),
                              c_f16=torch.zeros((M, N), dtype=torch.float16, device=dev),
                              w_scale=torch.from_numpy(sw).to(dev), a_scale=sa_dev))
@@ -385,6 +387,19 @@ def test_grouped_launch_matches_single_calls_and_the_oracle(gpu, oracle, M):
         got = pr["c_f16"].cpu().numpy().astype(np.float64)
         assert np.all(np.abs(got - f) <= 1e-3 * np.abs(f) + 1e-6)
     binding.apmm_gemm_grouped([], p, q)                                 # nothing to do
+    # the same list with the activations as unpacked codes (every second entry, so that runs of both kinds form)
+    mixed = []
+    for i, pr in enumerate(problems):
+        e = dict(pr, c_i32=torch.zeros_like(pr["c_i32"]), c_f16=torch.zeros_like(pr["c_f16"]))
+        if i % 3 != 2:
+            e["a_codes"], e["a_packed"] = pr["a_dev"], None
+        mixed.append(e)
+    binding.apmm_gemm_grouped(mixed, p, q)
+    torch.cuda.synchronize()
+    for pr, (want, f) in zip(mixed, wants):
+        assert np.array_equal(pr["c_i32"].cpu().numpy().astype(np.int64), want)
+        got = pr["c_f16"].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - f) <= 1e-3 * np.abs(f) + 1e-6)
 
 
 def test_extreme_values_hit_the_bound(gpu, oracle):
