@@ -31,18 +31,24 @@ constexpr int kThreads = 64 * kWaves;
 constexpr int kRowsPerWg = 16;
 constexpr int kMaxLdsBytes = 128 * 1024;
 
-// Words 4*hh .. 4*hh+3 of plane i of an n-bit operand in the common form, from the slots of one row and
-// k block (`slots` points at the uint4 of slot 0; consecutive slots are kPlaneWords / 4 apart).
-__device__ __forceinline__ uint4 plane_half_words(const uint4 *slots, int n, int i, int hh)
+// Words 4*hh .. 4*hh+3 of plane i of an n-bit operand in the common form come from one 16-byte vector of the
+// slots of a row and k block (`slots` points at the uint4 of slot 0; consecutive slots are kPlaneWords / 4
+// apart): plane_half_src gives its address, plane_half_from turns the loaded vector into the words.
+__device__ __forceinline__ const uint4 *plane_half_src(const uint4 *slots, int n, int i, int hh)
 {
     constexpr int kSlotVec = kPlaneWords / 4;
+    return slots + (i < 2 * pair_groups(n) ? (i / 2 * 2 + hh) : (n - 1)) * kSlotVec;
+}
+
+__device__ __forceinline__ uint4 plane_half_from(const uint4 raw, int n, int i, int hh)
+{
     if (i < 2 * pair_groups(n)) {
-        const uint4 s = slots[(i / 2 * 2 + hh) * kSlotVec];  // S[4 hh .. 4 hh + 3] of pair group i / 2
+        const uint4 s = raw;  // S[4 hh .. 4 hh + 3] of pair group i / 2
         const int b = i & 1;
         return make_uint4((s.x >> b) & 0x55555555u, (s.y >> b) & 0x55555555u, (s.z >> b) & 0x55555555u,
                           (s.w >> b) & 0x55555555u);
     }
-    const uint4 l = slots[(n - 1) * kSlotVec];
+    const uint4 l = raw;
     // word w = 4 hh + x: k step 2 hh + x / 2, words L[2 (x % 2)], L[2 (x % 2) + 1]
     const int k0 = 2 * hh, k1 = 2 * hh + 1;
     return make_uint4(((l.x >> k0) & 0x11111111u) | (((l.y >> k0) & 0x11111111u) << 2),
@@ -112,12 +118,22 @@ __device__ __forceinline__ void load_code_block(const uint8_t *__restrict__ code
 template <int MT, int Q, bool CODES>
 __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GroupArgs ga)
 {
-    // which problem of the launch this workgroup works on (uniform over the workgroup)
-    int idx = 0;
-    for (int i = 0; i + 1 < ga.count; ++i)
-        if ((int)blockIdx.x >= ga.wg_end[i]) idx = i + 1;
-    const GemmArgs g = ga.g[idx];
-    const int block = (int)blockIdx.x - (idx ? ga.wg_end[idx - 1] : 0);
+    // Which problem of the launch this workgroup works on (uniform over the workgroup).  Problem 0 is read from
+    // fixed kernel-argument offsets, so that a launch of one problem needs a single round of scalar loads before
+    // the first weight address is known (every dependent round costs a few hundred ns in a kernel of a few us).
+    GemmArgs g = ga.g[0];
+    int64_t chunk_kb = ga.chunk_kb[0];
+    int block = (int)blockIdx.x;
+    if (ga.count > 1) {
+        int idx = 0;
+        for (int i = 0; i + 1 < ga.count; ++i)
+            if ((int)blockIdx.x >= ga.wg_end[i]) idx = i + 1;
+        if (idx > 0) {
+            g = ga.g[idx];
+            chunk_kb = ga.chunk_kb[idx];
+            block -= ga.wg_end[idx - 1];
+        }
+    }
     extern __shared__ __align__(16) uint8_t lds_raw[];
     uint4 *a_lds = reinterpret_cast<uint4 *>(lds_raw);  // [kb][m < MT][j < p][hh < 2] plane words, common form
     const int p = g.p;
@@ -129,26 +145,49 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GroupArgs ga)
     const int64_t n_ld = n < round_up(g.N, kRowBlock) ? n : round_up(g.N, kRowBlock) - 1;
     constexpr int kSlotVec = kPlaneWords / 4;
 
-    // what the final store needs is requested first: a dependent round trip to memory at the end of
-    // a kernel this short would be a quarter of its duration
-    const int out_m = tid / kRowsPerWg;
-    const int64_t out_n = n0 + tid % kRowsPerWg;
-    const bool out_thread = tid < MT * kRowsPerWg && out_m < g.M && out_n < g.N;
-    float out_sa = 1.0f, out_sw = 1.0f;
-    if (out_thread && g.c_f16) {
-        out_sa = load_scale(g.a_scale, out_m);
-        out_sw = load_scale(g.w_scale, out_n);
+    // Order of the requests.  Loads return in order, so whatever is requested before the weights can be used
+    // while the weights are still on their way, and whatever is requested after them cannot.  First therefore
+    // this thread's first chunk of activations (packed input; usually its only one), which goes to LDS and
+    // through a barrier before the k loop; then the weights of the first k block, whose latency is the
+    // longest thing in this kernel; then what only the final store needs.
+    const uint32_t chunks_per_kb = (uint32_t)(MT * p * 2);
+    const uint32_t chunks_pass0 = (uint32_t)(chunk_kb < g.nkb ? chunk_kb : g.nkb) * chunks_per_kb;
+    // chunk c of a pass that starts at k block kb0: (k block, row m, plane j, half hh)
+    auto chunk_src = [&](uint32_t c, int64_t kb0, uint32_t &j, uint32_t &hh) {
+        const uint32_t ckb = c / chunks_per_kb;
+        const uint32_t rem = c - ckb * chunks_per_kb, plane = rem >> 1, m = plane / p;
+        j = plane - m * p;
+        hh = rem & 1;
+        const uint4 *slots = reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, kb0 + ckb, g.nkb, p, 0));
+        return plane_half_src(slots, p, j, hh);
+    };
+    uint4 a_first = make_uint4(0, 0, 0, 0);
+    uint32_t a_first_j = 0, a_first_hh = 0;
+    if constexpr (!CODES) {
+        if ((uint32_t)tid < chunks_pass0) a_first = *chunk_src(tid, 0, a_first_j, a_first_hh);
     }
 
-    // the weights of the first k block are requested before anything else: their latency is the
-    // longest thing in this kernel and overlaps with the copy of the activations
+    // (Everything from here to the LDS writes is loaded without a condition, from clamped addresses where the
+    // thread has nothing to load: the wait for the activations may leave exactly these loads outstanding only
+    // if every thread issues all of them.)
     int64_t kb = 4 * (int64_t)wave + sub;
     uint4 wnext[Q];
-    if (kb < g.nkb) {
-        const uint4 *wsrc = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld, kb, g.nkb, Q, 0));
+    {
+        const int64_t kb_ld = kb < g.nkb ? kb : g.nkb - 1;
+        const uint4 *wsrc = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld, kb_ld, g.nkb, Q, 0));
 #pragma unroll
         for (int s = 0; s < Q; ++s) wnext[s] = wsrc[s * kSlotVec];
     }
+
+    // What the final store needs is requested now as well (a dependent round trip to memory at the end of a
+    // kernel this short would be a quarter of its duration) and kept as loaded: nothing may use the values
+    // before the end, or the wave would wait for them here.  A missing scale vector reads a weight word instead.
+    const int out_m = tid / kRowsPerWg;
+    const int64_t out_n = n0 + tid % kRowsPerWg;
+    const bool out_thread = tid < MT * kRowsPerWg && out_m < g.M && out_n < g.N;
+    const uint16_t *dummy = reinterpret_cast<const uint16_t *>(g.w);
+    uint32_t out_sa_bits = *(g.a_scale ? g.a_scale + (out_m < g.M ? out_m : g.M - 1) : dummy);
+    uint32_t out_sw_bits = *(g.w_scale ? g.w_scale + (out_n < g.N ? out_n : g.N - 1) : dummy);
 
     uint32_t acc[MT];  // sum_ij 2^(i+j) popcount, modulo 2^32
 #pragma unroll
@@ -157,18 +196,16 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GroupArgs ga)
     // The activations of chunk_kb k blocks at a time sit in LDS (all of K when it fits, which is the usual
     // case): chunk (kb, m, j, hh) = four words of plane j of row m in k block kb.  A pass boundary is a multiple
     // of 32 k blocks, i.e. of the stride of the lanes' k blocks.
-    const int chunks_per_kb = MT * p * 2;
-    const int64_t chunk_kb = ga.chunk_kb[idx];
     for (int64_t kb0 = 0; kb0 < g.nkb; kb0 += chunk_kb) {
         const int64_t kb_end = kb0 + chunk_kb < g.nkb ? kb0 + chunk_kb : g.nkb;
         if (kb0) __syncthreads();  // every wave is done with the previous pass
         if constexpr (CODES) {
             // straight from the codes: a thread takes the 128 codes of (row m, k block) and writes every plane j in
             // the common form: word w = 2 ks + tp holds elements (ks, t = 2 tp + tt, jh, c) at bit 8c + 4jh + 2tt
-            const int64_t pass_kb = kb_end - kb0, total_blocks = pass_kb * MT;
-            for (int64_t c = tid; c < total_blocks; c += kThreads) {  // consecutive lanes: consecutive 128 bytes of a row
-                const int m = (int)(c / pass_kb);
-                const int64_t ckb = c % pass_kb;
+            // (32-bit index arithmetic: a pass holds at most 8192 sixteen-byte chunks)
+            const uint32_t pass_kb = (uint32_t)(kb_end - kb0), total_blocks = pass_kb * MT;
+            for (uint32_t c = tid; c < total_blocks; c += kThreads) {  // consecutive lanes: consecutive 128 bytes of a row
+                const uint32_t m = c / pass_kb, ckb = c - m * pass_kb;
                 uint32_t d[32];
                 load_code_block(g.a_codes, g.M, g.K, p, m, kb0 + ckb, d);
                 for (int j = 0; j < p; ++j) {
@@ -188,12 +225,16 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GroupArgs ga)
                 }
             }
         } else {
-            const int64_t total_chunks = (kb_end - kb0) * chunks_per_kb;
-            for (int64_t c = tid; c < total_chunks; c += kThreads) {
-                const int64_t ckb = c / chunks_per_kb;
-                const int rem = (int)(c % chunks_per_kb), m = rem / (2 * p), j = (rem >> 1) % p, hh = rem & 1;
-                const uint4 *slots = reinterpret_cast<const uint4 *>(g.a + tile_row_word(m, kb0 + ckb, g.nkb, p, 0));
-                a_lds[c] = plane_half_words(slots, p, j, hh);
+            const uint32_t total_chunks = (uint32_t)(kb_end - kb0) * chunks_per_kb;
+            uint32_t c = tid;
+            if (kb0 == 0) {  // the chunk requested at the top
+                if (c < total_chunks) a_lds[c] = plane_half_from(a_first, p, a_first_j, a_first_hh);
+                c += kThreads;
+            }
+            for (; c < total_chunks; c += kThreads) {
+                uint32_t j, hh;
+                const uint4 raw = *chunk_src(c, kb0, j, hh);
+                a_lds[c] = plane_half_from(raw, p, j, hh);
             }
         }
         __syncthreads();
@@ -249,7 +290,10 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_kernel(GroupArgs ga)
 #pragma unroll
         for (int w8 = 0; w8 < kWaves; ++w8) s += part[(w8 * MT + out_m) * kRowsPerWg + tid % kRowsPerWg];
         const uint32_t full = (uint32_t)g.K * (uint32_t)((1 << p) - 1) * (uint32_t)((1 << Q) - 1);
-        store_output(g, out_m, out_n, (int32_t)(full - 2u * s), out_sa, out_sw);
+        out_sa_bits = g.a_scale ? use_here(out_sa_bits) : 0x3c00u;  // 1.0
+        out_sw_bits = g.w_scale ? use_here(out_sw_bits) : 0x3c00u;
+        store_output(g, out_m, out_n, (int32_t)(full - 2u * s), half_bits_to_float((uint16_t)out_sa_bits),
+                     half_bits_to_float((uint16_t)out_sw_bits));
     }
 }
 
@@ -345,12 +389,21 @@ hipError_t launch_mt(const GroupArgs &ga, hipStream_t stream)
 template <int P, int Q, int TT, int RT, bool CODES>
 __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga)
 {
-    // which problem of the launch this workgroup works on (uniform over the workgroup)
-    int idx = 0;
-    for (int i = 0; i + 1 < ga.count; ++i)
-        if ((int)blockIdx.x >= ga.wg_end[i]) idx = i + 1;
-    const GemmArgs g = ga.g[idx];
-    const int block = (int)blockIdx.x - (idx ? ga.wg_end[idx - 1] : 0);
+    // which problem of the launch this workgroup works on (uniform over the workgroup); problem 0 from fixed
+    // kernel-argument offsets (see gemm_decode_kernel)
+    GemmArgs g = ga.g[0];
+    int64_t chunk_kb = ga.chunk_kb[0];
+    int block = (int)blockIdx.x;
+    if (ga.count > 1) {
+        int idx = 0;
+        for (int i = 0; i + 1 < ga.count; ++i)
+            if ((int)blockIdx.x >= ga.wg_end[i]) idx = i + 1;
+        if (idx > 0) {
+            g = ga.g[idx];
+            chunk_kb = ga.chunk_kb[idx];
+            block -= ga.wg_end[idx - 1];
+        }
+    }
     static_assert(P <= 2 && Q <= 2, "one plane group per operand");
     constexpr int TOKENS = 16 * TT, ROWS = kRowsPerWg * RT;
     constexpr int OUTS = (TT * RT * 256 + kThreads - 1) / kThreads;  // outputs per thread
@@ -367,44 +420,67 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) n_ld[rt] = n0 + rt * 16 + r16 < rows_b ? n0 + rt * 16 + r16 : rows_b - 1;
 
-    // What the final store needs is requested first (see gemm_decode_kernel).  Output o of this thread is
-    // element (tile t = (tid + o * kThreads) / 256, register v, lane l) of the accumulators, t = rt * TT + tt;
-    // 16x16 accumulator layout: lane l, register v holds row 4*(l/16) + v (weight row), column l%16 (token).
+    // Order of the requests (see gemm_decode_kernel): this thread's first two vectors of packed activations, then
+    // the weights of the first k block, then what only the final store needs.
+    const int64_t rows_a = round_up(g.M, kRowBlock);
+    const uint32_t vecs_pass0 = (uint32_t)(chunk_kb < g.nkb ? chunk_kb : g.nkb) * P * TOKENS;
+    // vector c of a pass that starts at k block kb0 is (k block, slot, token); LDS index = c with slot and token swapped
+    auto vec_src = [&](uint32_t c, int64_t kb0, uint32_t &lds_index) {
+        const uint32_t m = c % TOKENS, s = (c / TOKENS) % P, ckb = (c / TOKENS) / P;
+        const int64_t m_ld = m < rows_a ? m : rows_a - 1;  // tokens past the padded rows are clamped and never stored
+        lds_index = (ckb * TOKENS + m) * P + s;
+        return reinterpret_cast<const uint4 *>(g.a + tile_row_word(m_ld, kb0 + ckb, g.nkb, P, s));
+    };
+    constexpr int PEEL = 2;
+    uint4 a_first[PEEL];
+    uint32_t a_first_index[PEEL];
+    if constexpr (!CODES) {
+#pragma unroll
+        for (int i = 0; i < PEEL; ++i) {
+            a_first[i] = make_uint4(0, 0, 0, 0);
+            a_first_index[i] = 0;
+            if ((uint32_t)tid + i * kThreads < vecs_pass0) a_first[i] = *vec_src(tid + i * kThreads, 0, a_first_index[i]);
+        }
+    }
+
+    // (from here to the LDS writes every thread issues every load, from clamped addresses where it has nothing
+    // to load, see gemm_decode_kernel)
+    int64_t kb4 = wave;
+    uint4 wnext[RT][2];
+    {
+        const int64_t kb_ld = kb4 * 4 < g.nkb ? kb4 * 4 + kq : g.nkb - 4 + kq;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const uint4 *wsrc = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld[rt], kb_ld, g.nkb, Q, 0));
+#pragma unroll
+            for (int s = 0; s < Q; ++s) wnext[rt][s] = wsrc[s * kSlotVec];
+        }
+    }
+
+    // What the final store needs is requested now as well and kept as loaded (see gemm_decode_kernel): code sums
+    // PA[m], PW[n] and the scales.  Output o of this thread is element (tile t = (tid + o * kThreads) / 256,
+    // register v, lane l) of the accumulators, t = rt * TT + tt; 16x16 accumulator layout: lane l, register v holds
+    // row 4*(l/16) + v (weight row), column l%16 (token).
     bool out_ok[OUTS];
     int out_m[OUTS];
     int64_t out_n[OUTS];
-    float out_sa[OUTS], out_sw[OUTS];
-    uint32_t out_terms[OUTS];  // - 2 cw PA[m] - 2 ca PW[n] + K ca cw
+    uint32_t out_sa_bits[OUTS], out_sw_bits[OUTS], out_pa[OUTS], out_pw[OUTS];
 #pragma unroll
     for (int o = 0; o < OUTS; ++o) {
         const int e = tid + o * kThreads, t = e >> 8, v = (e >> 6) & 3, l = e & 63;
         out_m[o] = (t % TT) * 16 + (l & 15);
         out_n[o] = n0 + (t / TT) * 16 + 4 * (l >> 4) + v;
         out_ok[o] = t < TT * RT && out_m[o] < g.M && out_n[o] < g.N;
-        out_sa[o] = out_sw[o] = 1.0f;
-        out_terms[o] = 0;
-        if (out_ok[o]) {
-            // (with activation codes as input the row sum PA[m] is taken while packing and added below)
-            out_terms[o] = (uint32_t)g.K * ca * cw - (CODES ? 0u : 2u * cw * (uint32_t)g.a_sum[out_m[o]]) -
-                           2u * ca * (uint32_t)g.w_sum[out_n[o]];
-            if (g.c_f16) {
-                out_sa[o] = load_scale(g.a_scale, out_m[o]);
-                out_sw[o] = load_scale(g.w_scale, out_n[o]);
-            }
-        }
-    }
-
-    // the weights of the first k block are requested before anything else: their latency is the
-    // longest thing in this kernel and overlaps with the copy of the activations
-    int64_t kb4 = wave;
-    uint4 wnext[RT][2];
-    if (kb4 * 4 < g.nkb) {
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            const uint4 *wsrc = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld[rt], kb4 * 4 + kq, g.nkb, Q, 0));
-#pragma unroll
-            for (int s = 0; s < Q; ++s) wnext[rt][s] = wsrc[s * kSlotVec];
-        }
+        // clamped to the padded rows of the sums and to the last entry of the scales; a missing scale vector reads
+        // a weight word instead (replaced by 1.0 at the end)
+        const int64_t m_c = out_m[o] < rows_a ? out_m[o] : rows_a - 1, n_c = out_n[o] < rows_b ? out_n[o] : rows_b - 1;
+        const uint16_t *dummy = reinterpret_cast<const uint16_t *>(g.w);
+        // (with activation codes as input the row sum PA[m] is taken while packing, see below)
+        out_pa[o] = 0;
+        if constexpr (!CODES) out_pa[o] = (uint32_t)g.a_sum[m_c];
+        out_pw[o] = (uint32_t)g.w_sum[n_c];
+        out_sa_bits[o] = *(g.a_scale ? g.a_scale + (m_c < g.M ? m_c : g.M - 1) : dummy);
+        out_sw_bits[o] = *(g.w_scale ? g.w_scale + (n_c < g.N ? n_c : g.N - 1) : dummy);
     }
 
     mfma::v4f acc[RT][TT];
@@ -415,7 +491,6 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga
 
     // The activations of chunk_kb k blocks at a time sit in LDS (all of K when it fits, the usual case); a pass
     // boundary is a multiple of 32 k blocks, the stride of the waves' groups of four k blocks.
-    const int64_t chunk_kb = ga.chunk_kb[idx];
     uint32_t *pa_lds = reinterpret_cast<uint32_t *>(lds_raw) + chunk_kb * TOKENS * P * 4;  // behind the words
     if constexpr (CODES) {
         if (tid < TOKENS) pa_lds[tid] = 0u;  // token code sums, taken while packing (made visible by the barriers below)
@@ -427,10 +502,9 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga
         if constexpr (CODES) {
             // Straight from the codes: a thread takes the 128 codes of (token m, k block), writes them as the packed
             // words of that row and block (apmm_layout.h) and adds them to the token's code sum.
-            const int64_t total_blocks = pass_kb * TOKENS;
-            for (int64_t c = tid; c < total_blocks; c += kThreads) {  // consecutive lanes: consecutive 128 bytes of a row
-                const int m = (int)(c / pass_kb);
-                const int64_t ckb = c % pass_kb;
+            const uint32_t total_blocks = (uint32_t)pass_kb * TOKENS;
+            for (uint32_t c = tid; c < total_blocks; c += kThreads) {  // consecutive lanes: consecutive 128 bytes of a row
+                const uint32_t m = c / (uint32_t)pass_kb, ckb = c - m * (uint32_t)pass_kb;
                 uint32_t d[32];
                 load_code_block(g.a_codes, g.M, g.K, P, m, kb0 + ckb, d);
                 uint32_t sum = 0;
@@ -468,16 +542,19 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga
             }
         } else {
             // 16 tokens of a slot are 256 contiguous bytes (tokens past M: the last padded row block holds zero
-            // words up to a multiple of 32, tokens beyond it are clamped and never stored)
-            const int64_t rows_a = round_up(g.M, kRowBlock);
-            const int64_t total_vecs = pass_kb * P * TOKENS;
-            for (int64_t c = tid; c < total_vecs; c += kThreads) {
-                const int m = (int)(c % TOKENS);
-                const int s = (int)((c / TOKENS) % P);
-                const int64_t ckb = (c / TOKENS) / P;
-                const int64_t m_ld = m < rows_a ? m : rows_a - 1;
-                a_lds[(ckb * TOKENS + m) * P + s] =
-                    *reinterpret_cast<const uint4 *>(g.a + tile_row_word(m_ld, kb0 + ckb, g.nkb, P, s));
+            // words up to a multiple of 32)
+            const uint32_t total_vecs = (uint32_t)pass_kb * P * TOKENS;
+            uint32_t c = tid;
+            if (kb0 == 0) {  // the vectors requested at the top
+#pragma unroll
+                for (int i = 0; i < PEEL; ++i)
+                    if (c + i * kThreads < total_vecs) a_lds[a_first_index[i]] = a_first[i];
+                c += PEEL * kThreads;
+            }
+            for (; c < total_vecs; c += kThreads) {
+                uint32_t index;
+                const uint4 v = *vec_src(c, kb0, index);
+                a_lds[index] = v;
             }
         }
         __syncthreads();
@@ -485,7 +562,7 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga
             if (kb_end == g.nkb) {  // the code sums are complete
 #pragma unroll
                 for (int o = 0; o < OUTS; ++o)
-                    if (out_ok[o]) out_terms[o] -= 2u * cw * pa_lds[out_m[o]];
+                    if (out_ok[o]) out_pa[o] = pa_lds[out_m[o]];
             }
         }
 
@@ -559,7 +636,12 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga
         float s = 0.f;
 #pragma unroll
         for (int w8 = 0; w8 < kWaves; ++w8) s += part[w8 * RT * TT * 256 + e];
-        store_output(g, out_m[o], out_n[o], (int32_t)((uint32_t)(int32_t)s + out_terms[o]), out_sa[o], out_sw[o]);
+        // C = 4 S - 2 cw PA[m] - 2 ca PW[n] + K ca cw
+        const uint32_t terms = (uint32_t)g.K * ca * cw - 2u * cw * use_here(out_pa[o]) - 2u * ca * use_here(out_pw[o]);
+        const uint32_t sa_bits = g.a_scale ? use_here(out_sa_bits[o]) : 0x3c00u;  // 1.0
+        const uint32_t sw_bits = g.w_scale ? use_here(out_sw_bits[o]) : 0x3c00u;
+        store_output(g, out_m[o], out_n[o], (int32_t)((uint32_t)(int32_t)s + terms), half_bits_to_float((uint16_t)sa_bits),
+                     half_bits_to_float((uint16_t)sw_bits));
     }
 }
 
@@ -671,5 +753,6 @@ hipError_t launch_gemm_decode_group(const GemmArgs *gs, int count, hipStream_t s
 }
 
 hipError_t launch_gemm_decode(const GemmArgs &g, hipStream_t stream) { return launch_gemm_decode_group(&g, 1, stream); }
+
 
 }  // namespace apmm
