@@ -76,7 +76,6 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
     constexpr int STORE_STAGES = split_store_stages(WM, WN, SPLIT);  // stages of phase 1 that carry stores
     static_assert(STORE_STAGES % 2 == 0, "store schedule");
     constexpr uint32_t ca = (1u << P) - 1, cw = (1u << Q) - 1;
-    using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
     using NoStore = std::integral_constant<int, -1>;
 
@@ -109,38 +108,126 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
     const int64_t m_lane = m0 + wave_m * WM * 32 + kh * 4, n_lane = n0 + wave_n * WN * 32 + r32;
 
     v16f acc[WM][WN];  // by row block of the wave tile; phase ph owns blocks split_row0(ph) ...
-    // The accumulators start at the recovery terms rt[m] + ct[n], rt = -2 cw PA, ct = K ca cw - 2 ca PW: a
-    // rank-2 matrix, written by one fp32 MFMA with k = 2 per block: A = (rt[m], 1), B = (1, ct[n]).
-    // Lane l supplies row resp. column l % 32 of k index l / 32.  All values are integers below 2^24.
-    float b_init[WN];
+    uint4 ra[2][WMX][AF ? 6 : 2], rb[2][WN][2];  // raw words of a group (a single group uses [0] only; the field
+                                                 // form all six slots), by stage parity
+    v4i af[2][WMX], bf[2][WN];          // expanded fragments, by k step parity
+    const int64_t nst = g.nkb / 2;      // the packed K is a multiple of 512: an even number of whole stages
+    using I0 = std::integral_constant<int, 0>;
+
+    // raw words of stage st of phase ph into buffer buf: the activation group at slot slot_a, the weight group at
+    // slot slot_b (AS / BS: the group is a single one)
+    auto load_stage_of = [&](auto ph_c, auto as_c, auto bs_c, auto buf_c, int64_t st, int slot_a, int slot_b)
+                             __attribute__((always_inline)) {
+        constexpr int ph = decltype(ph_c)::value, buf = decltype(buf_c)::value;
+        constexpr bool AS = decltype(as_c)::value, BS = decltype(bs_c)::value;
+        constexpr int WMP = split_rows(WM, SPLIT, ph), ROW0 = split_row0(WM, SPLIT, ph);
+#pragma unroll
+        for (int bi = 0; bi < WMP; ++bi) {
+            const uint4 *src = pa_src[ROW0 + bi];
+            if constexpr (AF) {
+#pragma unroll
+                for (int sl = 0; sl < 6; ++sl) ra[buf][bi][sl] = src[st * kStageVecA + sl * kSlotVec];
+            } else {
+                ra[buf][bi][0] = src[st * kStageVecA + slot_a * kSlotVec];
+                if constexpr (!AS) ra[buf][bi][1] = src[st * kStageVecA + (slot_a + 1) * kSlotVec];
+            }
+        }
+#pragma unroll
+        for (int bj = 0; bj < WN; ++bj) {
+            rb[buf][bj][0] = pb_src[bj][st * kStageVecB + slot_b * kSlotVec];
+            if constexpr (!BS) rb[buf][bj][1] = pb_src[bj][st * kStageVecB + (slot_b + 1) * kSlotVec];
+        }
+    };
+
+    // Order of the first requests.  A kernel starts with cold caches and every dependent round trip to memory
+    // costs about a microsecond, so everything the prologue needs is requested before anything is used: the
+    // operands of stage 0 of the first sweep (slots 0 of both operands), then the code sums, then the scales.
+    // (The one-phase 256 x 256 kernel has no registers to hold the operands while all 256 accumulators are being
+    // set up; it requests them after that, one round trip later.  The kernels with 4-bit activations in the
+    // field form measured 1 - 2 us slower with the early request and keep the old order too.)
+    constexpr bool AS0 = !AF && pair_groups(P) == 0, BS0 = pair_groups(Q) == 0;  // the first sweep's groups
+    constexpr bool PRELOAD = !(WM == 4 && WN == 4 && SPLIT == 1) && !AF;
+    if constexpr (PRELOAD)
+        load_stage_of(I0{}, std::integral_constant<bool, AS0>{}, std::integral_constant<bool, BS0>{}, I0{}, 0, 0, 0);
+    uint32_t pw_raw[WN], pa_raw[WM];
 #pragma unroll
     for (int bj = 0; bj < WN; ++bj) {
         int64_t n = n_lane + bj * 32;
         if (n >= rows_b) n = rows_b - 1;
-        const float ct = (float)(int32_t)((uint32_t)g.K * ca * cw - 2u * ca * (uint32_t)g.w_sum[n]);
-        b_init[bj] = kh == 0 ? 1.0f : ct;
+        pw_raw[bj] = (uint32_t)g.w_sum[n];
+    }
+    if constexpr (PRELOAD) {
+#pragma unroll
+        for (int bi = 0; bi < WM; ++bi) {
+            int64_t m = m0 + (wave_m * WM + bi) * 32 + r32;
+            if (m >= rows_a) m = rows_a - 1;
+            pa_raw[bi] = (uint32_t)g.a_sum[m];
+        }
     }
     // Scales of the fp16 epilogue, requested now so that their latency is gone by the time they are needed:
     // sw[bj] for this lane's columns; the token scales of the wave's 32 * WM rows one row per lane (row
     // lane + 64 i in sa_rows[i]), handed to the lanes that need them by a lane permute in the epilogue.
-    // (kept as binary16 pairs through the k loop: registers are scarce there; 0x3c00 = 1.0)
-    uint32_t sw_raw[(WN + 1) / 2], sa_raw[(WM + 3) / 4];
+    uint32_t sw_h[WN], sa_h[(WM + 1) / 2];
 #pragma unroll
-    for (int i = 0; i < (WN + 1) / 2; ++i) sw_raw[i] = 0x3c003c00u;
+    for (int bj = 0; bj < WN; ++bj) sw_h[bj] = 0x3c00u;  // 1.0
 #pragma unroll
-    for (int i = 0; i < (WM + 3) / 4; ++i) sa_raw[i] = 0x3c003c00u;
-    if (g.c_f16) {
+    for (int i = 0; i < (WM + 1) / 2; ++i) sa_h[i] = 0x3c00u;
+    if (PRELOAD && g.c_f16) {
 #pragma unroll
         for (int bj = 0; bj < WN; ++bj) {
             const int64_t n = n_lane + bj * 32;
-            const uint32_t h = (g.w_scale && n < g.N) ? g.w_scale[n] : 0x3c00u;
-            sw_raw[bj / 2] = (bj & 1) ? (sw_raw[bj / 2] & 0xffffu) | (h << 16) : (sw_raw[bj / 2] & 0xffff0000u) | h;
+            if (g.w_scale && n < g.N) sw_h[bj] = g.w_scale[n];
         }
 #pragma unroll
         for (int i = 0; i < (WM + 1) / 2; ++i) {
             const int64_t m = m0 + wave_m * WM * 32 + lane + 64 * i;
-            const uint32_t h = (g.a_scale && m < g.M && lane + 64 * i < 32 * WM) ? g.a_scale[m] : 0x3c00u;
-            sa_raw[i / 2] = (i & 1) ? (sa_raw[i / 2] & 0xffffu) | (h << 16) : (sa_raw[i / 2] & 0xffff0000u) | h;
+            if (g.a_scale && m < g.M && lane + 64 * i < 32 * WM) sa_h[i] = g.a_scale[m];
+        }
+    }
+
+    // -- first uses from here on --
+    // The accumulators start at the recovery terms rt[m] + ct[n], rt = -2 cw PA, ct = K ca cw - 2 ca PW: a
+    // rank-2 matrix, written by one fp32 MFMA with k = 2 per block: A = (rt[m], 1), B = (1, ct[n]).
+    // Lane l supplies row resp. column l % 32 of k index l / 32.  All values are integers below 2^24.
+    float b_init[WN], a_init[WM];
+#pragma unroll
+    for (int bj = 0; bj < WN; ++bj) {
+        const float ct = (float)(int32_t)((uint32_t)g.K * ca * cw - 2u * ca * pw_raw[bj]);
+        b_init[bj] = kh == 0 ? 1.0f : ct;
+    }
+    if constexpr (PRELOAD) {
+#pragma unroll
+        for (int bi = 0; bi < WM; ++bi) {
+            const float rt = -(float)(2u * cw * pa_raw[bi]);
+            a_init[bi] = kh == 0 ? rt : 1.0f;
+        }
+    }
+    // (the scales are kept as binary16 pairs through the k loop: registers are scarce there)
+    uint32_t sw_raw[(WN + 1) / 2], sa_raw[(WM + 3) / 4];
+    if constexpr (PRELOAD) {
+#pragma unroll
+        for (int i = 0; i < (WN + 1) / 2; ++i) sw_raw[i] = sw_h[2 * i] | ((2 * i + 1 < WN ? sw_h[2 * i + 1] : 0x3c00u) << 16);
+#pragma unroll
+        for (int i = 0; i < (WM + 3) / 4; ++i)
+            sa_raw[i] = sa_h[2 * i] | ((2 * i + 1 < (WM + 1) / 2 ? sa_h[2 * i + 1] : 0x3c00u) << 16);
+    } else {  // loaded and packed one by one (this form is the one the register allocator gets through without spilling)
+#pragma unroll
+        for (int i = 0; i < (WN + 1) / 2; ++i) sw_raw[i] = 0x3c003c00u;
+#pragma unroll
+        for (int i = 0; i < (WM + 3) / 4; ++i) sa_raw[i] = 0x3c003c00u;
+        if (g.c_f16) {
+#pragma unroll
+            for (int bj = 0; bj < WN; ++bj) {
+                const int64_t n = n_lane + bj * 32;
+                const uint32_t h = (g.w_scale && n < g.N) ? g.w_scale[n] : 0x3c00u;
+                sw_raw[bj / 2] = (bj & 1) ? (sw_raw[bj / 2] & 0xffffu) | (h << 16) : (sw_raw[bj / 2] & 0xffff0000u) | h;
+            }
+#pragma unroll
+            for (int i = 0; i < (WM + 1) / 2; ++i) {
+                const int64_t m = m0 + wave_m * WM * 32 + lane + 64 * i;
+                const uint32_t h = (g.a_scale && m < g.M && lane + 64 * i < 32 * WM) ? g.a_scale[m] : 0x3c00u;
+                sa_raw[i / 2] = (i & 1) ? (sa_raw[i / 2] & 0xffffu) | (h << 16) : (sa_raw[i / 2] & 0xffff0000u) | h;
+            }
         }
     }
 
@@ -152,20 +239,20 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
         for (int v = 0; v < 16; ++v) zero[v] = 0.f;
 #pragma unroll
         for (int bi = 0; bi < WMP; ++bi) {
-            int64_t m = m0 + (wave_m * WM + ROW0 + bi) * 32 + r32;
-            if (m >= rows_a) m = rows_a - 1;
-            const float rt = -(float)(2u * cw * (uint32_t)g.a_sum[m]);
-            const float a_init = kh == 0 ? rt : 1.0f;
+            float a_in;
+            if constexpr (PRELOAD) {
+                a_in = a_init[ROW0 + bi];
+            } else {  // loaded here, block by block: no register to spare for holding them
+                int64_t m = m0 + (wave_m * WM + ROW0 + bi) * 32 + r32;
+                if (m >= rows_a) m = rows_a - 1;
+                const float rt = -(float)(2u * cw * (uint32_t)g.a_sum[m]);
+                a_in = kh == 0 ? rt : 1.0f;
+            }
 #pragma unroll
             for (int bj = 0; bj < WN; ++bj)
-                acc[ROW0 + bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_init, b_init[bj], zero, 0, 0, 0);
+                acc[ROW0 + bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_in, b_init[bj], zero, 0, 0, 0);
         }
     };
-
-    uint4 ra[2][WMX][AF ? 6 : 2], rb[2][WN][2];  // raw words of a group (a single group uses [0] only; the field
-                                                 // form all six slots), by stage parity
-    v4i af[2][WMX], bf[2][WN];          // expanded fragments, by k step parity
-    const int64_t nst = g.nkb / 2;      // the packed K is a multiple of 512: an even number of whole stages
 
     // int32 store of element e of phase ph under the k loop of the next phase: elements run along the row
     // blocks, then the 16 registers (rows), then the column blocks, so that the row pointer moves once per WN stores
@@ -184,10 +271,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
     // One sweep of K for phase ph, the activation group at slot slot_a and the weight group at slot slot_b
     // (AS / BS: the group is a single one).  exp_a + exp_b - 254 = 4 + the bit positions of the two groups.
     // STORES: the first STORE_STAGES stages also store phase ph - 1.
-    auto sweep = [&](auto ph_c, auto stores_c, auto as_c, auto bs_c, int slot_a, int slot_b, int exp_a, int exp_b)
-                     __attribute__((always_inline)) {
+    // PRELOADED: stage 0 is already in buffer 0 (the prologue's request).
+    auto sweep = [&](auto ph_c, auto stores_c, auto as_c, auto bs_c, int slot_a, int slot_b, int exp_a, int exp_b,
+                     auto preloaded_c) __attribute__((always_inline)) {
         constexpr int ph = decltype(ph_c)::value;
-        constexpr bool STORES = decltype(stores_c)::value;
+        constexpr bool STORES = decltype(stores_c)::value, PRELOADED = decltype(preloaded_c)::value;
         constexpr bool AS = decltype(as_c)::value, BS = decltype(bs_c)::value;
         constexpr int WMP = split_rows(WM, SPLIT, ph), ROW0 = split_row0(WM, SPLIT, ph);  // this phase's row blocks
         constexpr int PER_KS = WMP * WN;         // MFMAs per k step
@@ -197,23 +285,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
         constexpr int TPM = (TASKS + PER_KS - 1) / PER_KS;  // tasks per MFMA (the last MFMAs of a step may get fewer)
         constexpr int STAGE_ELEMS = KS * PER_KS / STORE_EVERY;  // outputs of the previous phase stored under one stage
         auto load_stage = [&](auto buf_c, int64_t st) __attribute__((always_inline)) {
-            constexpr int buf = decltype(buf_c)::value;
-#pragma unroll
-            for (int bi = 0; bi < WMP; ++bi) {
-                const uint4 *src = pa_src[ROW0 + bi];
-                if constexpr (AF) {
-#pragma unroll
-                    for (int sl = 0; sl < 6; ++sl) ra[buf][bi][sl] = src[st * kStageVecA + sl * kSlotVec];
-                } else {
-                    ra[buf][bi][0] = src[st * kStageVecA + slot_a * kSlotVec];
-                    if constexpr (!AS) ra[buf][bi][1] = src[st * kStageVecA + (slot_a + 1) * kSlotVec];
-                }
-            }
-#pragma unroll
-            for (int bj = 0; bj < WN; ++bj) {
-                rb[buf][bj][0] = pb_src[bj][st * kStageVecB + slot_b * kSlotVec];
-                if constexpr (!BS) rb[buf][bj][1] = pb_src[bj][st * kStageVecB + (slot_b + 1) * kSlotVec];
-            }
+            load_stage_of(ph_c, as_c, bs_c, buf_c, st, slot_a, slot_b);
         };
         // dword d of fragment f (f < WMP: A block f, else B block f - WMP) of k step ks, from buffer buf
         auto expand = [&](auto buf_c, auto ks_c, auto f_c, auto d_c) __attribute__((always_inline)) {
@@ -281,7 +353,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
                 __builtin_amdgcn_sched_barrier(0);
             });
         };
-        load_stage(I0{}, 0);
+        if constexpr (!PRELOADED) load_stage(I0{}, 0);
         // fragments of (stage 0, k step 0)
         static_for<FRAGS - FRAG0>([&](auto f_c) __attribute__((always_inline)) {
             using F = std::integral_constant<int, FRAG0 + decltype(f_c)::value>;
@@ -311,42 +383,43 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
             st_ptr = reinterpret_cast<char *>(g.c_i32 + (m_lane + split_row0(WM, SPLIT, ph - 1) * 32) * g.N + n_lane);
         // the first sweep of a later phase carries the stores of the phase before it
         using First = std::integral_constant<bool, (ph > 0)>;
+        using Pre = std::integral_constant<bool, (ph == 0 && PRELOAD)>;  // stage 0 of the very first sweep came with the prologue
         if constexpr (AF) {
             // one sweep per weight group; (ua / 8)(uw / 2) 2^6 = 4 ua uw
             if constexpr (pair_groups(Q) > 0) {
-                sweep(ph_c, First{}, F{}, F{}, 0, 0, 130, 130);
-                for (int hb = 1; hb < pair_groups(Q); ++hb) sweep(ph_c, F{}, F{}, F{}, 0, 2 * hb, 130, 130 + 2 * hb);
-                if constexpr (has_single_group(Q)) sweep(ph_c, F{}, F{}, T{}, 0, Q - 1, 130, 130 + Q - 1);
+                sweep(ph_c, First{}, F{}, F{}, 0, 0, 130, 130, Pre{});
+                for (int hb = 1; hb < pair_groups(Q); ++hb) sweep(ph_c, F{}, F{}, F{}, 0, 2 * hb, 130, 130 + 2 * hb, F{});
+                if constexpr (has_single_group(Q)) sweep(ph_c, F{}, F{}, T{}, 0, Q - 1, 130, 130 + Q - 1, F{});
             } else {
-                sweep(ph_c, First{}, F{}, T{}, 0, 0, 130, 130);
+                sweep(ph_c, First{}, F{}, T{}, 0, 0, 130, 130, Pre{});
             }
         } else
         // pair x pair, pair x single, single x pair, single x single
         if constexpr (pair_groups(P) > 0) {
             if constexpr (pair_groups(Q) > 0) {
-                sweep(ph_c, First{}, F{}, F{}, 0, 0, 129, 129);
-                for (int hb = 1; hb < pair_groups(Q); ++hb) sweep(ph_c, F{}, F{}, F{}, 0, 2 * hb, 129, 129 + 2 * hb);
-                if constexpr (has_single_group(Q)) sweep(ph_c, F{}, F{}, T{}, 0, Q - 1, 129, 129 + Q - 1);
+                sweep(ph_c, First{}, F{}, F{}, 0, 0, 129, 129, Pre{});
+                for (int hb = 1; hb < pair_groups(Q); ++hb) sweep(ph_c, F{}, F{}, F{}, 0, 2 * hb, 129, 129 + 2 * hb, F{});
+                if constexpr (has_single_group(Q)) sweep(ph_c, F{}, F{}, T{}, 0, Q - 1, 129, 129 + Q - 1, F{});
             } else {
-                sweep(ph_c, First{}, F{}, T{}, 0, Q - 1, 129, 129 + Q - 1);
+                sweep(ph_c, First{}, F{}, T{}, 0, Q - 1, 129, 129 + Q - 1, Pre{});
             }
             for (int ha = 1; ha < pair_groups(P); ++ha) {
                 for (int hb = 0; hb < pair_groups(Q); ++hb)
-                    sweep(ph_c, F{}, F{}, F{}, 2 * ha, 2 * hb, 129 + 2 * ha, 129 + 2 * hb);
-                if constexpr (has_single_group(Q)) sweep(ph_c, F{}, F{}, T{}, 2 * ha, Q - 1, 129 + 2 * ha, 129 + Q - 1);
+                    sweep(ph_c, F{}, F{}, F{}, 2 * ha, 2 * hb, 129 + 2 * ha, 129 + 2 * hb, F{});
+                if constexpr (has_single_group(Q)) sweep(ph_c, F{}, F{}, T{}, 2 * ha, Q - 1, 129 + 2 * ha, 129 + Q - 1, F{});
             }
             if constexpr (has_single_group(P)) {
                 for (int hb = 0; hb < pair_groups(Q); ++hb)
-                    sweep(ph_c, F{}, T{}, F{}, P - 1, 2 * hb, 129 + P - 1, 129 + 2 * hb);
-                if constexpr (has_single_group(Q)) sweep(ph_c, F{}, T{}, T{}, P - 1, Q - 1, 129 + P - 1, 129 + Q - 1);
+                    sweep(ph_c, F{}, T{}, F{}, P - 1, 2 * hb, 129 + P - 1, 129 + 2 * hb, F{});
+                if constexpr (has_single_group(Q)) sweep(ph_c, F{}, T{}, T{}, P - 1, Q - 1, 129 + P - 1, 129 + Q - 1, F{});
             }
         } else {  // P == 1
             if constexpr (pair_groups(Q) > 0) {
-                sweep(ph_c, First{}, T{}, F{}, 0, 0, 129, 129);
-                for (int hb = 1; hb < pair_groups(Q); ++hb) sweep(ph_c, F{}, T{}, F{}, 0, 2 * hb, 129, 129 + 2 * hb);
-                if constexpr (has_single_group(Q)) sweep(ph_c, F{}, T{}, T{}, 0, Q - 1, 129, 129 + Q - 1);
+                sweep(ph_c, First{}, T{}, F{}, 0, 0, 129, 129, Pre{});
+                for (int hb = 1; hb < pair_groups(Q); ++hb) sweep(ph_c, F{}, T{}, F{}, 0, 2 * hb, 129, 129 + 2 * hb, F{});
+                if constexpr (has_single_group(Q)) sweep(ph_c, F{}, T{}, T{}, 0, Q - 1, 129, 129 + Q - 1, F{});
             } else {
-                sweep(ph_c, First{}, T{}, T{}, 0, 0, 129, 129);
+                sweep(ph_c, First{}, T{}, T{}, 0, 0, 129, 129, Pre{});
             }
         }
     });
