@@ -435,6 +435,26 @@ def test_empty_problem_and_outputs_selection(gpu, oracle):
     binding.apmm_gemm(0, 24, 256, 2, 1, wp, wp, c_i32=empty)
 
 
+@pytest.mark.parametrize("M", [1, 7, 40, 300])
+@pytest.mark.parametrize("which", ["a_scale", "w_scale"])
+def test_one_scale_vector_only(gpu, oracle, M, which):
+    """Only one of the two scale vectors: the missing one counts as 1 (small-M kernels, both tile kernels,
+    fp16 alone and next to int32, packed activations and codes)."""
+    case = dict(M=M, N=130, K=640, p=2, q=2, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 4100 + M)
+    one = dict(data, a_scale=data["a_scale"] if which == "a_scale" else None,
+               w_scale=data["w_scale"] if which == "w_scale" else None)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], 2, 2)
+    for want_i32 in (True, False):
+        c32, c16 = run_case(gpu, one, case, want_i32=want_i32, want_f16=True)
+        check_f16(c16, want, one, oracle)
+        if want_i32:
+            assert np.array_equal(c32.astype(np.int64), want)
+    c32, c16 = run_from_codes(gpu, one, case, workspace=True)
+    assert np.array_equal(c32.astype(np.int64), want)
+    check_f16(c16, want, one, oracle)
+
+
 def test_deterministic(gpu):
     case = dict(M=200, N=330, K=1024, p=2, q=2, a_dist="bernoulli", scaled=False)
     data = inputs.make_case(case, 4100)
