@@ -63,8 +63,10 @@ def algos_for(case):
 
 # ------------------------------------------------------------- pack layout --
 @pytest.mark.parametrize("rows,K,bits", [(1, 1, 1), (5, 31, 3), (32, 128, 2), (33, 129, 4), (70, 500, 8),
-                                         (16, 512, 2), (100, 4096, 1), (257, 1000, 5)])
+                                         (16, 512, 2), (100, 4096, 1), (257, 1000, 5), (37, 4097, 2), (5, 11008, 4),
+                                         (3, 20000, 3), (40, 16400, 1), (9, 70000, 7)])
 def test_pack_unpack_roundtrip(gpu, rows, K, bits):
+    """Includes rows of more than 4096 elements, which four waves share, and the code sums behind the tiles."""
     torch, binding = gpu
     rng = np.random.default_rng(rows * 7919 + K * 13 + bits)
     codes = rng.integers(0, 256, size=(rows, K), dtype=np.uint8)     # high bits are dirt
@@ -76,6 +78,11 @@ def test_pack_unpack_roundtrip(gpu, rows, K, bits):
         assert packed.numel() == size(rows, K, bits)
         back = unpack(packed, rows, K, bits).cpu().numpy()
         assert np.array_equal(back, codes & ((1 << bits) - 1))
+        # one int32 per padded row at the end of the buffer: the sum of the row's codes over the padded K
+        rows_p, k_p = -(-rows // 32) * 32, -(-K // 512) * 512
+        sums = packed.cpu().numpy()[-4 * rows_p:].view(np.int32)
+        want = (codes & ((1 << bits) - 1)).astype(np.int64).sum(axis=1) + (k_p - K) * ((1 << bits) - 1)
+        assert np.array_equal(sums[:rows].astype(np.int64), want) and not sums[rows:].any()
 
 
 def test_pack_is_plane_decomposition(gpu):
