@@ -22,6 +22,7 @@ Integer GEMM time does not depend on the values, so codes are random; parity on 
 import argparse
 import os
 import sys
+import time
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
@@ -41,10 +42,16 @@ def main():
     dev = torch.device("cuda:0")
     binding.load()
 
+    def settle(step, ms=40.0):
+        # after idling (data generation between cases) the GPU needs some tens of ms of work before its clocks settle
+        t0 = time.perf_counter()
+        while (time.perf_counter() - t0) * 1e3 < ms:
+            for i in range(20):
+                step(i)
+            torch.cuda.synchronize()
+
     def clock_calls(step, iters):
-        for _ in range(5):
-            step(0)
-        torch.cuda.synchronize()
+        settle(step)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for i in range(iters):
@@ -64,6 +71,7 @@ def main():
                     step(i)
             g.replay()
             torch.cuda.synchronize()
+            settle(lambda i: g.replay() if i % 20 == 0 else None, ms=20.0)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(replays):
