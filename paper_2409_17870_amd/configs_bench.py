@@ -177,10 +177,35 @@ def main():
             del a, a_packed, wps
             torch.cuda.empty_cache()
         if idx == 5:
+            # the same layer with the projections that share an input fused by concatenating their weights (what a
+            # model would do: q,k,v -> one 15360-channel linear, gate,up -> one 27648-channel linear): four GEMMs
+            fused_calls = fused_graph = 0.0
+            for (name, N, K) in (("q,k,v fused", 15360, 5120), ("o", 5120, 5120), ("gate,up fused", 27648, 5120),
+                                 ("down", 5120, 13824)):
+                case = dict(M=512, N=N, K=K, p=4, q=2)
+                M, p, q = 512, 4, 2
+                a, a_packed, wps, sa, sw = operands(case)
+                h = torch.empty((M, N), dtype=torch.float16, device=dev)
+
+                def pack_gemm(i):
+                    binding.apmm_pack_activations(a, p, out=a_packed)
+                    binding.apmm_gemm(M, N, K, p, q, a_packed, wps[0], want_i32=False, want_f16=True, w_scale=sw,
+                                      a_scale=sa, c_f16=h)
+
+                nb = N * K * q / 8.0 + M * K * p / 8.0 + 2.0 * M * N + 2.0 * (M + N) + M * K + M * K * p / 8.0
+                tc, tg = clock_calls(pack_gemm, 200), clock_graph(pack_gemm, 10)
+                fused_calls += tc
+                fused_graph += tg
+                row("cfg5 %s: pack + GEMM, fp16" % name, case, tc, tg, nb)
+                del a, a_packed, wps
+                torch.cuda.empty_cache()
             ops = sum(2.0 * c["M"] * c["N"] * c["K"] for c in inputs.config_cases(5))
             print("| cfg5 whole sweep (7 linears) | | | | W2A4 | %.1f | %.1f | %.0f | | %.1f (int8 MFMA) | %.0f %% |" % (
                 sweep_calls, sweep_graph, ops / min(sweep_calls, sweep_graph) / 1e6, ops / INT8_PEAK * 1e6,
                 100.0 * ops / INT8_PEAK * 1e6 / min(sweep_calls, sweep_graph)), flush=True)
+            print("| cfg5 whole layer, shared inputs fused (4 linears) | | | | W2A4 | %.1f | %.1f | %.0f | | %.1f (int8 MFMA) | %.0f %% |" % (
+                fused_calls, fused_graph, ops / min(fused_calls, fused_graph) / 1e6, ops / INT8_PEAK * 1e6,
+                100.0 * ops / INT8_PEAK * 1e6 / min(fused_calls, fused_graph)), flush=True)
 
 
 if __name__ == "__main__":
