@@ -51,10 +51,11 @@ __device__ __forceinline__ uint32_t field_plane_half_word(const uint32_t *tile_r
     return out;
 }
 
-__global__ __launch_bounds__(kTile * kTile) void gemm_valu_kernel(GemmArgs g)
+__global__ __launch_bounds__(kTile * kTile) void gemm_valu_kernel(GemmArgs g, int64_t tiles_n)
 {
-    const int64_t n = (int64_t)blockIdx.x * kTile + threadIdx.x;
-    const int64_t m = (int64_t)blockIdx.y * kTile + threadIdx.y;
+    // one-dimensional grid (the y dimension would cap M at about a million rows)
+    const int64_t n = ((int64_t)blockIdx.x % tiles_n) * kTile + threadIdx.x;
+    const int64_t m = ((int64_t)blockIdx.x / tiles_n) * kTile + threadIdx.y;
     if (m >= g.M || n >= g.N) return;
     const int p = g.p, q = g.q;
 
@@ -85,8 +86,8 @@ __global__ __launch_bounds__(kTile * kTile) void gemm_valu_kernel(GemmArgs g)
 hipError_t launch_gemm_valu(const GemmArgs &args, hipStream_t stream)
 {
     const int64_t gx = (args.N + kTile - 1) / kTile, gy = (args.M + kTile - 1) / kTile;
-    if (gx > 0x7fffffffLL || gy > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(gemm_valu_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(kTile, kTile), 0, stream, args);
+    if (gx > 0x7fffffffLL / gy) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(gemm_valu_kernel, dim3((unsigned)(gx * gy)), dim3(kTile, kTile), 0, stream, args, gx);
     return hipGetLastError();
 }
 

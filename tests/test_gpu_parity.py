@@ -462,6 +462,18 @@ def test_one_scale_vector_only(gpu, oracle, M, which):
     check_f16(c16, want, one, oracle)
 
 
+@pytest.mark.parametrize("M,N,K,p,q", [(2, 150000, 128, 1, 1), (16, 70001, 200, 2, 2), (70001, 48, 128, 2, 1),
+                                       (1048600, 8, 64, 5, 1), (40, 33000, 100, 2, 2)])
+def test_long_dimensions(gpu, oracle, M, N, K, p, q):
+    """Many output channels for the small-M kernels (tens of thousands of workgroups), many rows for the tile
+    kernels and for the general kernel (whose grid used to end at about a million rows)."""
+    case = dict(M=M, N=N, K=K, p=p, q=q, a_dist="bernoulli", scaled=False)
+    data = inputs.make_case(case, 4300 + p)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+    c32, _ = run_case(gpu, data, case, want_f16=False)
+    assert np.array_equal(c32.astype(np.int64), want)
+
+
 def test_deterministic(gpu):
     case = dict(M=200, N=330, K=1024, p=2, q=2, a_dist="bernoulli", scaled=False)
     data = inputs.make_case(case, 4100)
