@@ -38,7 +38,7 @@ typedef enum {
     APMM_ERR_INVALID_ARG = 1, /* null pointer, negative size, bits outside [1, 8], misaligned buffer */
     APMM_ERR_UNSUPPORTED = 2, /* valid request that no kernel in this build covers */
     APMM_ERR_OVERFLOW = 3,    /* K * (2^p - 1) * (2^q - 1) does not fit the 32-bit output */
-    APMM_ERR_WORKSPACE = 4,   /* workspace smaller than apmm_workspace_bytes() */
+    APMM_ERR_WORKSPACE = 4,   /* workspace missing or smaller than the call needs (apmm_gemm_from_codes) */
     APMM_ERR_HIP = 5          /* a HIP call failed; text in apmm_last_error() */
 } apmm_status;
 
@@ -47,7 +47,7 @@ typedef enum {
     APMM_ALGO_AUTO = 0,
     APMM_ALGO_VALU_POPCOUNT = 1, /* plane pairs by XOR + popcount on the vector ALU, D_ij = K - 2*popc */
     APMM_ALGO_MFMA_INT8 = 2,     /* reserved: the int8 MFMA kernel of earlier builds; this build answers APMM_ERR_UNSUPPORTED */
-    APMM_ALGO_DECODE = 3,        /* small-M weight-streaming kernels: M <= 16, and M <= 64 for p, q <= 2 */
+    APMM_ALGO_DECODE = 3,        /* small-M weight-streaming kernels: M <= 16 with q <= 4 and p not 3 or 4, and M <= 64 for p, q <= 2 */
     APMM_ALGO_MFMA_FP4 = 4       /* plane groups recombined to E2M1 codes in registers, f8f6f4 MFMA, exact fp32 accumulate
                                     (p, q <= 4 and 4 * roundup(K,512) * (2^p-1)(2^q-1) < 2^24) */
 } apmm_algo;
