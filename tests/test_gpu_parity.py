@@ -474,6 +474,26 @@ def test_long_dimensions(gpu, oracle, M, N, K, p, q):
     assert np.array_equal(c32.astype(np.int64), want)
 
 
+def test_seeded_random_shapes_every_entry_point(gpu, oracle):
+    """Sixty shapes and widths drawn from a fixed seed (token counts around the kernels' thresholds, ragged N and K):
+    apmm_gemm with automatic kernel choice and apmm_gemm_from_codes against the oracle."""
+    rng = np.random.default_rng(20240917)
+    for i in range(60):
+        M = int(rng.choice([1, 2, 3, 7, 15, 16, 17, 31, 33, 63, 64, 65, 100, 257]))
+        N = int(rng.integers(1, 400))
+        K = int(rng.choice([1, 31, 64, 127, 128, 500, 512, 513, 1100, 2049, 4100]))
+        p, q = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+        case = dict(M=M, N=N, K=K, p=p, q=q, a_dist="bernoulli", scaled=True)
+        data = inputs.make_case(case, 8000 + i)
+        want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+        c32, c16 = run_case(gpu, data, case)
+        assert np.array_equal(c32.astype(np.int64), want), case
+        check_f16(c16, want, data, oracle)
+        c32, c16 = run_from_codes(gpu, data, case, dirty_high_bits=bool(i & 1), workspace=True)
+        assert np.array_equal(c32.astype(np.int64), want), case
+        check_f16(c16, want, data, oracle)
+
+
 def test_deterministic(gpu):
     case = dict(M=200, N=330, K=1024, p=2, q=2, a_dist="bernoulli", scaled=False)
     data = inputs.make_case(case, 4100)
