@@ -494,6 +494,57 @@ def test_seeded_random_shapes_every_entry_point(gpu, oracle):
         check_f16(c16, want, data, oracle)
 
 
+def test_graph_capture_and_replay(gpu, oracle):
+    """The calls only enqueue kernels on the given stream, so a serving loop can capture them in a HIP graph:
+    pack + GEMM, GEMM from codes and a grouped launch are captured once and replayed several times with other
+    work and synchronisations in between; every replay must give the eager (oracle-checked) result."""
+    torch, binding = gpu
+    dev = torch.device("cuda:0")
+    p, q = 2, 2
+    case = dict(M=8, N=300, K=1000, p=p, q=q, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 8200)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+    a = torch.from_numpy(data["a_codes"]).to(dev)
+    wp = binding.apmm_pack_weights(torch.from_numpy(data["w_codes"]).to(dev), q)
+    sa, sw = torch.from_numpy(data["a_scale"]).to(dev), torch.from_numpy(data["w_scale"]).to(dev)
+    big = dict(M=300, N=260, K=700, p=p, q=q, a_dist="bernoulli", scaled=False)
+    big_data = inputs.make_case(big, 8201)
+    big_want = oracle.gemm_i64(big_data["a_codes"], big_data["w_codes"], p, q)
+    big_a = torch.from_numpy(big_data["a_codes"]).to(dev)
+    big_wp = binding.apmm_pack_weights(torch.from_numpy(big_data["w_codes"]).to(dev), q)
+    ap = torch.empty(binding.apmm_packed_activation_bytes(8, 1000, p), dtype=torch.uint8, device=dev)
+    big_ap = torch.empty(binding.apmm_packed_activation_bytes(300, 700, p), dtype=torch.uint8, device=dev)
+    outs = dict(c1=torch.zeros((8, 300), dtype=torch.int32, device=dev), h1=torch.zeros((8, 300), dtype=torch.float16, device=dev),
+                c2=torch.zeros((8, 300), dtype=torch.int32, device=dev), c3=torch.zeros((8, 300), dtype=torch.int32, device=dev),
+                c4=torch.zeros((300, 260), dtype=torch.int32, device=dev))
+
+    def work():
+        binding.apmm_pack_activations(a, p, out=ap)
+        binding.apmm_gemm(8, 300, 1000, p, q, ap, wp, want_f16=True, w_scale=sw, a_scale=sa, c_i32=outs["c1"], c_f16=outs["h1"])
+        binding.apmm_gemm_from_codes(a, 300, p, q, wp, c_i32=outs["c2"])
+        binding.apmm_gemm_grouped([dict(M=8, N=300, K=1000, a_codes=a, w_packed=wp, c_i32=outs["c3"])], p, q)
+        binding.apmm_pack_activations(big_a, p, out=big_ap)
+        binding.apmm_gemm(300, 260, 700, p, q, big_ap, big_wp, c_i32=outs["c4"])
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        work()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            work()
+    for replay in range(4):
+        for t in outs.values():
+            t.zero_()                     # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for key in ("c1", "c2", "c3"):
+            assert np.array_equal(outs[key].cpu().numpy().astype(np.int64), want), (key, replay)
+        check_f16(outs["h1"].cpu().numpy(), want, data, oracle)
+        assert np.array_equal(outs["c4"].cpu().numpy().astype(np.int64), big_want), replay
+
+
 def test_deterministic(gpu):
     case = dict(M=200, N=330, K=1024, p=2, q=2, a_dist="bernoulli", scaled=False)
     data = inputs.make_case(case, 4100)
