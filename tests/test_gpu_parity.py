@@ -494,6 +494,29 @@ def test_seeded_random_shapes_every_entry_point(gpu, oracle):
         check_f16(c16, want, data, oracle)
 
 
+@pytest.mark.parametrize("M", [5, 300])
+def test_outputs_at_odd_element_offsets(gpu, oracle, M):
+    """Outputs that start one element into an allocation: the fp16 output is then 2- but not 4-byte aligned (the tile
+    kernels' paired fp16 stores must not be used), the int32 output 4- but not 16-byte aligned."""
+    torch, binding = gpu
+    dev = torch.device("cuda:0")
+    case = dict(M=M, N=256, K=640, p=2, q=1, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 8300 + M)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], 2, 1)
+    ap = binding.apmm_pack_activations(torch.from_numpy(data["a_codes"]).to(dev), 2)
+    wp = binding.apmm_pack_weights(torch.from_numpy(data["w_codes"]).to(dev), 1)
+    sa, sw = torch.from_numpy(data["a_scale"]).to(dev), torch.from_numpy(data["w_scale"]).to(dev)
+    raw16 = torch.zeros(M * 256 + 8, dtype=torch.float16, device=dev)
+    raw32 = torch.zeros(M * 256 + 8, dtype=torch.int32, device=dev)
+    c16, c32 = raw16[1:1 + M * 256].view(M, 256), raw32[1:1 + M * 256].view(M, 256)
+    binding.apmm_gemm(M, 256, 640, 2, 1, ap, wp, want_f16=True, w_scale=sw, a_scale=sa, c_i32=c32, c_f16=c16)
+    torch.cuda.synchronize()
+    assert np.array_equal(c32.cpu().numpy().astype(np.int64), want)
+    check_f16(c16.cpu().numpy(), want, data, oracle)
+    assert raw16[0].item() == 0 and raw16[1 + M * 256:].abs().sum().item() == 0       # nothing written outside
+    assert raw32[0].item() == 0 and raw32[1 + M * 256:].abs().sum().item() == 0
+
+
 def test_graph_capture_and_replay(gpu, oracle):
     """The calls only enqueue kernels on the given stream, so a serving loop can capture them in a HIP graph:
     pack + GEMM, GEMM from codes and a grouped launch are captured once and replayed several times with other
