@@ -104,7 +104,8 @@ apmm_status apmm_unpack_activations(const void *a_packed, int64_t M, int64_t K, 
  *   c_i32    : device, M x N row-major int32 result, or NULL
  *   c_f16    : device, M x N row-major IEEE binary16 bit patterns of
  *              C[m][n] * a_scale[m] * w_scale[n] (product in fp32, one rounding to
- *              nearest-even at the end), or NULL
+ *              nearest-even at the end; a product beyond the binary16 range, |x| >= 65520,
+ *              becomes an infinity of its sign, as IEEE 754 rounding has it), or NULL
  *   w_scale  : device, N binary16 per-output-channel scales, or NULL (= 1)
  *   a_scale  : device, M binary16 per-token scales, or NULL (= 1)
  *   workspace: device scratch of at least apmm_workspace_bytes() bytes (may be NULL if 0)

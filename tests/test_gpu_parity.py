@@ -494,6 +494,29 @@ def test_seeded_random_shapes_every_entry_point(gpu, oracle):
         check_f16(c16, want, data, oracle)
 
 
+@pytest.mark.parametrize("M,p,q", [(3, 8, 8), (40, 7, 8), (200, 8, 6), (300, 4, 4)])
+def test_fp16_output_beyond_the_binary16_range(gpu, oracle, M, p, q):
+    """Wide codes with only one scale vector: many products leave the binary16 range.  Round-to-nearest-even turns
+    |x| >= 65520 into an infinity of the same sign; everything representable stays within the tolerance; the int32
+    output is untouched.  Every kernel family (XOR/popcount for wide codes, few tokens, large tiles)."""
+    torch, binding = gpu
+    case = dict(M=M, N=130, K=2048, p=p, q=q, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 8200 + M)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+    # per-channel scales only, stretched so that the median product sits at the edge of the range
+    data["a_scale"] = None
+    stretch = 65520.0 / (0.05 * max(1.0, float(np.median(np.abs(want)))))
+    data["w_scale"] = (data["w_scale"].astype(np.float32) * np.float32(stretch)).astype(np.float16)
+    f = oracle.scale_f64(want, None, data["w_scale"].view(np.uint16))
+    over, fin = np.abs(f) >= 65520.0 * (1 + 1e-3), np.abs(f) <= 65504.0
+    assert over.sum() > 100 and fin.sum() > 100
+    c32, c16 = run_case(gpu, data, case)
+    assert np.array_equal(c32.astype(np.int64), want)
+    got = c16.astype(np.float64)
+    assert np.all(np.isinf(got[over])) and np.array_equal(np.sign(got[over]), np.sign(f[over]))
+    assert np.all(np.abs(got[fin] - f[fin]) <= 1e-3 * np.abs(f[fin]) + 1e-6)
+
+
 @pytest.mark.parametrize("M", [5, 300])
 def test_outputs_at_odd_element_offsets(gpu, oracle, M):
     """Outputs that start one element into an allocation: the fp16 output is then 2- but not 4-byte aligned (the tile
