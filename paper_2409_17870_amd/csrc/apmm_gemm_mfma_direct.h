@@ -27,7 +27,7 @@
 // the operand bytes and come straight from L1/L2 into registers (paper Sec. 4.1: the planes are stored so
 // that one 16-byte load brings a row's share of a k block).  There is no barrier in the k loop.
 //
-// Workgroup = 2 x 2 waves, wave tile (32*WM) x (32*WN).  Stage = two packed k blocks = four MFMA k steps
+// Workgroup = 2 x 2 waves (4 x 1 for WM = 1), wave tile (32*WM) x (32*WN).  Stage = two packed k blocks = four MFMA k steps
 // of 64.  Lane l of a wave owns, for each of its row blocks, row l % 32 and k block l / 32 of the stage:
 // per group one or two 16-byte loads.  The expansion of k step ks+1 (and, at the end of a stage, of step 0
 // of the next stage) is interleaved with the MFMAs of step ks; the raw words of the next stage are loaded
@@ -50,6 +50,11 @@ namespace mfma {
 // the output go out under the k loop (one element per MFMA of the second phase), the first phase keeps nearly
 // the operand reuse of the whole tile, and only the short second phase pays for the stores and the low reuse.
 // Both are used for interior tiles with int32 output only and K long enough to carry the stores.
+// Arrangement of the four waves of a workgroup: 2 x 2, or 4 x 1 for wave tiles of a single row block (each row
+// block of the workgroup tile is then loaded by one wave only, which matters when the activation operand is the
+// heavy one: the 6-bit field form).
+constexpr int waves_m(int wm) { return wm == 1 ? 4 : 2; }
+constexpr int waves_n(int wm) { return 4 / waves_m(wm); }
 constexpr int split_phases(int split) { return split == 1 ? 1 : 2; }
 constexpr int split_rows(int wm, int split, int ph) { return split == 1 ? wm : split == 2 ? wm / 2 : (ph == 0 ? wm - 1 : 1); }
 constexpr int split_row0(int wm, int split, int ph) { return ph == 0 ? 0 : split_rows(wm, split, 0); }
@@ -70,7 +75,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
     constexpr int SLOTS_A = activation_slots(P);
     constexpr int PHASES = split_phases(SPLIT);
     constexpr int WMX = split_rows(WM, SPLIT, 0);  // row blocks of the largest phase (the first)
-    constexpr int BM = 64 * WM, BN = 64 * WN;
+    constexpr int BM = 32 * WM * waves_m(WM), BN = 32 * WN * waves_n(WM);
     constexpr int KS = 4;                    // MFMA k steps per stage
     constexpr int STORE_EVERY = split_store_every(SPLIT);
     constexpr int STORE_STAGES = split_store_stages(WM, WN, SPLIT);  // stages of phase 1 that carry stores
@@ -80,7 +85,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int t
     using NoStore = std::integral_constant<int, -1>;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wave_m = wave >> 1, wave_n = wave & 1;
+    const int wave_m = wave / waves_n(WM), wave_n = wave % waves_n(WM);
     const int r32 = lane & 31, kh = lane >> 5;
     const int lid = xcd_tile_id(blockIdx.x, tiles_total);
     const int tm = lid / tiles_n, tn = lid % tiles_n;
@@ -521,7 +526,7 @@ inline bool direct_split_usable(const GemmArgs &g)
 template <int P, int Q, int WM, int WN, int SPLIT = 1>
 hipError_t launch_direct_variant(const GemmArgs &g, hipStream_t stream)
 {
-    constexpr int BM = 64 * WM, BN = 64 * WN;
+    constexpr int BM = 32 * WM * waves_m(WM), BN = 32 * WN * waves_n(WM);
     const int64_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int64_t tiles = tiles_m * tiles_n;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
