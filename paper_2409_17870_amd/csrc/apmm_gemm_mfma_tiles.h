@@ -35,13 +35,23 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream)
     }
     if constexpr (AF) {
         (void)no_split;
-        if (best == 2) return launch_direct_variant<P, Q, 2, 4>(g, stream);
+        static const char *square = std::getenv("APMM_MFMA_AF_2X2");
+        const bool old_arrangement = square && square[0] == '1';
+        if (best == 2) {
+            // 1-bit weights: four wave tiles of 32 x 256 need 3.5 instead of 4 KB per wave and k step (with wider
+            // weights the 2 x 2 arrangement of 64 x 128 wave tiles is the lighter one).  Measured at M = 2048 with both
+            // outputs: 8 % faster at K = 11008, 2 - 5 % slower at K = 4096, where the store of the tile weighs more
+            // than the k loop: taken from K = 8192 on.
+            if constexpr (Q == 1) {
+                if (!old_arrangement && g.nkb >= 64) return launch_direct_variant<P, Q, 1, 8>(g, stream);
+            }
+            return launch_direct_variant<P, Q, 2, 4>(g, stream);
+        }
         // The 128 x 128 tile as four wave tiles of 32 x 128 one above the other: every activation row block (6 bits per
         // element, three quarters of the bytes) is loaded by one wave only, 14 instead of 16 KB through L1 per k step,
         // and these tiles are bound by L1: measured 12 % faster than 2 x 2 wave tiles of 64 x 64
         // (APMM_MFMA_AF_2X2=1 brings those back, for comparison).
-        static const char *square = std::getenv("APMM_MFMA_AF_2X2");
-        if (square && square[0] == '1') return launch_direct_variant<P, Q, 2, 2>(g, stream);
+        if (old_arrangement) return launch_direct_variant<P, Q, 2, 2>(g, stream);
         return launch_direct_variant<P, Q, 1, 4>(g, stream);
     } else {
         switch (best) {

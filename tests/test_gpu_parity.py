@@ -627,6 +627,17 @@ def sampled_check(gpu, oracle, case, seed, n_rows=48, n_cols=48):
     assert np.all((c64 - K) % 2 == 0)
 
 
+@pytest.mark.parametrize("p,q,M,N,K", [(4, 1, 2000, 2300, 8200), (3, 1, 1100, 4000, 8704), (4, 2, 2000, 2300, 8200),
+                                       (4, 2, 500, 5000, 5000), (3, 3, 300, 4200, 2600)])
+def test_field_form_tile_arrangements(gpu, oracle, p, q, M, N, K):
+    """3- and 4-bit activations at sizes where the launch rule takes each arrangement of the field-form kernels: the
+    128 x 256 tile as four wave tiles of 32 x 256 (1-bit weights, K of 8192 or more) and as 2 x 2 wave tiles of
+    64 x 128, the 128 x 128 tile as four wave tiles of 32 x 128; ragged borders.  Sampled rows x columns against the
+    oracle, checksums over every output."""
+    case = dict(M=M, N=N, K=K, p=p, q=q, a_dist="normal" if p == 4 else "bernoulli", scaled=True)
+    sampled_check(gpu, oracle, case, 7300 + 10 * p + q + M)
+
+
 def test_config2_square_4096_w1a2(gpu, oracle):
     sampled_check(gpu, oracle, inputs.config_cases(2)[0], inputs.BASE_SEED + 2)
 
