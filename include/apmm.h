@@ -80,10 +80,12 @@ apmm_status apmm_pack_activations(const uint8_t *a_codes, int64_t M, int64_t K, 
 /* Paper Sec. 3.1 (the feature matrix is quantised onto the symmetric bipolar-INT grid) fused with the
  * packing of Sec. 4.1, for activations that arrive as binary16 numbers: one pass instead of writing and
  * re-reading one code byte per element.  Per row (token) m:
- *   a_scale[m] = half(max_k |x[m][k]| / (2^p - 1))          (single precision division, rounded to nearest even)
- *   code       = clamp(floor((x / a_scale[m]) / 2) + 2^(p-1), 0, 2^p - 1)
- * i.e. x / a_scale moved to the nearest odd integer (ties upward) of the grid; a row whose scale rounds to
- * zero gets the code of +1 everywhere.  The result is the packed operand apmm_pack_activations would give
+ *   a_scale[m] = max_k |x[m][k]| / (2^p - 1), correctly rounded to binary16 (nearest, ties to even)
+ *   code       = (v + 2^p - 1) / 2, v = the odd integer of [-(2^p - 1), 2^p - 1] nearest to x / a_scale[m],
+ *                the upper one on a tie
+ * decided as in exact arithmetic on the binary16 values (an element exactly on a cell border
+ * x = 2 c a_scale[m] always lands in the upper cell); a row whose scale rounds to zero gets the code of +1
+ * everywhere.  The result is the packed operand apmm_pack_activations would give
  * for those codes, and a_scale is the per-token scale for apmm_gemm's fp16 epilogue.
  *   x_f16    : device, M x K binary16 bit patterns, row-major, finite values
  *   a_packed : device, apmm_packed_activation_bytes(M, K, p) bytes, written entirely

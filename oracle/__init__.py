@@ -61,8 +61,8 @@ def _load():
     lib.oracle_float_to_half_bits.argtypes = [ctypes.c_float]
     lib.oracle_quantize_rows.restype = None
     lib.oracle_quantize_rows.argtypes = [i64, i64, ctypes.c_int, u16p, u8p, u16p]
-    lib.oracle_max_abs.restype = i64
-    lib.oracle_max_abs.argtypes = [i64, i64p]
+    lib.oracle_double_to_half_bits.restype = ctypes.c_uint16
+    lib.oracle_double_to_half_bits.argtypes = [ctypes.c_double]
     _lib = lib
     return lib
 
@@ -147,6 +147,10 @@ def scale_f64(c, a_scale_bits=None, w_scale_bits=None):
 
 def float_to_half_bits(f):
     return int(_load().oracle_float_to_half_bits(float(f)))
+
+
+def double_to_half_bits(f):
+    return int(_load().oracle_double_to_half_bits(float(f)))
 
 
 def quantize_rows(x_f16, p):

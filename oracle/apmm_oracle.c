@@ -178,23 +178,13 @@ void oracle_scale_f64(int64_t M, int64_t N, const int64_t *c,
     }
 }
 
-/* Largest |C| over the result, for the 32-bit output requirement of Sec. 3.2. */
-int64_t oracle_max_abs(int64_t count, const int64_t *c)
+/* double -> IEEE-754 binary16 bit pattern, one rounding to nearest, ties to even (finite inputs;
+ * values beyond the half range become infinity).  Every step is exact in double: the division is by a
+ * power of two, so the rounding decision is taken on the exact value. */
+uint16_t oracle_double_to_half_bits(double f)
 {
-    int64_t best = 0;
-    for (int64_t i = 0; i < count; ++i) {
-        int64_t v = c[i] < 0 ? -c[i] : c[i];
-        if (v > best) best = v;
-    }
-    return best;
-}
-
-/* float -> IEEE-754 binary16 bit pattern, round to nearest, ties to even (finite inputs;
- * values beyond the half range become infinity). */
-uint16_t oracle_float_to_half_bits(float f)
-{
-    double a = f < 0 ? -(double)f : (double)f;
-    uint16_t sign = (f < 0 || (f == 0 && 1.0f / f < 0)) ? 0x8000u : 0u;
+    double a = f < 0 ? -f : f;
+    uint16_t sign = (f < 0 || (f == 0 && 1.0 / f < 0)) ? 0x8000u : 0u;
     if (a != a) return (uint16_t)(sign | 0x7e00u);
     if (a == 0.0) return sign;
     /* spacing of half values around a: 2^-24 below 2^-14, else 2^(e-10) with 2^e <= a < 2^(e+1) */
@@ -203,6 +193,7 @@ uint16_t oracle_float_to_half_bits(float f)
     while (a >= 2.0 * pw && e < 16) { pw *= 2.0; ++e; }
     double ulp = pw / 1024.0;
     double q = a / ulp;                                 /* exact: division by a power of two */
+    if (q >= 4096.0) return (uint16_t)(sign | 0x7c00u); /* beyond twice the largest half: infinity */
     double fl = (double)(int64_t)q;                     /* q >= 0 */
     double frac = q - fl;
     int64_t n = (int64_t)fl;
@@ -214,15 +205,23 @@ uint16_t oracle_float_to_half_bits(float f)
     return (uint16_t)(sign | (uint16_t)((e + 15) << 10) | (uint16_t)(n - 1024));
 }
 
+/* float -> binary16: a float is a double, so this is the same single rounding. */
+uint16_t oracle_float_to_half_bits(float f) { return oracle_double_to_half_bits((double)f); }
+
 /* Paper Sec. 3.1: the bipolar-INT grid is symmetric (the odd integers from -(2^p - 1) to 2^p - 1),
- * which suits symmetric quantisation of the feature matrix.  Reading taken (the paper gives no
- * formula): per row (token), scale = max|x| / (2^p - 1) rounded to binary16; every element is divided by
- * that rounded scale and moved to the nearest odd integer (ties upward), clamped to the grid; the code is
- * (value + 2^p - 1) / 2.  A row whose scale rounds to zero gets the code of +1 everywhere.
- * The decision is taken in single precision, the precision the GPU kernel computes it in, and, as
- * quantisers usually do, by multiplying with the reciprocal of the scale (one division per row):
- *   s = half(max|x| / (float)(2^p - 1));  r = 1.0f / s;
- *   u = clamp(floorf(x * (r * 0.5f)) + 2^(p-1), 0, 2^p - 1).
+ * which suits symmetric quantisation of the feature matrix.  The paper gives no formula; the reading
+ * taken is the plain symmetric per-token quantiser onto that grid:
+ *   scale  s = max_k |x[k]| / (2^p - 1), rounded once to binary16 (it is stored as binary16);
+ *   value    = the odd integer v of the grid nearest to x / s, ties to the upper one;
+ *   code   u = (v + 2^p - 1) / 2.
+ * Written out without any rounding in the decision: the grid point of code c is 2c - (2^p - 1), the
+ * border between the cells of codes c - 1 and c is the even integer 2c - 2^p, and x / s >= border is the
+ * same as x >= border * s because s > 0.  x and s are binary16 numbers and the border is a small integer,
+ * so border * s and the comparison are exact in double: u is the number of borders at or below x.
+ * (The division for the scale: the quotient of a binary16 number by an odd integer up to 255 is never
+ * closer than 2^-19 relative to a binary16 rounding tie, so rounding the double quotient once gives the
+ * correctly rounded binary16 scale.)
+ * A row whose scale rounds to zero gets the code of +1 everywhere.
  * x: M x K binary16 bit patterns (finite); codes: M x K; scale_half: M binary16 bit patterns. */
 void oracle_quantize_rows(int64_t M, int64_t K, int p, const uint16_t *x_half,
                           uint8_t *codes, uint16_t *scale_half)
@@ -230,27 +229,26 @@ void oracle_quantize_rows(int64_t M, int64_t K, int p, const uint16_t *x_half,
     const int top = (1 << p) - 1;
     for (int64_t m = 0; m < M; ++m) {
         const uint16_t *x = x_half + m * K;
-        float amax = 0.0f;
+        double amax = 0.0;
         for (int64_t k = 0; k < K; ++k) {
-            float v = (float)oracle_half_bits_to_double(x[k]);
+            double v = oracle_half_bits_to_double(x[k]);
             if (v < 0) v = -v;
             if (v > amax) amax = v;
         }
-        const float s32 = amax / (float)top;
-        const uint16_t sh = oracle_float_to_half_bits(s32);
-        const float s = (float)oracle_half_bits_to_double(sh);
+        const uint16_t sh = oracle_double_to_half_bits(amax / (double)top);
+        const double s = oracle_half_bits_to_double(sh);
         scale_half[m] = sh;
         for (int64_t k = 0; k < K; ++k) {
             int u = 1 << (p - 1);
-            if (s > 0.0f) {
-                const float half_r = (1.0f / s) * 0.5f;
-                const float v = (float)oracle_half_bits_to_double(x[k]) * half_r;
-                const double cell = __builtin_floor((double)v);
-                const double shifted = cell + (double)(1 << (p - 1));
-                u = shifted < 0 ? 0 : shifted > top ? top : (int)shifted;
+            if (s > 0.0) {
+                const double xv = oracle_half_bits_to_double(x[k]);
+                u = 0;
+                for (int c = 1; c <= top; ++c) {
+                    const double border = (double)(2 * c - (1 << p)) * s;   /* exact */
+                    if (xv >= border) u = c;
+                }
             }
             codes[m * K + k] = (uint8_t)u;
         }
     }
 }
-

@@ -307,10 +307,11 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const uint8_t *__restric
 // grid; Sec. 4.1: decomposition and reassembly).  One wave per row (token):
 //   1. max |x| over the row (on the bit patterns, two halves per operation);
 //      scale = half(max|x| / (2^bits - 1)), stored per token; r = 1 / scale;
-//   2. u = clamp(floor(x * (r / 2)) + 2^(bits-1), 0, 2^bits - 1): x / scale moved to the nearest odd
-//      integer (ties upward), as a code; then the same packing as pack_kernel.
+//   2. u = clamp(floor(x / (2 scale)) + 2^(bits-1), 0, 2^bits - 1): x / scale moved to the nearest odd
+//      integer (ties upward), as a code; the floor is that of the exact quotient (computed as x * (r / 2)
+//      with a correction that covers the rounding of r and of the product); then the same packing as pack_kernel.
 // Rows of up to 8192 elements stay in registers between the two steps; longer rows are read again (from
-// L2).  Single precision throughout, so that the codes are a function of the inputs alone.  A row whose
+// L2).  The codes are those of exact arithmetic on the binary16 inputs and the binary16 scale.  A row whose
 // scale rounds to zero gets the code of +1 everywhere.
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 constexpr int kCachedGroups = 4;  // 32-element groups per lane kept in registers
@@ -399,7 +400,13 @@ __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(const uint16_t 
             for (int c = 0; c < 4; ++c) {
                 const uint32_t pair = h[2 * t4 + (c >> 1)];
                 const float xf = __half2float(__ushort_as_half((uint16_t)((c & 1) ? pair >> 16 : pair & 0xffffu)));
-                float u = floorf(xf * half_r) + mid;  // exact: |floor| is far below 2^24
+                // t = x / (2 s) up to 2^-23 relative (rounded reciprocal, rounded product); the cell is floor of
+                // the exact quotient.  An exact quotient that is an integer c (x on a border, ties upward) may
+                // come out just below c; any other exact quotient is at least 2^-12 away from every integer
+                // (x and 2 c s are binary16 numbers times small integers), and |t| <= 129.  Moving t up by
+                // 2^-21 |t| (between 2^-23 |t| and 2^-12) therefore gives the exact floor in every case.
+                const float t = xf * half_r;
+                float u = floorf(fmaf(fabsf(t), 0x1p-21f, t)) + mid;  // exact: |floor| is far below 2^24
                 u = __builtin_amdgcn_fmed3f(u, 0.0f, ftop);
                 if (!whole && kg * 32 + 4 * t4 + c >= K) u = ftop;
                 v = __builtin_amdgcn_cvt_pk_u8_f32(u, c, v);  // byte c of v = u

@@ -304,9 +304,9 @@ def test_degenerate_shapes(gpu, oracle, M, N, K):
 def test_two_phase_kernels(gpu, oracle, p, q, K):
     """130 whole 256 x 256 tiles, int32 output only, one sweep of at most 4096 k: the launch rule picks the MFMA
     kernels that store the first part of a tile under the k loop of the second (the uneven cut for 1-bit weights
-    from K = 3072 on, else the even one).  Sampled rows x columns against the oracle, checksums over every output."""
+    from K = 3072 on, else the even one).  Every output against the oracle."""
     case = dict(M=3328, N=2560, K=K, p=p, q=q, a_dist="bernoulli", scaled=False)
-    sampled_check(gpu, oracle, case, 7000 + 10 * p + q)
+    full_check(gpu, oracle, case, 7000 + 10 * p + q)
 
 
 def test_long_k_beyond_the_fp32_exactness_bound(gpu, oracle):
@@ -600,31 +600,21 @@ def test_deterministic(gpu):
 
 
 # ----------------------------------------- full-size workload configurations --
-def sampled_check(gpu, oracle, case, seed, n_rows=48, n_cols=48):
-    """Full-size run in the default launch configuration; the oracle recomputes a sample of
-    rows x columns, and two checksums that hold at any size cover every output."""
+def full_check(gpu, oracle, case, seed, also_from_codes=False):
+    """Full-size run in the default launch configuration (the one bench.py times); every int32 output and
+    every fp16 output is compared with the oracle's (oracle.gemm_i64, oracle.scale_f64)."""
     data = inputs.make_case(case, seed)
     c32, c16 = run_case(gpu, data, case)
-    M, N, K, p, q = case["M"], case["N"], case["K"], case["p"], case["q"]
-    rng = np.random.default_rng(seed)
-    rows = np.sort(rng.choice(M, size=min(n_rows, M), replace=False))
-    cols = np.sort(rng.choice(N, size=min(n_cols, N), replace=False))
-    # always include the corners and tile borders
-    rows = np.unique(np.concatenate([rows, [0, M - 1], [r for r in (255, 256, 127, 128) if r < M]]))
-    cols = np.unique(np.concatenate([cols, [0, N - 1], [c for c in (255, 256, 127, 128) if c < N]]))
-    want = oracle.gemm_i64(data["a_codes"][rows], data["w_codes"][cols], p, q)
-    assert np.array_equal(c32[np.ix_(rows, cols)].astype(np.int64), want)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], case["p"], case["q"])
+    assert c32.shape == want.shape
+    assert np.array_equal(c32.astype(np.int64), want)
     if c16 is not None:
-        sub = dict(a_scale=data["a_scale"][rows] if data["a_scale"] is not None else None,
-                   w_scale=data["w_scale"][cols] if data["w_scale"] is not None else None)
-        check_f16(c16[np.ix_(rows, cols)], want, sub, oracle)
-    # checksums over ALL outputs: sum_m C[m][n] = (sum_m a[m]) . w[n] and the same for rows
-    av = 2 * data["a_codes"].astype(np.int64) - ((1 << p) - 1)
-    wv = 2 * data["w_codes"].astype(np.int64) - ((1 << q) - 1)
-    c64 = c32.astype(np.int64)
-    assert np.array_equal(c64.sum(axis=0), wv @ av.sum(axis=0))
-    assert np.array_equal(c64.sum(axis=1), av @ wv.sum(axis=0))
-    assert np.all((c64 - K) % 2 == 0)
+        check_f16(c16, want, data, oracle)
+    if also_from_codes:
+        c32, c16 = run_from_codes(gpu, data, case, workspace=True)
+        assert np.array_equal(c32.astype(np.int64), want)
+        if data["a_scale"] is not None or data["w_scale"] is not None:
+            check_f16(c16, want, data, oracle)
 
 
 @pytest.mark.parametrize("p,q,M,N,K", [(4, 1, 2000, 2300, 8200), (3, 1, 1100, 4000, 8704), (4, 2, 2000, 2300, 8200),
@@ -632,35 +622,40 @@ def sampled_check(gpu, oracle, case, seed, n_rows=48, n_cols=48):
 def test_field_form_tile_arrangements(gpu, oracle, p, q, M, N, K):
     """3- and 4-bit activations at sizes where the launch rule takes each arrangement of the field-form kernels: the
     128 x 256 tile as four wave tiles of 32 x 256 (1-bit weights, K of 8192 or more) and as 2 x 2 wave tiles of
-    64 x 128, the 128 x 128 tile as four wave tiles of 32 x 128; ragged borders.  Sampled rows x columns against the
-    oracle, checksums over every output."""
+    64 x 128, the 128 x 128 tile as four wave tiles of 32 x 128; ragged borders.  Every int32 and fp16 output
+    against the oracle."""
     case = dict(M=M, N=N, K=K, p=p, q=q, a_dist="normal" if p == 4 else "bernoulli", scaled=True)
-    sampled_check(gpu, oracle, case, 7300 + 10 * p + q + M)
+    full_check(gpu, oracle, case, 7300 + 10 * p + q + M)
 
 
 def test_config2_square_4096_w1a2(gpu, oracle):
-    sampled_check(gpu, oracle, inputs.config_cases(2)[0], inputs.BASE_SEED + 2)
+    full_check(gpu, oracle, inputs.config_cases(2)[0], inputs.BASE_SEED + 2)
 
 
 @pytest.mark.parametrize("idx", range(9))
 def test_config3_decode_w2a2(gpu, oracle, idx):
+    """Decode shapes, whole outputs against the oracle, through both ways the activations can arrive: packed by
+    apmm_pack_activations (then apmm_gemm) and as codes (apmm_gemm_from_codes, the one-launch form these shapes
+    take and the one the decode timings are quoted on)."""
     case = inputs.config_cases(3)[idx]
     data = inputs.make_case(case, inputs.BASE_SEED + 3)
-    want = oracle.gemm_i64(data["a_codes"], data["w_codes"][:512], case["p"], case["q"])
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], case["p"], case["q"])
     c32, c16 = run_case(gpu, data, case, want_i32=True, want_f16=True)
-    assert np.array_equal(c32[:, :512].astype(np.int64), want)
-    sub = dict(a_scale=data["a_scale"], w_scale=data["w_scale"][:512])
-    check_f16(c16[:, :512], want, sub, oracle)
-    av = 2 * data["a_codes"].astype(np.int64) - 3
-    wv = 2 * data["w_codes"].astype(np.int64) - 3
-    assert np.array_equal(c32.astype(np.int64), av @ wv.T)       # tiny M: whole result by library matmul
+    assert np.array_equal(c32.astype(np.int64), want)
+    check_f16(c16, want, data, oracle)
+    c32, c16 = run_from_codes(gpu, data, case)
+    assert np.array_equal(c32.astype(np.int64), want)
+    check_f16(c16, want, data, oracle)
 
 
 @pytest.mark.parametrize("idx", range(6))
 def test_config4_prefill_w1a4_w2a4(gpu, oracle, idx):
-    sampled_check(gpu, oracle, inputs.config_cases(4)[idx], inputs.BASE_SEED + 4)
+    full_check(gpu, oracle, inputs.config_cases(4)[idx], inputs.BASE_SEED + 4)
 
 
-@pytest.mark.parametrize("idx", [0, 4, 6])
+@pytest.mark.parametrize("idx", range(7))
 def test_config5_decoder_layer_w2a4(gpu, oracle, idx):
-    sampled_check(gpu, oracle, inputs.config_cases(5)[idx], inputs.BASE_SEED + 5 + idx)
+    """All seven linears of the layer (q, k, v, o, gate, up, down), each with its own seeded inputs, through
+    apmm_pack_activations + apmm_gemm and through apmm_gemm_from_codes with a workspace (online packing)."""
+    case = inputs.config_cases(5)[idx]
+    full_check(gpu, oracle, case, inputs.BASE_SEED + 5 + idx, also_from_codes=True)

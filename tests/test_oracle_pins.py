@@ -263,6 +263,89 @@ def test_float_to_half_matches_the_library_conversion(oracle):
             assert oracle.float_to_half_bits(v) == int(np.float32(v).astype(np.float16).view(np.uint16)), v
 
 
+def _golden_quantize_rows():
+    rows = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "quantize_borders.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            p, s, x, c = [t.strip() for t in line.split(":")]
+            rows.append((int(p), int(s, 16), np.array([int(t, 16) for t in x.split()], dtype=np.uint16),
+                         np.array([int(t) for t in c.split()], dtype=np.uint8)))
+    return rows
+
+
+def test_quantize_matches_the_hand_worked_border_rows(oracle):
+    """Sec. 3.1 quantiser on rows with non-power-of-two scales and elements on, just below and just above
+    cell borders; scale and codes worked by hand in tests/golden/quantize_borders.txt.  (A quantiser that
+    multiplies by a rounded reciprocal of the scale lands in the lower cell at 4 s and 8 s of the third row.)"""
+    rows = _golden_quantize_rows()
+    assert [r[0] for r in rows] == [2, 3, 4]
+    for p, sbits, xbits, want in rows:
+        codes, s = oracle.quantize_rows(xbits.view(np.float16).reshape(1, -1), p)
+        assert int(s[0]) == sbits
+        assert np.array_equal(codes[0], want), (p, codes[0], want)
+
+
+def _nearest_odd_code(x, s, p):
+    """Code of the grid point nearest to x / s in exact rational arithmetic: argmin over all 2^p grid
+    values of |x / s - v|, the larger v on a tie."""
+    from fractions import Fraction
+    t = Fraction(float(x)) / Fraction(float(s))
+    best = None
+    for u in range(1 << p):
+        d = abs(t - (2 * u - ((1 << p) - 1)))
+        if best is None or d <= best[0]:
+            best = (d, u)
+    return best[1]
+
+
+@pytest.mark.parametrize("p", [1, 2, 3, 4, 6, 8])
+def test_quantize_is_the_nearest_grid_point_in_exact_arithmetic(oracle, p):
+    """Brute force from the definition: for rows with arbitrary (non-power-of-two) scales, every element
+    gets the code whose grid value is nearest to x / s, compared as exact fractions.  The rows hold random
+    values plus, for every border of the grid, the binary16 numbers at and around border * s."""
+    top = (1 << p) - 1
+    rng = np.random.default_rng(100 + p)
+    for trial in range(12):
+        amax = np.float16(rng.uniform(0.01, 900.0) if trial else 6.1e-5 * 3)   # one row with a subnormal scale
+        s_guess = np.float16(np.float32(amax) / np.float32(top))
+        extra = []
+        for c in range(1, top + 1):
+            b = np.float16(np.float64(2 * c - (1 << p)) * np.float64(s_guess))
+            for step in (-2, -1, 0, 1, 2):
+                v = (b.view(np.int16) + np.int16(step)).view(np.float16) if b != 0 else np.float16(step * 6e-8)
+                if np.isfinite(v) and abs(float(v)) <= float(amax):
+                    extra.append(v)
+        rnd = (rng.normal(size=40) * float(amax) / 2.5).astype(np.float16)
+        rnd = rnd[np.abs(rnd.astype(np.float64)) <= float(amax)]
+        x = np.concatenate([[amax], np.array(extra, dtype=np.float16), rnd]).astype(np.float16)
+        codes, sb = oracle.quantize_rows(x.reshape(1, -1), p)
+        s = sb.view(np.float16)[0]
+        # the scale: exact quotient, one rounding to binary16 (numpy rounds the exact double quotient's
+        # float32 rounding; both agree, see the oracle's note on ties)
+        from fractions import Fraction
+        q = Fraction(float(amax)) / top
+        lo, hi = np.nextafter(s, np.float16(-np.inf)), np.nextafter(s, np.float16(np.inf))
+        assert abs(Fraction(float(s)) - q) <= abs(Fraction(float(lo)) - q)
+        assert abs(Fraction(float(s)) - q) <= abs(Fraction(float(hi)) - q)
+        assert s > 0
+        want = np.array([_nearest_odd_code(v, s, p) for v in x], dtype=np.uint8)
+        assert np.array_equal(codes[0], want), (p, trial)
+
+
+def test_double_to_half_is_one_rounding(oracle):
+    """double -> binary16 directly, not through binary32: values chosen so that rounding to binary32 first
+    would land on a binary16 tie and then go the other way."""
+    x = 1.0 + 2.0 ** -11 + 2.0 ** -30           # just above the tie between 1 and 1 + 2^-10
+    assert np.float32(x) == np.float32(1.0 + 2.0 ** -11)       # binary32 loses the 2^-30
+    assert oracle.double_to_half_bits(x) == 0x3C01              # the exact value rounds up
+    assert oracle.double_to_half_bits(1.0 + 2.0 ** -11) == 0x3C00   # the tie itself goes to even
+    assert oracle.double_to_half_bits(1.0 + 3 * 2.0 ** -11 - 2.0 ** -30) == 0x3C01
+    assert oracle.double_to_half_bits(1e300) == 0x7C00 and oracle.double_to_half_bits(-1e300) == 0xFC00
+    assert oracle.double_to_half_bits(65519.999) == 0x7BFF and oracle.double_to_half_bits(65520.0) == 0x7C00
+
+
 def test_quantize_one_bit_is_the_sign(oracle):
     """Sec. 3.1: 1-bit bipolar-INT is binary quantisation, code = [x >= 0], scale = max|x|."""
     x = inputs.normal_features_f16(21, inputs.TAG_A, 9, 200)
