@@ -145,6 +145,23 @@ apmm_status apmm_gemm_from_codes(int64_t M, int64_t N, int64_t K, int p, int q,
                                  const uint16_t *w_scale, const uint16_t *a_scale,
                                  void *workspace, size_t workspace_bytes, void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): apmm_gemm_from_codes without the workspace argument.  The packed activations go into
+ * a buffer of APMM_NOALLOC_MAX_PACKED_BYTES bytes that is part of the library's device code (one per GPU, held
+ * until the process ends); the call allocates and frees nothing.  Arguments, result and kernel choice as in
+ * apmm_gemm_from_codes with a workspace of that size.
+ *   - Returns APMM_ERR_WORKSPACE (nothing launched) when apmm_packed_activation_bytes(M, K, p) exceeds
+ *     APMM_NOALLOC_MAX_PACKED_BYTES, whether or not the shape would have needed the buffer.
+ *   - Every call on one GPU uses that GPU's one buffer, from the packing launch to the end of the GEMM that
+ *     follows it on `stream`: calls that overlap on one GPU (different streams, or different threads) race.
+ *     Calls on one stream are ordered and safe.  Nothing in the buffer has to be cleared between calls: the
+ *     packing writes every byte the GEMM reads. */
+#define APMM_NOALLOC_MAX_PACKED_BYTES ((size_t)8 << 20)
+apmm_status apmm_gemm_from_codes_noalloc(int64_t M, int64_t N, int64_t K, int p, int q,
+                                         const uint8_t *a_codes, const void *w_packed,
+                                         int32_t *c_i32, uint16_t *c_f16,
+                                         const uint16_t *w_scale, const uint16_t *a_scale, void *stream);
+
 /* One linear of a grouped call: C = A * W^T with the arguments of apmm_gemm. */
 typedef struct apmm_problem {
     int64_t M, N, K;

@@ -16,7 +16,7 @@ ALGO_AUTO, ALGO_VALU_POPCOUNT, ALGO_MFMA_INT8, ALGO_DECODE, ALGO_MFMA_FP4 = 0, 1
 
 EXPORTS = [
     "apmm_packed_bytes", "apmm_packed_activation_bytes", "apmm_workspace_bytes", "apmm_pack_weights", "apmm_pack_activations",
-    "apmm_quantize_pack_activations", "apmm_unpack", "apmm_unpack_activations", "apmm_gemm", "apmm_gemm_ex", "apmm_gemm_from_codes", "apmm_gemm_grouped",
+    "apmm_quantize_pack_activations", "apmm_unpack", "apmm_unpack_activations", "apmm_gemm", "apmm_gemm_ex", "apmm_gemm_from_codes", "apmm_gemm_from_codes_noalloc", "apmm_gemm_grouped",
     "apmm_time_next_gemm", "apmm_status_string", "apmm_last_error", "apmm_version",
 ]
 
@@ -72,6 +72,8 @@ def load():
     lib.apmm_gemm_ex.argtypes = gemm_args + [ci]
     lib.apmm_gemm_from_codes.restype = ci
     lib.apmm_gemm_from_codes.argtypes = gemm_args
+    lib.apmm_gemm_from_codes_noalloc.restype = ci
+    lib.apmm_gemm_from_codes_noalloc.argtypes = [i64, i64, i64, ci, ci, vp, vp, vp, vp, vp, vp, vp]
     lib.apmm_gemm_grouped.restype = ci
     lib.apmm_gemm_grouped.argtypes = [ci, ctypes.POINTER(ApmmProblem), ci, ci, vp, ctypes.c_size_t, vp]
     lib.apmm_time_next_gemm.restype = ci
@@ -208,6 +210,19 @@ def apmm_gemm_from_codes(a_codes, N, p, q, w_packed, want_i32=True, want_f16=Fal
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().apmm_gemm_from_codes(M, N, K, p, q, _ptr(a_codes), _ptr(w_packed), _ptr(c_i32), _ptr(c_f16),
                                        _ptr(w_scale), _ptr(a_scale), _ptr(workspace), ws_bytes, _stream()))
+    return c_i32, c_f16
+
+
+NOALLOC_MAX_PACKED_BYTES = 8 << 20  # APMM_NOALLOC_MAX_PACKED_BYTES of include/apmm.h
+
+
+def apmm_gemm_from_codes_noalloc(a_codes, N, p, q, w_packed, c_i32=None, c_f16=None, w_scale=None, a_scale=None):
+    """apmm_gemm_from_codes with the packed activations in the library's built-in buffer.  The call itself
+    allocates nothing: the outputs are the caller's preallocated tensors."""
+    _dev_u8(a_codes, "a_codes")
+    M, K = a_codes.shape
+    _check(load().apmm_gemm_from_codes_noalloc(M, N, K, p, q, _ptr(a_codes), _ptr(w_packed), _ptr(c_i32), _ptr(c_f16),
+                                               _ptr(w_scale), _ptr(a_scale), _stream()))
     return c_i32, c_f16
 
 

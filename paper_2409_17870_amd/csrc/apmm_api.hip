@@ -2,6 +2,7 @@
 // lives here and nothing is allocated.
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "../../include/apmm.h"
 #include "apmm_kernels.h"
@@ -236,6 +237,62 @@ apmm_status apmm_gemm_from_codes(int64_t M, int64_t N, int64_t K, int p, int q, 
     const apmm_status cs = check_gemm(M, N, K, p, q, workspace, w_packed, c_i32, c_f16, w_scale, a_scale, g, empty);
     if (cs != APMM_OK) return cs;
     return run_gemm(g, APMM_ALGO_AUTO, s);
+}
+
+}  // extern "C"
+
+namespace {
+
+// Packed activations of apmm_gemm_from_codes_noalloc: one array per GPU, held until the process ends.  In host
+// code the array's name is only a stand-in: the device address is looked up once per device (below) and that
+// pointer is what kernels and every other call get.
+constexpr size_t kScratchBytes = APMM_NOALLOC_MAX_PACKED_BYTES;
+__device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};  // by device ordinal; written once under the mutex
+
+apmm_status scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "apmm_gemm_from_codes_noalloc: hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(APMM_ERR_UNSUPPORTED, "gemm_from_codes_noalloc: device ordinal beyond 63");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));  // this device's copy of the array
+        if (e != hipSuccess) return fail_hip(e, "apmm_gemm_from_codes_noalloc: hipGetSymbolAddress");
+        if (!ptr) return fail(APMM_ERR_HIP, "gemm_from_codes_noalloc: no device address for the scratch array");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return APMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+apmm_status apmm_gemm_from_codes_noalloc(int64_t M, int64_t N, int64_t K, int p, int q, const uint8_t *a_codes,
+                                         const void *w_packed, int32_t *c_i32, uint16_t *c_f16,
+                                         const uint16_t *w_scale, const uint16_t *a_scale, void *stream)
+{
+    if (M < 0 || K < 1 || !bits_ok(p))
+        return fail(APMM_ERR_INVALID_ARG, "gemm: M < 0, N < 0, K < 1 or bits outside [1, 8]");
+    const size_t need = apmm_packed_activation_bytes(M, K, p);
+    if (need > kScratchBytes) {
+        std::snprintf(g_error, sizeof(g_error),
+                      "gemm_from_codes_noalloc: the packed activations of this call take %zu bytes, the built-in "
+                      "buffer holds %zu (use apmm_gemm_from_codes with a workspace)", need, kScratchBytes);
+        return APMM_ERR_WORKSPACE;
+    }
+    void *ws = nullptr;
+    const apmm_status st = scratch_of_current_device(&ws);
+    if (st != APMM_OK) return st;
+    return apmm_gemm_from_codes(M, N, K, p, q, a_codes, w_packed, c_i32, c_f16, w_scale, a_scale, ws, kScratchBytes,
+                                stream);
 }
 
 apmm_status apmm_time_next_gemm(void *start_event, void *stop_event)
