@@ -46,7 +46,6 @@ typedef enum {
 typedef enum {
     APMM_ALGO_AUTO = 0,
     APMM_ALGO_VALU_POPCOUNT = 1, /* plane pairs by XOR + popcount on the vector ALU, D_ij = K - 2*popc */
-    APMM_ALGO_MFMA_INT8 = 2,     /* reserved: the int8 MFMA kernel of earlier builds; this build answers APMM_ERR_UNSUPPORTED */
     APMM_ALGO_DECODE = 3,        /* small-M weight-streaming kernels: M <= 16 with q <= 4 and p not 3 or 4, and M <= 64 for p, q <= 2 */
     APMM_ALGO_MFMA_FP4 = 4       /* plane groups recombined to E2M1 codes in registers, f8f6f4 MFMA, exact fp32 accumulate
                                     (p, q <= 4 and 4 * roundup(K,512) * (2^p-1)(2^q-1) < 2^24) */
@@ -128,7 +127,9 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q,
                          void *workspace, size_t workspace_bytes, void *stream,
                          int algo);
 
-/* apmm_gemm taking the activation codes as they are (paper Sec. 4.1 and 3.2 in one call): `a_codes` is
+/* apmm_gemm taking the activation codes as they are: the preprocessing of paper Sec. 4.1 (decomposition,
+ * reassembly, concatenation) for the activations and the bit-wise MatMul of Sec. 3.2 in one call, as an
+ * inference engine meets them (Sec. 5.2: the activations of a layer are produced online).  `a_codes` is
  * the device M x K row-major uint8 matrix that apmm_pack_activations would take (bits above p are
  * ignored, no alignment needed).  Result and all other arguments as in apmm_gemm.
  *   - For a few tokens the small-M kernels regroup the codes into the packed form on their way into
@@ -174,7 +175,8 @@ typedef struct apmm_problem {
     const uint8_t *a_codes;   /* device, M x K unpacked activation codes as for apmm_gemm_from_codes, or NULL */
 } apmm_problem;
 
-/* Several independent GEMMs of equal p and q with as few launches as possible (for callers whose
+/* Paper Sec. 5.2 setting (the linears of a decoder layer, each the MatMul of Sec. 3.2): several independent
+ * GEMMs of equal p and q with as few launches as possible (for callers whose
  * linears are small enough that the launch, not the data, bounds them: the q/k/v or gate/up
  * projections of one decoder layer at a few tokens share their activations and can go in one launch).
  * `problems` is a HOST array of `count` entries, read before the call returns.  Each entry obeys the
@@ -187,11 +189,17 @@ typedef struct apmm_problem {
 apmm_status apmm_gemm_grouped(int count, const apmm_problem *problems, int p, int q,
                               void *workspace, size_t workspace_bytes, void *stream);
 
-/* Measurement aid.  The next apmm_gemm / apmm_gemm_ex call of the calling thread, if it runs the large-tile
- * MFMA kernel, attaches the two hipEvent_t (created by the caller; either may be NULL) to that kernel's
- * dispatch itself (hipExtLaunchKernel): afterwards they hold the kernel's own begin and end, without the
- * dispatch gaps that events recorded before and after the call include.  Any other GEMM call drops them. */
+/* Measurement aid.  The next apmm_gemm / apmm_gemm_ex / apmm_gemm_from_codes call of the calling thread, if it
+ * runs the large-tile MFMA kernel or a small-M kernel in one launch, attaches the two hipEvent_t (created by the
+ * caller; either may be NULL) to that kernel's dispatch itself (hipExtLaunchKernel): afterwards they hold the
+ * kernel's own begin and end, without the dispatch gaps that events recorded before and after the call include.
+ * A call that runs the general XOR/popcount kernel drops them. */
 apmm_status apmm_time_next_gemm(void *start_event, void *stop_event);
+
+/* Measurement aid.  Name, with its template arguments, of the GEMM kernel that the last GEMM call of the calling
+ * thread launched ("" before the first), e.g. "gemm_mfma_direct_kernel<2,1,4,4,3>" (activation bits, weight bits,
+ * wave tile in 32-row and 32-column blocks, store phases).  The string is overwritten by the next GEMM call. */
+const char *apmm_last_gemm_kernel(void);
 
 const char *apmm_status_string(apmm_status status);
 /* Text of the last error on the calling thread ("" if none). */

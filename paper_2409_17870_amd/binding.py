@@ -12,12 +12,12 @@ import torch  # imported before the library so that both share one HIP runtime (
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libapmm.so")
 
-ALGO_AUTO, ALGO_VALU_POPCOUNT, ALGO_MFMA_INT8, ALGO_DECODE, ALGO_MFMA_FP4 = 0, 1, 2, 3, 4
+ALGO_AUTO, ALGO_VALU_POPCOUNT, ALGO_DECODE, ALGO_MFMA_FP4 = 0, 1, 3, 4
 
 EXPORTS = [
     "apmm_packed_bytes", "apmm_packed_activation_bytes", "apmm_workspace_bytes", "apmm_pack_weights", "apmm_pack_activations",
     "apmm_quantize_pack_activations", "apmm_unpack", "apmm_unpack_activations", "apmm_gemm", "apmm_gemm_ex", "apmm_gemm_from_codes", "apmm_gemm_from_codes_noalloc", "apmm_gemm_grouped",
-    "apmm_time_next_gemm", "apmm_status_string", "apmm_last_error", "apmm_version",
+    "apmm_time_next_gemm", "apmm_last_gemm_kernel", "apmm_status_string", "apmm_last_error", "apmm_version",
 ]
 
 
@@ -78,6 +78,8 @@ def load():
     lib.apmm_gemm_grouped.argtypes = [ci, ctypes.POINTER(ApmmProblem), ci, ci, vp, ctypes.c_size_t, vp]
     lib.apmm_time_next_gemm.restype = ci
     lib.apmm_time_next_gemm.argtypes = [vp, vp]
+    lib.apmm_last_gemm_kernel.restype = ctypes.c_char_p
+    lib.apmm_last_gemm_kernel.argtypes = []
     lib.apmm_status_string.restype = ctypes.c_char_p
     lib.apmm_status_string.argtypes = [ci]
     lib.apmm_last_error.restype = ctypes.c_char_p
@@ -244,6 +246,11 @@ def apmm_gemm_grouped(problems, p, q):
             t = pr.get(key)
             setattr(arr[i], key, t.data_ptr() if t is not None else None)
     _check(load().apmm_gemm_grouped(len(problems), arr, p, q, None, 0, _stream()))
+
+
+def apmm_last_gemm_kernel():
+    """Name of the GEMM kernel the last GEMM call of this thread launched."""
+    return load().apmm_last_gemm_kernel().decode()
 
 
 def apmm_time_next_gemm(start_event, stop_event):

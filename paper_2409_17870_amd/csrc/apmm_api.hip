@@ -166,14 +166,12 @@ apmm_status run_gemm(const apmm::GemmArgs &g, int algo, hipStream_t s)
         else if (apmm::gemm_mfma_fp4_supported(g)) algo = APMM_ALGO_MFMA_FP4;
         else algo = APMM_ALGO_VALU_POPCOUNT;
     }
-    if (algo != APMM_ALGO_MFMA_FP4) (void)apmm::take_kernel_timing();  // only that kernel takes timing events
+    if (algo != APMM_ALGO_MFMA_FP4 && algo != APMM_ALGO_DECODE) (void)apmm::take_kernel_timing();  // the others take no timing events
     hipError_t e;
     switch (algo) {
     case APMM_ALGO_VALU_POPCOUNT:
         e = apmm::launch_gemm_valu(g, s);
         break;
-    case APMM_ALGO_MFMA_INT8:
-        return fail(APMM_ERR_UNSUPPORTED, "gemm: no int8 MFMA kernel in this build");
     case APMM_ALGO_MFMA_FP4:
         if (!apmm::gemm_mfma_fp4_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: FP4 MFMA kernel covers p, q in 1..4 while 4 K (2^p - 1)(2^q - 1) < 2^24");
         e = apmm::launch_gemm_mfma_fp4(g, s);
@@ -200,7 +198,8 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
 {
     (void)workspace;
     (void)workspace_bytes;
-    if (algo < APMM_ALGO_AUTO || algo > APMM_ALGO_MFMA_FP4) return fail(APMM_ERR_INVALID_ARG, "gemm: unknown algo");
+    if (algo != APMM_ALGO_AUTO && algo != APMM_ALGO_VALU_POPCOUNT && algo != APMM_ALGO_DECODE && algo != APMM_ALGO_MFMA_FP4)
+        return fail(APMM_ERR_INVALID_ARG, "gemm: unknown algo");
     apmm::GemmArgs g;
     bool empty;
     const apmm_status st = check_gemm(M, N, K, p, q, a_packed, w_packed, c_i32, c_f16, w_scale, a_scale, g, empty);
@@ -225,7 +224,6 @@ apmm_status apmm_gemm_from_codes(int64_t M, int64_t N, int64_t K, int p, int q, 
     const bool fused_pays = M * N <= 65536;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (fused_ok && (fused_pays || !room)) {
-        (void)apmm::take_kernel_timing();
         const hipError_t e = apmm::launch_gemm_decode(g, s);
         if (e != hipSuccess) return fail_hip(e, "apmm_gemm_from_codes");
         return APMM_OK;
@@ -362,6 +360,8 @@ const char *apmm_status_string(apmm_status status)
 }
 
 const char *apmm_last_error(void) { return g_error; }
+
+const char *apmm_last_gemm_kernel(void) { return apmm::last_kernel(); }
 
 int apmm_version(void) { return 100; }
 

@@ -21,6 +21,8 @@
 // once per workgroup from their packed tiles into LDS with every plane in the common form of the XOR/popcount
 // kernels (16 elements per word at the even bit positions, apmm_layout.h); a weight plane is brought to the
 // same form after loading, so that any activation plane can be XOR-ed with any weight plane.
+#include <hip/hip_ext.h>
+
 #include "apmm_mfma_common.h"
 
 namespace apmm {
@@ -345,7 +347,12 @@ hipError_t launch_group(Kernel kernel, bool &attr_set, const GroupArgs &ga, size
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)ga.wg_end[ga.count - 1]), dim3(kThreads), lds, stream, ga);
+    const KernelTiming timing = take_kernel_timing();
+    if (timing.start || timing.stop)
+        hipExtLaunchKernelGGL(kernel, dim3((unsigned)ga.wg_end[ga.count - 1]), dim3(kThreads), lds, stream,
+                              timing.start, timing.stop, 0, ga);
+    else
+        hipLaunchKernelGGL(kernel, dim3((unsigned)ga.wg_end[ga.count - 1]), dim3(kThreads), lds, stream, ga);
     return hipGetLastError();
 }
 
@@ -355,6 +362,7 @@ hipError_t launch_mt_q(const GroupArgs &ga, hipStream_t stream)
     size_t lds = 0;
     for (int i = 0; i < ga.count; ++i) lds = lds > decode_lds_bytes(ga.g[i], MT) ? lds : decode_lds_bytes(ga.g[i], MT);
     static bool attr_set[2] = {false, false};
+    note_kernel("gemm_decode_kernel<%d,%d,%s>", MT, Q, ga.g[0].a_codes ? "codes" : "packed");
     if (ga.g[0].a_codes) return launch_group(gemm_decode_kernel<MT, Q, true>, attr_set[1], ga, lds, stream);
     return launch_group(gemm_decode_kernel<MT, Q, false>, attr_set[0], ga, lds, stream);
 }
@@ -674,6 +682,7 @@ hipError_t launch_decode_mfma_v(const GroupArgs &ga, hipStream_t stream)
     for (int i = 0; i < ga.count; ++i)
         lds = lds > decode_mfma_lds_bytes(ga.g[i], RT) ? lds : decode_mfma_lds_bytes(ga.g[i], RT);
     static bool attr_set[2] = {false, false};
+    note_kernel("gemm_decode_mfma_kernel<%d,%d,%d,%d,%s>", P, Q, TT, RT, ga.g[0].a_codes ? "codes" : "packed");
     if (ga.g[0].a_codes) return launch_group(gemm_decode_mfma_kernel<P, Q, TT, RT, true>, attr_set[1], ga, lds, stream);
     return launch_group(gemm_decode_mfma_kernel<P, Q, TT, RT, false>, attr_set[0], ga, lds, stream);
 }

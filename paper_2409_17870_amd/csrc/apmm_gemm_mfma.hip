@@ -1,12 +1,24 @@
 // Dispatch of the MFMA GEMMs (design A).  The kernels are instantiated in apmm_gemm_mfma_p<P>.hip,
 // one translation unit per activation width, so that they compile in parallel.
+#include <cstdarg>
+#include <cstdio>
+
 #include "apmm_kernels.h"
 
 namespace apmm {
 
 namespace {
 thread_local KernelTiming g_timing = {nullptr, nullptr};
+thread_local char g_last_kernel[96] = "";
 }
+void note_kernel(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    std::vsnprintf(g_last_kernel, sizeof(g_last_kernel), fmt, ap);
+    va_end(ap);
+}
+const char *last_kernel() { return g_last_kernel; }
 void set_kernel_timing(hipEvent_t start, hipEvent_t stop) { g_timing = KernelTiming{start, stop}; }
 KernelTiming take_kernel_timing()
 {

@@ -531,6 +531,7 @@ hipError_t launch_direct_variant(const GemmArgs &g, hipStream_t stream)
     const int64_t tiles = tiles_m * tiles_n;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
     const KernelTiming timing = take_kernel_timing();
+    note_kernel("gemm_mfma_direct_kernel<%d,%d,%d,%d,%d>", P, Q, WM, WN, SPLIT);
     if (timing.start || timing.stop)
         hipExtLaunchKernelGGL((gemm_mfma_direct_kernel<P, Q, WM, WN, SPLIT>), dim3((unsigned)tiles), dim3(256), 0,
                               stream, timing.start, timing.stop, 0, g, (int)tiles_n, (int)tiles);

@@ -6,8 +6,20 @@
 namespace apmm {
 namespace mfma {
 
+// Switches for A/B measurements of the launch rule exist only in builds with -DAPMM_DEBUG_SWITCHES; the
+// product build reads no environment variable.
+inline const char *debug_switch(const char *name)
+{
+#ifdef APMM_DEBUG_SWITCHES
+    return std::getenv(name);
+#else
+    (void)name;
+    return nullptr;
+#endif
+}
+
 // Tile choice: estimate each candidate as (rounds of 256 tiles) x (tile area) x (measured relative
-// cost per MFMA of that tile shape) and take the cheapest.  APMM_MFMA_TILE=0..3 forces one (debugging).
+// cost per MFMA of that tile shape) and take the cheapest.  (Debug builds: APMM_MFMA_TILE=0..3 forces one.)
 template <int P, int Q>
 hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream)
 {
@@ -19,8 +31,8 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream)
                            {128, 128, AF ? 1.15 : 1.2}};
     int best = 0;
     double best_t = 0;
-    static const char *forced = std::getenv("APMM_MFMA_TILE");
-    static const char *no_split = std::getenv("APMM_MFMA_SPLIT");
+    static const char *forced = debug_switch("APMM_MFMA_TILE");
+    static const char *no_split = debug_switch("APMM_MFMA_SPLIT");
     if (forced && forced[0] >= '0' && forced[0] <= '3' && !(AF && forced[0] < '2')) {
         best = forced[0] - '0';
     } else {
@@ -35,7 +47,7 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream)
     }
     if constexpr (AF) {
         (void)no_split;
-        static const char *square = std::getenv("APMM_MFMA_AF_2X2");
+        static const char *square = debug_switch("APMM_MFMA_AF_2X2");
         const bool old_arrangement = square && square[0] == '1';
         if (best == 2) {
             // 1-bit weights: four wave tiles of 32 x 256 need 3.5 instead of 4 KB per wave and k step (with wider

@@ -87,6 +87,7 @@ hipError_t launch_gemm_valu(const GemmArgs &args, hipStream_t stream)
 {
     const int64_t gx = (args.N + kTile - 1) / kTile, gy = (args.M + kTile - 1) / kTile;
     if (gx > 0x7fffffffLL / gy) return hipErrorInvalidValue;
+    note_kernel("gemm_valu_kernel");
     hipLaunchKernelGGL(gemm_valu_kernel, dim3((unsigned)(gx * gy)), dim3(kTile, kTile), 0, stream, args, gx);
     return hipGetLastError();
 }

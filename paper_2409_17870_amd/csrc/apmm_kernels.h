@@ -23,13 +23,17 @@ hipError_t launch_gemm_valu(const GemmArgs &args, hipStream_t stream);
 bool gemm_mfma_fp4_supported(const GemmArgs &args);
 hipError_t launch_gemm_mfma_fp4(const GemmArgs &args, hipStream_t stream);
 
-// Measurement aid: a pair of events that the next large-tile MFMA GEMM launch of the calling thread attaches
-// to its kernel dispatch (hipExtLaunchKernel), so that they hold the kernel's own begin and end.
+// Measurement aid: a pair of events that the next GEMM launch of the calling thread (large-tile MFMA kernel or
+// small-M kernels) attaches to its kernel dispatch (hipExtLaunchKernel), so that they hold the kernel's own
+// begin and end.
 struct KernelTiming {
     hipEvent_t start, stop;
 };
 void set_kernel_timing(hipEvent_t start, hipEvent_t stop);
 KernelTiming take_kernel_timing();  // returns the pair and clears it
+// Measurement aid: name (with template arguments) of the GEMM kernel the calling thread launched last.
+void note_kernel(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
+const char *last_kernel();
 
 // Small-M weight-streaming kernels (M <= 16; M <= 64 on the matrix unit for p, q <= 2).
 bool gemm_decode_supported(const GemmArgs &args);

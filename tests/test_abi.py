@@ -81,7 +81,7 @@ def test_argument_errors_come_before_any_launch(lib):
     assert _gemm(lib, 0, 4, 32768, 8, 8) == 0                       # M == 0: ok, nothing launched
     assert _gemm(lib, 4, 4, 32769, 8, 8) == OVERFLOW
     assert _gemm(lib, 4, 4, 40000, 8, 8) == OVERFLOW
-    assert _gemm(lib, 64, 64, 128, 2, 2, algo=2) == UNSUPPORTED     # reserved algo id: no int8 MFMA kernel in this build
+    assert _gemm(lib, 64, 64, 128, 2, 2, algo=2) == INVALID         # an id no kernel of this build has
     assert lib.apmm_status_string(OVERFLOW) == b"result exceeds 32 bits"
     assert lib.apmm_pack_weights(None, 4, 128, 2, None, None) == INVALID
     assert lib.apmm_pack_activations(0x1000, 4, 128, 0, 0x2000, None) == INVALID

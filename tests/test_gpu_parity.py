@@ -12,7 +12,7 @@ from paper_2409_17870_amd import inputs
 
 pytestmark = pytest.mark.gpu
 
-VALU, MFMA, DECODE, FP4 = 1, 2, 3, 4
+VALU, DECODE, FP4 = 1, 3, 4
 
 
 @pytest.fixture(scope="module")
