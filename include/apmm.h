@@ -46,9 +46,12 @@ typedef enum {
 typedef enum {
     APMM_ALGO_AUTO = 0,
     APMM_ALGO_VALU_POPCOUNT = 1, /* plane pairs by XOR + popcount on the vector ALU, D_ij = K - 2*popc */
-    APMM_ALGO_DECODE = 3,        /* small-M weight-streaming kernels: M <= 16 with q <= 4 and p not 3 or 4, and M <= 64 for p, q <= 2 */
-    APMM_ALGO_MFMA_FP4 = 4       /* plane groups recombined to E2M1 codes in registers, f8f6f4 MFMA, exact fp32 accumulate
+    APMM_ALGO_DECODE = 3,        /* small-M weight-streaming kernels: M <= 64 for p, q <= 2 (matrix unit), M <= 16 with q <= 4 and
+                                    p not 3 or 4 otherwise (XOR + popcount) */
+    APMM_ALGO_MFMA_FP4 = 4,      /* plane groups recombined to E2M1 codes in registers, f8f6f4 MFMA, exact fp32 accumulate
                                     (p, q <= 4 and 4 * roundup(K,512) * (2^p-1)(2^q-1) < 2^24) */
+    APMM_ALGO_DECODE_VALU = 5    /* the XOR + popcount small-M kernel whatever the widths (M <= 16, q <= 4, p not 3 or 4):
+                                    design B at decode shapes, for comparison */
 } apmm_algo;
 
 /* Bytes of the packed form of a rows x K operand of `bits`-bit codes (paper Sec. 4.1:
@@ -135,7 +138,7 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q,
  *   - For a few tokens the small-M kernels regroup the codes into the packed form on their way into
  *     on-chip memory: one launch, no packed buffer.  The separate packing launch costs as much as such a
  *     GEMM.  Taken when the small-M kernels cover the shape (M <= 16 with q <= 4 and p not 3 or 4, or
- *     M <= 64 with p, q <= 2) and M * N <= 65536.
+ *     M <= 64 with p, q <= 2) and M <= 16 or M * N <= 65536.
  *   - Otherwise the codes are packed into `workspace` (device, 16-byte aligned, at least
  *     apmm_packed_activation_bytes(M, K, p) bytes, overwritten) and apmm_gemm runs on that: two launches.
  * Without such a workspace the call still takes the one-launch path wherever the small-M kernels cover the

@@ -12,7 +12,7 @@ import torch  # imported before the library so that both share one HIP runtime (
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libapmm.so")
 
-ALGO_AUTO, ALGO_VALU_POPCOUNT, ALGO_DECODE, ALGO_MFMA_FP4 = 0, 1, 3, 4
+ALGO_AUTO, ALGO_VALU_POPCOUNT, ALGO_DECODE, ALGO_MFMA_FP4, ALGO_DECODE_VALU = 0, 1, 3, 4, 5
 
 EXPORTS = [
     "apmm_packed_bytes", "apmm_packed_activation_bytes", "apmm_workspace_bytes", "apmm_pack_weights", "apmm_pack_activations",

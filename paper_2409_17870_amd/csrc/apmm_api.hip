@@ -166,7 +166,7 @@ apmm_status run_gemm(const apmm::GemmArgs &g, int algo, hipStream_t s)
         else if (apmm::gemm_mfma_fp4_supported(g)) algo = APMM_ALGO_MFMA_FP4;
         else algo = APMM_ALGO_VALU_POPCOUNT;
     }
-    if (algo != APMM_ALGO_MFMA_FP4 && algo != APMM_ALGO_DECODE) (void)apmm::take_kernel_timing();  // the others take no timing events
+    if (algo == APMM_ALGO_VALU_POPCOUNT) (void)apmm::take_kernel_timing();  // that kernel takes no timing events
     hipError_t e;
     switch (algo) {
     case APMM_ALGO_VALU_POPCOUNT:
@@ -179,6 +179,10 @@ apmm_status run_gemm(const apmm::GemmArgs &g, int algo, hipStream_t s)
     case APMM_ALGO_DECODE:
         if (!apmm::gemm_decode_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: decode kernel does not cover this request");
         e = apmm::launch_gemm_decode(g, s);
+        break;
+    case APMM_ALGO_DECODE_VALU:
+        if (!apmm::gemm_decode_valu_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: the XOR/popcount small-M kernel does not cover this request");
+        e = apmm::launch_gemm_decode_valu(g, s);
         break;
     default:
         return fail(APMM_ERR_INVALID_ARG, "gemm: unknown algo");
@@ -198,7 +202,8 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
 {
     (void)workspace;
     (void)workspace_bytes;
-    if (algo != APMM_ALGO_AUTO && algo != APMM_ALGO_VALU_POPCOUNT && algo != APMM_ALGO_DECODE && algo != APMM_ALGO_MFMA_FP4)
+    if (algo != APMM_ALGO_AUTO && algo != APMM_ALGO_VALU_POPCOUNT && algo != APMM_ALGO_DECODE && algo != APMM_ALGO_MFMA_FP4 &&
+        algo != APMM_ALGO_DECODE_VALU)
         return fail(APMM_ERR_INVALID_ARG, "gemm: unknown algo");
     apmm::GemmArgs g;
     bool empty;
@@ -219,9 +224,10 @@ apmm_status apmm_gemm_from_codes(int64_t M, int64_t N, int64_t K, int p, int q, 
     if (workspace && !aligned16(workspace)) return fail(APMM_ERR_INVALID_ARG, "gemm_from_codes: workspace must be 16-byte aligned");
     const bool fused_ok = apmm::gemm_decode_supported(g);
     const bool room = workspace && workspace_bytes >= apmm_packed_activation_bytes(M, K, p);
-    // Every workgroup of the small-M kernels regroups all M x K codes for itself: that beats a packing launch
-    // (about 3 us) while M x N is small, and loses to it beyond (measured: break-even near 16 tokens x 4096 channels).
-    const bool fused_pays = M * N <= 65536;
+    // Every workgroup of the small-M kernels loads all M x K codes for itself: that beats a packing launch
+    // (2.5 - 3 us) up to 16 tokens at every width measured (16 tokens x 11008 channels: 7.3 us in one launch, 7.2 us
+    // in two), and for more tokens while M x N is small.
+    const bool fused_pays = M <= 16 || M * N <= 65536;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (fused_ok && (fused_pays || !room)) {
         const hipError_t e = apmm::launch_gemm_decode(g, s);

@@ -32,6 +32,7 @@ constexpr int kWaves = 8;
 constexpr int kThreads = 64 * kWaves;
 constexpr int kRowsPerWg = 16;
 constexpr int kMaxLdsBytes = 128 * 1024;
+constexpr int kMfmaMinTokens = 1;  // the matrix-unit kernel serves every token count its code widths allow
 
 // Words 4*hh .. 4*hh+3 of plane i of an n-bit operand in the common form come from one 16-byte vector of the
 // slots of a row and k block (`slots` points at the uint4 of slot 0; consecutive slots are kPlaneWords / 4
@@ -380,115 +381,267 @@ hipError_t launch_mt(const GroupArgs &ga, hipStream_t stream)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Small-M kernel on the matrix unit (3 <= M <= 64, p, q <= 2).  With more than a couple of tokens
-// the XOR/popcount form needs 2 p q M lane-operations per weight word and becomes VALU bound; the
-// E2M1 MFMA needs one expansion of the weight words (1.25 - 1.5 operations per 8 codes) whatever M is.
-// Same split of the work (8 waves over K, lane = weight row l % 16 and k block l / 16 of four), same
-// algebra as the large-M MFMA kernel:
+// Small-M kernel on the matrix unit (M <= 64, p, q <= 2).  With more than a couple of tokens the
+// XOR/popcount form needs 2 p q M lane-operations per weight word and becomes VALU bound; the E2M1 MFMA
+// needs one expansion of the weight words (1.25 - 1.5 operations per 8 codes) whatever M is.
+// Same split of the work as the XOR/popcount kernel (8 waves over K, lane = weight row l % 16 and k block
+// l / 16 of four), same algebra as the large-M MFMA kernel:
 //   v_mfma_scale_f32_16x16x128_f8f6f4: A = 16 weight rows x 128 k, B = 128 k x 16 tokens, codes as E2M1;
 //   MFMA ks of an iteration multiplies k step ks of the four k blocks held by the four lane groups;
 //   a workgroup owns RT tiles of 16 output channels and all TT tiles of 16 tokens: a weight fragment is
 //   expanded once and multiplied with TT token fragments, a token fragment with RT weight fragments;
-//   the packed activations of all K are copied once per workgroup into LDS as they are, [k block][token][slot],
-//   and expanded where they are used; C = acc - 2 cw PA[m] - 2 ca PW[n] + K ca cw with the packed row sums
-//   (the operand scales make acc = 4 S).
-// RT = 2 halves the number of workgroups (and of activation copies) when there are plenty of output channels.
+//   C = acc - 2 cw PA[m] - 2 ca PW[n] + K ca cw with the packed row sums (the operand scales make acc = 4 S).
+// No staging through LDS and no barrier before the k loop: the waves split K, so every (token, k block)
+// fragment of the activations is consumed by exactly one lane group of one wave, which loads it straight
+// from global memory (L2) like its weights: lane (r16, kq) takes the P slots of token 16 tt + r16 in its
+// k block, 256 contiguous bytes per 16 lanes.  Everything a wave needs is requested in its first
+// instructions; the only barrier is the one of the cross-wave reduction at the end.
+// With activation codes as input (CODES = 1, or 2 for rows that allow no aligned 16-byte loads) a wave loads
+// the codes of its group of four k blocks together, turns every 16 codes into the packed word they form and
+// passes the words to the lanes that need them through LDS of its own (see load_chunks); the tokens' code
+// sums PA[m], which the packed operand would have carried, come from one more MFMA per k step against a
+// weight fragment of all-one codes.  NJ = 1 is the variant for at most two tokens: one chunk per lane, few
+// enough registers for three workgroups per CU.
+// The first problem's arguments are plain kernel arguments ahead of the group descriptor: this file is built
+// with kernel-argument preloading, so the first 14 dwords of the kernel-argument segment are in scalar
+// registers when the wave starts and a single-problem launch computes its first addresses without a round
+// trip to memory for its arguments (measured: 0.3 us of a 3.4 us launch).
+// RT = 2 halves the number of workgroups when there are plenty of output channels.
+// Measured against the version that staged the activations of all K through LDS behind a workgroup barrier
+// (W2A2, us per launch inside a graph, cold weights; 4096 x 4096 / 11008 x 4096 / 4096 x 11008): packed
+// operands, 8 tokens 3.6 -> 3.1 / 5.1 -> 4.4 / 5.8 -> 4.6; from codes, 1 token (then on the XOR/popcount
+// kernel) 4.3 -> 3.2 / 7.6 -> 4.7 / 6.1 -> 4.9, 16 tokens 5.7 -> 4.4 / 9.8 -> 7.3 / 10.1 -> 7.1.
 // ---------------------------------------------------------------------------------------------
-template <int P, int Q, int TT, int RT, bool CODES>
-__global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga)
+struct DecodeProblem {
+    const uint32_t *w;
+    const void *a;          // packed activations, or codes (CODES)
+    int64_t N, K, M;
+    uint16_t *c_f16;
+    int32_t *c_i32;
+    const uint16_t *w_scale, *a_scale;
+};
+
+// problem of this workgroup and its index among the problem's workgroups
+__device__ __forceinline__ int pick_problem(DecodeProblem &pr, uint32_t misc, const GroupArgs &ga)
 {
-    // which problem of the launch this workgroup works on (uniform over the workgroup); problem 0 from fixed
-    // kernel-argument offsets (see gemm_decode_kernel)
-    GemmArgs g = ga.g[0];
-    int64_t chunk_kb = ga.chunk_kb[0];
     int block = (int)blockIdx.x;
-    if (ga.count > 1) {
+    const int count = (int)(misc >> 8);
+    if (count > 1) {
         int idx = 0;
-        for (int i = 0; i + 1 < ga.count; ++i)
+        for (int i = 0; i + 1 < count; ++i)
             if ((int)blockIdx.x >= ga.wg_end[i]) idx = i + 1;
         if (idx > 0) {
-            g = ga.g[idx];
-            chunk_kb = ga.chunk_kb[idx];
+            const GemmArgs &g = ga.g[idx];
+            pr.w = g.w;
+            pr.a = g.a_codes ? static_cast<const void *>(g.a_codes) : static_cast<const void *>(g.a);
+            pr.N = g.N; pr.K = g.K; pr.M = g.M;
+            pr.c_f16 = g.c_f16; pr.c_i32 = g.c_i32;
+            pr.w_scale = g.w_scale; pr.a_scale = g.a_scale;
             block -= ga.wg_end[idx - 1];
         }
     }
+    return block;
+}
+
+template <int P, int Q, int TT, int RT, int CODES, int NJ = 8>
+__global__ __launch_bounds__(kThreads, (CODES == 1 && TT == 1) ? (NJ == 1 && RT == 1 ? 6 : 4) : 2)  // waves per SIMD aimed at
+void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg, int k_arg,
+                             uint32_t misc_arg /* M | problems << 8 */, int reserved_arg, uint16_t *cf_arg, int32_t *ci_arg,
+                             const uint16_t *ws_arg, const uint16_t *as_arg, GroupArgs ga)
+{
     static_assert(P <= 2 && Q <= 2, "one plane group per operand");
-    constexpr int TOKENS = 16 * TT, ROWS = kRowsPerWg * RT;
+    static_assert(NJ == 8 || (NJ == 1 && CODES == 1 && TT == 1), "NJ = 1: codes of at most two tokens");
+    (void)reserved_arg;
+    DecodeProblem pr = {w_arg, a_arg, n_arg, k_arg, (int64_t)(misc_arg & 0xffu), cf_arg, ci_arg, ws_arg, as_arg};
+    const int block = pick_problem(pr, misc_arg, ga);
+    constexpr int ROWS = kRowsPerWg * RT;
     constexpr int OUTS = (TT * RT * 256 + kThreads - 1) / kThreads;  // outputs per thread
     constexpr uint32_t ca = (1u << P) - 1, cw = (1u << Q) - 1;
-    extern __shared__ __align__(16) uint8_t lds_raw[];
-    uint4 *a_lds = reinterpret_cast<uint4 *>(lds_raw);  // [kb][token < TOKENS][slot < P]: packed words as they are
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t n0 = (int64_t)block * ROWS;
     constexpr int kSlotVec = kPlaneWords / 4;
-
+    extern __shared__ __align__(16) uint8_t lds_raw[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r16 = lane & 15, kq = lane >> 4;
-    const int64_t rows_b = round_up(g.N, kRowBlock);
-    int64_t n_ld[RT];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) n_ld[rt] = n0 + rt * 16 + r16 < rows_b ? n0 + rt * 16 + r16 : rows_b - 1;
+    const int64_t n0 = (int64_t)block * ROWS;
+    const int64_t nkb = ((pr.K + kKPad - 1) / kKPad) * (kKPad / kKBlock);
+    const int64_t rows_a = round_up(pr.M, kRowBlock), rows_b = round_up(pr.N, kRowBlock);
 
-    // Order of the requests (see gemm_decode_kernel): this thread's first two vectors of packed activations, then
-    // the weights of the first k block, then what only the final store needs.
-    const int64_t rows_a = round_up(g.M, kRowBlock);
-    const uint32_t vecs_pass0 = (uint32_t)(chunk_kb < g.nkb ? chunk_kb : g.nkb) * P * TOKENS;
-    // vector c of a pass that starts at k block kb0 is (k block, slot, token); LDS index = c with slot and token swapped
-    auto vec_src = [&](uint32_t c, int64_t kb0, uint32_t &lds_index) {
-        const uint32_t m = c % TOKENS, s = (c / TOKENS) % P, ckb = (c / TOKENS) / P;
-        const int64_t m_ld = m < rows_a ? m : rows_a - 1;  // tokens past the padded rows are clamped and never stored
-        lds_index = (ckb * TOKENS + m) * P + s;
-        return reinterpret_cast<const uint4 *>(g.a + tile_row_word(m_ld, kb0 + ckb, g.nkb, P, s));
+    // this lane's weight rows and tokens, at its k block of the wave's first group of four
+    const int groups = (int)(nkb / 4);                       // groups of four k blocks; the waves take them in turn
+    const int iters = groups > wave ? (groups - wave + kWaves - 1) / kWaves : 0;
+    const uint4 *wsrc[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        const int64_t n = n0 + rt * 16 + r16 < rows_b ? n0 + rt * 16 + r16 : rows_b - 1;
+        wsrc[rt] = reinterpret_cast<const uint4 *>(pr.w + tile_row_word(n, 4 * wave + kq, nkb, Q, 0));
+    }
+    constexpr int kIterVecW = 4 * kWaves * Q * kSlotVec;     // uint4 between this lane's k blocks of consecutive iterations
+    constexpr int kIterVecA = 4 * kWaves * P * kSlotVec;
+    const uint4 *asrc[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        asrc[tt] = nullptr;
+        if constexpr (!CODES) {
+            // tokens past M: the padded rows of the last row block hold zero words (read, never stored)
+            const int64_t t = tt * 16 + r16, t_ld = t < rows_a ? t : rows_a - 1;
+            asrc[tt] = reinterpret_cast<const uint4 *>(static_cast<const uint32_t *>(pr.a) +
+                                                       tile_row_word(t_ld, 4 * wave + kq, nkb, P, 0));
+        }
+    }
+
+    uint4 wnext[RT][2], anext[TT][2];
+    auto load_packed = [&](int it) __attribute__((always_inline)) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int s = 0; s < Q; ++s) wnext[rt][s] = wsrc[rt][(int64_t)it * kIterVecW + s * kSlotVec];
+        if constexpr (!CODES) {
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int s = 0; s < P; ++s) anext[tt][s] = asrc[tt][(int64_t)it * kIterVecA + s * kSlotVec];
+        }
     };
-    constexpr int PEEL = 2;
-    uint4 a_first[PEEL];
-    uint32_t a_first_index[PEEL];
-    if constexpr (!CODES) {
+    // CODES.  The codes of one token tile and one group of four k blocks are 16 runs of 512 contiguous bytes
+    // (one per token).  The wave loads them together, lane l taking chunk l % 32 (16 codes) of token 2 j + l / 32 in
+    // its j-th load: every load instruction reads two whole runs.  The 16 codes of a chunk are exactly one packed
+    // word of their row and k block (word w = chunk % 8 of k block chunk / 8: apmm_layout.h), so a lane turns
+    // each chunk into that word with seven operations and the words change lanes through a piece of LDS that
+    // belongs to the wave alone (no workgroup barrier): lane (r16, kq) reads back the eight words of token r16 in
+    // k block kq, its MFMA fragment.
+    constexpr int kXposeWords = P == 1 ? 1024 : 512;  // per wave: [token 16][k block 4][word 8] (single group: two partial words each)
+    uint32_t *xpose = reinterpret_cast<uint32_t *>(lds_raw) + kWaves * RT * TT * 256 + kWaves * TT * 16 + wave * kXposeWords;
+    // CODES == 1: K is a multiple of 16 and the matrix starts at a multiple of 16 bytes, so every chunk is one
+    // aligned 16-byte load and lies wholly inside the row or wholly in the padding.  The loads are issued without
+    // any condition on the lane (lanes with nothing to load read the first chunk of the matrix instead and mask it
+    // away at the point of use): a load inside a divergent branch makes the wave wait for it, and for everything
+    // requested before it, at the end of the branch.
+    // CODES == 2: any K and alignment, byte by byte (correct, slow).
+    auto load_chunks = [&](int tt, int it, uint4 (&v)[NJ]) __attribute__((always_inline)) {
+        const int64_t k0 = (int64_t)4 * kKBlock * (wave + (int64_t)kWaves * it) + 16 * (lane & 31);
+        const int64_t m_tile = pr.M - tt * 16;  // tokens of this tile that exist
+        // (the row length as an opaque value: the addresses are then formed where they are used instead of being
+        // kept in registers across the k loop, two registers per load and token tile)
+        int64_t row_len = pr.K;
+        asm volatile("" : "+s"(row_len));
+        // CODES == 1: one 32-bit lane offset serves all eight loads; the token pair's row is a uniform base.  Lanes
+        // with nothing to load (odd token past M, chunk in the padding) read the first chunk of the pair's first
+        // token, which exists whenever the load is issued at all.
+        uint32_t lane_off = 0;
+        if (k0 + 16 <= row_len) lane_off = (uint32_t)((lane >> 5) * row_len + k0);
 #pragma unroll
-        for (int i = 0; i < PEEL; ++i) {
-            a_first[i] = make_uint4(0, 0, 0, 0);
-            a_first_index[i] = 0;
-            if ((uint32_t)tid + i * kThreads < vecs_pass0) a_first[i] = *vec_src(tid + i * kThreads, 0, a_first_index[i]);
+        for (int jj = 0; jj < NJ; ++jj) {
+            const int64_t t = tt * 16 + 2 * jj + (lane >> 5);
+            if constexpr (CODES == 1) {
+                const uint8_t *pair_row = static_cast<const uint8_t *>(pr.a) + (int64_t)(tt * 16 + 2 * jj) * row_len;  // uniform
+                const uint32_t off = t < pr.M ? lane_off : 0u;
+                if (2 * jj < m_tile) v[jj] = *reinterpret_cast<const uint4 *>(pair_row + off);  // uniform: token pairs that exist
+                else v[jj] = make_uint4(0, 0, 0, 0);
+            } else {
+                uint32_t d[4] = {0u, 0u, 0u, 0u};  // tokens past M: zero words, as the padded rows of a packed operand
+                if (t < pr.M) {
+                    const uint8_t *src = static_cast<const uint8_t *>(pr.a) + t * row_len + k0;
+                    const int64_t left = row_len - k0;
+                    const int count = left >= 16 ? 16 : (left > 0 ? (int)left : 0);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) d[i] = 0xffffffffu;  // positions past K hold the all-ones padding code
+#pragma unroll 1
+                    for (int e = 0; e < count; ++e) {
+                        const uint32_t flip = (uint32_t)(src[e] ^ 0xffu) << (8 * (e & 3));
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (i == (e >> 2)) d[i] ^= flip;
+                    }
+                }
+                v[jj] = make_uint4(d[0], d[1], d[2], d[3]);
+            }
         }
-    }
-
-    // (from here to the LDS writes every thread issues every load, from clamped addresses where it has nothing
-    // to load, see gemm_decode_kernel)
-    int64_t kb4 = wave;
-    uint4 wnext[RT][2];
-    {
-        const int64_t kb_ld = kb4 * 4 < g.nkb ? kb4 * 4 + kq : g.nkb - 4 + kq;
+    };
+    auto chunks_to_fragment = [&](int tt, int it, const uint4 (&v)[NJ], uint4 (&aq)[2]) __attribute__((always_inline)) {
+        constexpr uint32_t code_mask = 0x01010101u * ca;
+        // the wave's previous fragment has been read by every lane before anything is overwritten
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int w = lane & 7, slot = ((lane >> 5) * 4 + ((lane & 31) >> 3)) * 8 + w;  // + 64 jj: token 2 jj + l / 32
+        const int64_t k0 = (int64_t)4 * kKBlock * (wave + (int64_t)kWaves * it) + 16 * (lane & 31);
+        const bool inside = k0 + 16 <= pr.K;
+        const int64_t m_tile = pr.M - tt * 16;
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            const uint4 *wsrc = reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld[rt], kb_ld, g.nkb, Q, 0));
-#pragma unroll
-            for (int s = 0; s < Q; ++s) wnext[rt][s] = wsrc[s * kSlotVec];
+        for (int jj = 0; jj < NJ; ++jj) {
+            if (2 * jj >= m_tile) continue;  // uniform; the slots of tokens that do not exist are never stored outputs
+            // what the lane loaded counts only for a token that exists and a chunk inside the row; a chunk in the
+            // padding of an existing token holds the all-ones code, a token past M zero words
+            uint32_t m_and = code_mask, m_or = 0u;
+            if constexpr (CODES == 1) {
+                const bool valid = tt * 16 + 2 * jj + (lane >> 5) < pr.M;
+                m_and = valid && inside ? code_mask : 0u;
+                m_or = valid && !inside ? code_mask : 0u;
+            }
+            // dword i = 2 t2 + jh of the chunk holds the elements (t = 2 tp + t2, jh, c = 0..3) of the word
+            const uint32_t d0 = (v[jj].x & m_and) | m_or, d1 = (v[jj].y & m_and) | m_or, d2 = (v[jj].z & m_and) | m_or,
+                           d3 = (v[jj].w & m_and) | m_or;
+            if constexpr (P == 2) {
+                // S[w]: bit b of element (t2, jh, c) at 8c + 4jh + 2 t2 + b
+                xpose[64 * jj + slot] = d0 | (d1 << 4) | (d2 << 2) | (d3 << 6);
+            } else {
+                // L[2 tp], L[2 tp + 1]: the bit of element (ks, t, jh, c) at 8c + 4jh + ks; this chunk is k step w / 2
+                const int ks = w >> 1;
+                *reinterpret_cast<uint2 *>(xpose + 2 * (64 * jj + slot)) = make_uint2((d0 | (d1 << 4)) << ks, (d2 | (d3 << 4)) << ks);
+            }
         }
-    }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int mine = (r16 * 4 + kq) * 8;
+        if constexpr (P == 2) {
+            aq[0] = *reinterpret_cast<const uint4 *>(xpose + mine);
+            aq[1] = *reinterpret_cast<const uint4 *>(xpose + mine + 4);
+        } else {
+            uint4 q[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) q[i] = *reinterpret_cast<const uint4 *>(xpose + 2 * mine + 4 * i);
+            // q[i] = (first, second partial of word 2i, first, second partial of word 2i + 1); words with even w feed
+            // L[0], L[1], words with odd w L[2], L[3]
+            aq[0] = make_uint4(q[0].x | q[1].x | q[2].x | q[3].x, q[0].y | q[1].y | q[2].y | q[3].y,
+                               q[0].z | q[1].z | q[2].z | q[3].z, q[0].w | q[1].w | q[2].w | q[3].w);
+        }
+    };
 
-    // What the final store needs is requested now as well and kept as loaded (see gemm_decode_kernel): code sums
-    // PA[m], PW[n] and the scales.  Output o of this thread is element (tile t = (tid + o * kThreads) / 256,
-    // register v, lane l) of the accumulators, t = rt * TT + tt; 16x16 accumulator layout: lane l, register v holds
-    // row 4*(l/16) + v (weight row), column l%16 (token).
+    // Order of the requests: weights and activations of the first iteration, then what only the final store
+    // needs (kept as loaded: nothing may use those values before the end, or the wave would wait for them here).
+    // one token tile: the chunks of the next iteration are requested as soon as those of the current one have been
+    // turned into words (their registers are free from then on), ahead of the MFMAs
+    uint4 vcur[CODES && TT == 1 ? NJ : 1];
+    if (iters > 0) {
+        load_packed(0);
+        if constexpr (CODES && TT == 1) load_chunks(0, 0, vcur);
+    }
     bool out_ok[OUTS];
     int out_m[OUTS];
     int64_t out_n[OUTS];
     uint32_t out_sa_bits[OUTS], out_sw_bits[OUTS], out_pa[OUTS], out_pw[OUTS];
+    {
+        const int32_t *w_sum = reinterpret_cast<const int32_t *>(pr.w + row_sum_word(rows_b, nkb, Q));
+        const int32_t *a_sum = CODES ? nullptr
+                                     : reinterpret_cast<const int32_t *>(static_cast<const uint32_t *>(pr.a) +
+                                                                         row_sum_word(rows_a, nkb, P));
+        const uint16_t *dummy = reinterpret_cast<const uint16_t *>(pr.w);
 #pragma unroll
-    for (int o = 0; o < OUTS; ++o) {
-        const int e = tid + o * kThreads, t = e >> 8, v = (e >> 6) & 3, l = e & 63;
-        out_m[o] = (t % TT) * 16 + (l & 15);
-        out_n[o] = n0 + (t / TT) * 16 + 4 * (l >> 4) + v;
-        out_ok[o] = t < TT * RT && out_m[o] < g.M && out_n[o] < g.N;
-        // clamped to the padded rows of the sums and to the last entry of the scales; a missing scale vector reads
-        // a weight word instead (replaced by 1.0 at the end)
-        const int64_t m_c = out_m[o] < rows_a ? out_m[o] : rows_a - 1, n_c = out_n[o] < rows_b ? out_n[o] : rows_b - 1;
-        const uint16_t *dummy = reinterpret_cast<const uint16_t *>(g.w);
-        // (with activation codes as input the row sum PA[m] is taken while packing, see below)
-        out_pa[o] = 0;
-        if constexpr (!CODES) out_pa[o] = (uint32_t)g.a_sum[m_c];
-        out_pw[o] = (uint32_t)g.w_sum[n_c];
-        out_sa_bits[o] = *(g.a_scale ? g.a_scale + (m_c < g.M ? m_c : g.M - 1) : dummy);
-        out_sw_bits[o] = *(g.w_scale ? g.w_scale + (n_c < g.N ? n_c : g.N - 1) : dummy);
+        for (int o = 0; o < OUTS; ++o) {
+            // output o of this thread is element (tile t = e / 256, register v, lane l) of the accumulators,
+            // t = rt * TT + tt; 16x16 accumulator layout: lane l, register v holds row 4*(l/16) + v (weight row),
+            // column l%16 (token)
+            const int e = tid + o * kThreads, t = e >> 8, v = (e >> 6) & 3, l = e & 63;
+            out_m[o] = (t % TT) * 16 + (l & 15);
+            out_n[o] = n0 + (t / TT) * 16 + 4 * (l >> 4) + v;
+            out_ok[o] = t < TT * RT && out_m[o] < pr.M && out_n[o] < pr.N;
+            const int64_t m_c = out_m[o] < rows_a ? out_m[o] : rows_a - 1, n_c = out_n[o] < rows_b ? out_n[o] : rows_b - 1;
+            out_pa[o] = 0;
+            if constexpr (!CODES) out_pa[o] = (uint32_t)a_sum[m_c];
+            out_pw[o] = (uint32_t)w_sum[n_c];
+            out_sa_bits[o] = *(pr.a_scale ? pr.a_scale + (m_c < pr.M ? m_c : pr.M - 1) : dummy);
+            out_sw_bits[o] = *(pr.w_scale ? pr.w_scale + (n_c < pr.N ? n_c : pr.N - 1) : dummy);
+        }
     }
 
     mfma::v4f acc[RT][TT];
@@ -496,146 +649,93 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = mfma::v4f{0.f, 0.f, 0.f, 0.f};
+    // CODES: the tokens' code sums PA[m] come from the matrix unit as well: one more MFMA per k step against a
+    // weight fragment of all-one codes gives 4 PA[token] in every row
+    mfma::v4f acc_pa[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) acc_pa[tt] = mfma::v4f{0.f, 0.f, 0.f, 0.f};
 
-    // The activations of chunk_kb k blocks at a time sit in LDS (all of K when it fits, the usual case); a pass
-    // boundary is a multiple of 32 k blocks, the stride of the waves' groups of four k blocks.
-    uint32_t *pa_lds = reinterpret_cast<uint32_t *>(lds_raw) + chunk_kb * TOKENS * P * 4;  // behind the words
-    if constexpr (CODES) {
-        if (tid < TOKENS) pa_lds[tid] = 0u;  // token code sums, taken while packing (made visible by the barriers below)
-    }
-    for (int64_t kb0 = 0; kb0 < g.nkb; kb0 += chunk_kb) {
-        const int64_t kb_end = kb0 + chunk_kb < g.nkb ? kb0 + chunk_kb : g.nkb;
-        const int64_t pass_kb = kb_end - kb0;
-        __syncthreads();  // every wave is done with the previous pass (first pass: the sums are zero)
-        if constexpr (CODES) {
-            // Straight from the codes: a thread takes the 128 codes of (token m, k block), writes them as the packed
-            // words of that row and block (apmm_layout.h) and adds them to the token's code sum.
-            const uint32_t total_blocks = (uint32_t)pass_kb * TOKENS;
-            for (uint32_t c = tid; c < total_blocks; c += kThreads) {  // consecutive lanes: consecutive 128 bytes of a row
-                const uint32_t m = c / (uint32_t)pass_kb, ckb = c - m * (uint32_t)pass_kb;
-                uint32_t d[32];
-                load_code_block(g.a_codes, g.M, g.K, P, m, kb0 + ckb, d);
-                uint32_t sum = 0;
+    for (int it = 0; it < iters; ++it) {
+        uint4 wq[RT][2], aq[TT][2];
 #pragma unroll
-                for (int i = 0; i < 32; ++i) sum = __builtin_amdgcn_sad_u8(d[i], 0u, sum);
-                // a pass has a multiple of 4 k blocks: the four lanes of an aligned quad hold blocks of the same token
-                sum += __shfl_xor(sum, 1);
-                sum += __shfl_xor(sum, 2);
-                if ((lane & 3) == 0) atomicAdd(&pa_lds[m], sum);
-                uint4 *dst = a_lds + (ckb * TOKENS + m) * P;
-                if (P == 2) {
-                    uint32_t word[8];  // S[w], w = 2 ks + tp: bit b of element (ks, t = 2 tp + tt, jh, c) at 8c + 4jh + 2tt + b
+        for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-                    for (int w = 0; w < 8; ++w) {
-                        word[w] = 0;
-#pragma unroll
-                        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                            for (int jh = 0; jh < 2; ++jh)
-                                word[w] |= d[8 * (w >> 1) + 2 * (2 * (w & 1) + tt) + jh] << (4 * jh + 2 * tt);
-                    }
-                    dst[0] = make_uint4(word[0], word[1], word[2], word[3]);
-                    dst[1] = make_uint4(word[4], word[5], word[6], word[7]);
-                } else {
-                    uint32_t word[4];  // L[t]: the bit of element (ks, t, jh, c) at 8c + 4jh + ks
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        word[t] = 0;
-#pragma unroll
-                        for (int ks = 0; ks < 4; ++ks)
-                            word[t] |= (d[8 * ks + 2 * t] | (d[8 * ks + 2 * t + 1] << 4)) << ks;
-                    }
-                    dst[0] = make_uint4(word[0], word[1], word[2], word[3]);
-                }
-            }
-        } else {
-            // 16 tokens of a slot are 256 contiguous bytes (tokens past M: the last padded row block holds zero
-            // words up to a multiple of 32)
-            const uint32_t total_vecs = (uint32_t)pass_kb * P * TOKENS;
-            uint32_t c = tid;
-            if (kb0 == 0) {  // the vectors requested at the top
-#pragma unroll
-                for (int i = 0; i < PEEL; ++i)
-                    if (c + i * kThreads < total_vecs) a_lds[a_first_index[i]] = a_first[i];
-                c += PEEL * kThreads;
-            }
-            for (; c < total_vecs; c += kThreads) {
-                uint32_t index;
-                const uint4 v = *vec_src(c, kb0, index);
-                a_lds[index] = v;
-            }
-        }
-        __syncthreads();
-        if constexpr (CODES) {
-            if (kb_end == g.nkb) {  // the code sums are complete
-#pragma unroll
-                for (int o = 0; o < OUTS; ++o)
-                    if (out_ok[o]) out_pa[o] = pa_lds[out_m[o]];
-            }
-        }
-
-        // nkb and the pass boundaries are multiples of 4: whole groups of four k blocks
-        for (; kb4 * 4 < kb_end; kb4 += kWaves) {
-            const int64_t kb = kb4 * 4 + kq;
-            uint4 wq[RT][2], aq[TT][2];
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-                for (int s = 0; s < Q; ++s) wq[rt][s] = wnext[rt][s];
-            if ((kb4 + kWaves) * 4 < g.nkb) {  // next block of this lane
-#pragma unroll
-                for (int rt = 0; rt < RT; ++rt) {
-                    const uint4 *wsrc =
-                        reinterpret_cast<const uint4 *>(g.w + tile_row_word(n_ld[rt], kb + 4 * kWaves, g.nkb, Q, 0));
-#pragma unroll
-                    for (int s = 0; s < Q; ++s) wnext[rt][s] = wsrc[s * kSlotVec];
-                }
-            }
+            for (int s = 0; s < Q; ++s) wq[rt][s] = wnext[rt][s];
+        if constexpr (!CODES) {
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-                for (int s = 0; s < P; ++s) aq[tt][s] = a_lds[((kb - kb0) * TOKENS + tt * 16 + r16) * P + s];
-            mfma::static_for<4>([&](auto ks_c) __attribute__((always_inline)) {
-                constexpr int ks = decltype(ks_c)::value;
-                mfma::v8i a8[RT], b8[TT];
-#pragma unroll
-                for (int rt = 0; rt < RT; ++rt) a8[rt] = mfma::v8i{0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) b8[tt] = mfma::v8i{0, 0, 0, 0, 0, 0, 0, 0};
-                mfma::static_for<4>([&](auto d_c) __attribute__((always_inline)) {
-                    constexpr int d = decltype(d_c)::value;
-#pragma unroll
-                    for (int rt = 0; rt < RT; ++rt) {
-                        if constexpr (Q == 1) a8[rt][d] = (int)mfma::fp4_single_dword<ks, d>(wq[rt][0]);
-                        else a8[rt][d] = (int)mfma::fp4_pair_dword<ks, d>(wq[rt][0], wq[rt][1]);
-                    }
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt) {
-                        if constexpr (P == 1) b8[tt][d] = (int)mfma::fp4_single_dword<ks, d>(aq[tt][0]);
-                        else b8[tt][d] = (int)mfma::fp4_pair_dword<ks, d>(aq[tt][0], aq[tt][1]);
-                    }
-                });
-                // E8M0 exponents: 2^2 per operand turns (ua/2)(uw/2) into 4 ua uw
-#pragma unroll
-                for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt)
-                        acc[rt][tt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                            a8[rt], b8[tt], acc[rt][tt], 4, 4, 0, 129 + (Q == 1 ? mfma::fp4_single_exponent(ks) : 0), 0,
-                            129 + (P == 1 ? mfma::fp4_single_exponent(ks) : 0));
-            });
+                for (int s = 0; s < P; ++s) aq[tt][s] = anext[tt][s];
         }
+        if constexpr (CODES && TT == 1) {
+            if (it + 1 < iters) load_packed(it + 1);
+            chunks_to_fragment(0, it, vcur, aq[0]);
+            if (it + 1 < iters) load_chunks(0, it + 1, vcur);
+        } else {
+            if (it + 1 < iters) load_packed(it + 1);
+            if constexpr (CODES) {
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    uint4 v[NJ];
+                    load_chunks(tt, it, v);
+                    chunks_to_fragment(tt, it, v, aq[tt]);
+                    __builtin_amdgcn_sched_barrier(0);  // one tile's chunks in registers at a time
+                }
+            }
+        }
+        mfma::static_for<4>([&](auto ks_c) __attribute__((always_inline)) {
+            constexpr int ks = decltype(ks_c)::value;
+            mfma::v8i a8[RT], b8[TT];
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) a8[rt] = mfma::v8i{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) b8[tt] = mfma::v8i{0, 0, 0, 0, 0, 0, 0, 0};
+            mfma::static_for<4>([&](auto d_c) __attribute__((always_inline)) {
+                constexpr int d = decltype(d_c)::value;
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    if constexpr (Q == 1) a8[rt][d] = (int)mfma::fp4_single_dword<ks, d>(wq[rt][0]);
+                    else a8[rt][d] = (int)mfma::fp4_pair_dword<ks, d>(wq[rt][0], wq[rt][1]);
+                }
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    if constexpr (P == 1) b8[tt][d] = (int)mfma::fp4_single_dword<ks, d>(aq[tt][0]);
+                    else b8[tt][d] = (int)mfma::fp4_pair_dword<ks, d>(aq[tt][0], aq[tt][1]);
+                }
+            });
+            // E8M0 exponents: 2^2 per operand turns (ua/2)(uw/2) into 4 ua uw
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+                    acc[rt][tt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                        a8[rt], b8[tt], acc[rt][tt], 4, 4, 0, 129 + (Q == 1 ? mfma::fp4_single_exponent(ks) : 0), 0,
+                        129 + (P == 1 ? mfma::fp4_single_exponent(ks) : 0));
+            if constexpr (CODES) {
+                const mfma::v8i ones = {0x11111111, 0x11111111, 0x11111111, 0x11111111, 0, 0, 0, 0};  // E2M1 0.5 = the code 1
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+                    acc_pa[tt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                        ones, b8[tt], acc_pa[tt], 4, 4, 0, 129, 0, 129 + (P == 1 ? mfma::fp4_single_exponent(ks) : 0));
+            }
+        });
     }
 
-    // reduce over the waves through LDS: part[wave][tile t][v][lane]
-    __syncthreads();  // every wave is done reading the activations
+    // reduce over the waves through LDS: part[wave][tile t][v][lane], and (CODES) the code sums pa[wave][token]
     float *part = reinterpret_cast<float *>(lds_raw);
+    uint32_t *pa_lds = reinterpret_cast<uint32_t *>(lds_raw) + kWaves * RT * TT * 256;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
             for (int v = 0; v < 4; ++v) part[((wave * RT * TT + rt * TT + tt) * 4 + v) * 64 + lane] = acc[rt][tt][v];
+    if constexpr (CODES) {
+        // register 0 of lanes 0 .. 15 is row 0, token = lane: 4 PA[token], an integer below 2^24
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+            if (lane < 16) pa_lds[wave * TT * 16 + tt * 16 + lane] = (uint32_t)(int32_t)acc_pa[tt][0] >> 2;
+    }
     __syncthreads();
 #pragma unroll
     for (int o = 0; o < OUTS; ++o) {
@@ -644,35 +744,63 @@ __global__ __launch_bounds__(kThreads) void gemm_decode_mfma_kernel(GroupArgs ga
         float s = 0.f;
 #pragma unroll
         for (int w8 = 0; w8 < kWaves; ++w8) s += part[w8 * RT * TT * 256 + e];
+        uint32_t pa = out_pa[o];
+        if constexpr (CODES) {
+            pa = 0;
+#pragma unroll
+            for (int w8 = 0; w8 < kWaves; ++w8) pa += pa_lds[w8 * TT * 16 + out_m[o]];
+        } else {
+            pa = use_here(pa);
+        }
         // C = 4 S - 2 cw PA[m] - 2 ca PW[n] + K ca cw
-        const uint32_t terms = (uint32_t)g.K * ca * cw - 2u * cw * use_here(out_pa[o]) - 2u * ca * use_here(out_pw[o]);
-        const uint32_t sa_bits = g.a_scale ? use_here(out_sa_bits[o]) : 0x3c00u;  // 1.0
-        const uint32_t sw_bits = g.w_scale ? use_here(out_sw_bits[o]) : 0x3c00u;
-        store_output(g, out_m[o], out_n[o], (int32_t)((uint32_t)(int32_t)s + terms), half_bits_to_float((uint16_t)sa_bits),
-                     half_bits_to_float((uint16_t)sw_bits));
+        const uint32_t terms = (uint32_t)pr.K * ca * cw - 2u * cw * pa - 2u * ca * use_here(out_pw[o]);
+        const uint32_t sa_bits = pr.a_scale ? use_here(out_sa_bits[o]) : 0x3c00u;  // 1.0
+        const uint32_t sw_bits = pr.w_scale ? use_here(out_sw_bits[o]) : 0x3c00u;
+        const int32_t c = (int32_t)((uint32_t)(int32_t)s + terms);
+        const int64_t at = (int64_t)out_m[o] * pr.N + out_n[o];
+        if (pr.c_i32) pr.c_i32[at] = c;
+        if (pr.c_f16)
+            pr.c_f16[at] = float_to_half_bits((float)c * half_bits_to_float((uint16_t)sa_bits) *
+                                              half_bits_to_float((uint16_t)sw_bits));
     }
 }
 
 int decode_token_tiles(int64_t M) { return M <= 16 ? 1 : M <= 32 ? 2 : 4; }
 
-int64_t decode_mfma_pass_kb(const GemmArgs &g)
-{
-    const int tt = decode_token_tiles(g.M);
-    return pass_k_blocks(g.nkb, (size_t)16 * tt * 16 * g.p, (size_t)16 * tt * 4);
-}
-
 size_t decode_mfma_lds_bytes(const GemmArgs &g, int rt)
 {
     const int tt = decode_token_tiles(g.M);
-    const size_t a_bytes = (size_t)decode_mfma_pass_kb(g) * 16 * tt * 16 * g.p + 16 * tt * 4;  // packed words + code sums
-    const size_t part_bytes = (size_t)kWaves * rt * tt * 256 * 4;
-    return a_bytes > part_bytes ? a_bytes : part_bytes;
+    // accumulator partials + code sums + (codes) the waves' exchange areas
+    return (size_t)kWaves * rt * tt * 256 * 4 + (size_t)kWaves * tt * 16 * 4 + (g.a_codes ? (size_t)kWaves * (g.p == 1 ? 4096 : 2048) : 0);
 }
 
 bool decode_mfma_supported(const GemmArgs &g)
 {
-    return g.M >= 3 && g.M <= 64 && g.p <= 2 && g.q <= 2 && decode_mfma_pass_kb(g) > 0 &&
+    return g.M >= kMfmaMinTokens && g.M <= 64 && g.p <= 2 && g.q <= 2 && g.K <= 0x7fffffffLL && g.N <= 0x7fffffffLL &&
            4 * g.nkb * kKBlock * 9 < (1 << 24);
+}
+
+template <class Kernel>
+hipError_t launch_group_scalars(Kernel kernel, bool &attr_set, const GroupArgs &ga, size_t lds, hipStream_t stream)
+{
+    if (!attr_set) {  // idempotent; a race here is harmless
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const GemmArgs &g = ga.g[0];
+    const void *a = g.a_codes ? static_cast<const void *>(g.a_codes) : static_cast<const void *>(g.a);
+    const uint32_t misc = (uint32_t)g.M | ((uint32_t)ga.count << 8);
+    const dim3 grid((unsigned)ga.wg_end[ga.count - 1]), block(kThreads);
+    const KernelTiming timing = take_kernel_timing();
+    if (timing.start || timing.stop)
+        hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, timing.start, timing.stop, 0, g.w, a, (int)g.N, (int)g.K,
+                              misc, 0, g.c_f16, g.c_i32, g.w_scale, g.a_scale, ga);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, lds, stream, g.w, a, (int)g.N, (int)g.K, misc, 0, g.c_f16, g.c_i32,
+                           g.w_scale, g.a_scale, ga);
+    return hipGetLastError();
 }
 
 template <int P, int Q, int TT, int RT>
@@ -681,10 +809,29 @@ hipError_t launch_decode_mfma_v(const GroupArgs &ga, hipStream_t stream)
     size_t lds = 0;
     for (int i = 0; i < ga.count; ++i)
         lds = lds > decode_mfma_lds_bytes(ga.g[i], RT) ? lds : decode_mfma_lds_bytes(ga.g[i], RT);
-    static bool attr_set[2] = {false, false};
+    static bool attr_set[4] = {false, false, false, false};
     note_kernel("gemm_decode_mfma_kernel<%d,%d,%d,%d,%s>", P, Q, TT, RT, ga.g[0].a_codes ? "codes" : "packed");
-    if (ga.g[0].a_codes) return launch_group(gemm_decode_mfma_kernel<P, Q, TT, RT, true>, attr_set[1], ga, lds, stream);
-    return launch_group(gemm_decode_mfma_kernel<P, Q, TT, RT, false>, attr_set[0], ga, lds, stream);
+    if (ga.g[0].a_codes) {
+        // (four token tiles from codes with two row tiles would not fit the registers: the launcher never asks for it)
+        if constexpr (TT == 4 && RT == 2) {
+            return hipErrorInvalidValue;
+        } else {
+            // one aligned 16-byte load per chunk when every problem's rows allow it, else the byte-wise variant
+            bool vec_ok = true;
+            for (int i = 0; i < ga.count; ++i)
+                vec_ok = vec_ok && (ga.g[i].K & 15) == 0 && (reinterpret_cast<uintptr_t>(ga.g[i].a_codes) & 15) == 0;
+            if constexpr (TT == 1) {
+                // at most two tokens everywhere: the variant that loads one chunk per lane (fewer registers, three
+                // workgroups per CU)
+                bool two = vec_ok;
+                for (int i = 0; i < ga.count; ++i) two = two && ga.g[i].M <= 2;
+                if (two) return launch_group_scalars(gemm_decode_mfma_kernel<P, Q, TT, RT, 1, 1>, attr_set[3], ga, lds, stream);
+            }
+            if (vec_ok) return launch_group_scalars(gemm_decode_mfma_kernel<P, Q, TT, RT, 1>, attr_set[1], ga, lds, stream);
+            return launch_group_scalars(gemm_decode_mfma_kernel<P, Q, TT, RT, 2>, attr_set[2], ga, lds, stream);
+        }
+    }
+    return launch_group_scalars(gemm_decode_mfma_kernel<P, Q, TT, RT, 0>, attr_set[0], ga, lds, stream);
 }
 
 template <int P, int Q>
@@ -711,11 +858,11 @@ hipError_t launch_decode_mfma(const GroupArgs &ga, int rt, hipStream_t stream)
 
 // kernel variant that serves a problem: 0 = none, 100 + token tiles = matrix unit, else the token tile of the
 // XOR/popcount kernel
-int decode_variant(const GemmArgs &g)
+int decode_variant(const GemmArgs &g, bool xor_only = false)
 {
     if (g.M < 1 || g.M > 64 || g.q < 1 || g.q > 4) return 0;
     if (activation_field_form(g.p)) return 0;  // 3- and 4-bit activations are laid out for the large-tile MFMA kernel
-    if (decode_mfma_supported(g)) return 100 + decode_token_tiles(g.M);
+    if (!xor_only && decode_mfma_supported(g)) return 100 + decode_token_tiles(g.M);
     if (g.M > 16) return 0;
     return decode_pass_kb(g, decode_mt(g.M)) > 0 ? decode_mt(g.M) : 0;
 }
@@ -724,6 +871,7 @@ int decode_variant(const GemmArgs &g)
 
 // M <= 16 with q <= 4, or M <= 64 with p, q <= 2; never activations in the field form (p = 3, 4).
 bool gemm_decode_supported(const GemmArgs &g) { return decode_variant(g) != 0; }
+bool gemm_decode_valu_supported(const GemmArgs &g) { return decode_variant(g, true) != 0; }
 
 bool gemm_decode_group_supported(const GemmArgs *gs, int count)
 {
@@ -736,19 +884,27 @@ bool gemm_decode_group_supported(const GemmArgs *gs, int count)
     return v != 0;
 }
 
-hipError_t launch_gemm_decode_group(const GemmArgs *gs, int count, hipStream_t stream)
+hipError_t launch_gemm_decode_group(const GemmArgs *gs, int count, hipStream_t stream, bool xor_only)
 {
     GroupArgs ga;
-    if (!gemm_decode_group_supported(gs, count)) return hipErrorInvalidValue;
-    const int variant = decode_variant(gs[0]);
+    if (xor_only ? (count != 1 || !gemm_decode_valu_supported(gs[0])) : !gemm_decode_group_supported(gs, count))
+        return hipErrorInvalidValue;
+    const int variant = decode_variant(gs[0], xor_only);
     if (variant > 100) {
         // two row tiles per workgroup once that still leaves two workgroups per CU
         int64_t rows = 0;
         for (int i = 0; i < count; ++i) rows += gs[i].N;
         // (from unpacked codes already at half as many channels: every workgroup regroups all the codes for itself,
         // so fewer, larger workgroups pay: 7.7 -> 6.7 us for 4 tokens at 11008 x 4096, a loss at 4096 channels)
-        const int rt = rows >= (gs[0].a_codes ? 256 * 2 * kRowsPerWg : 2 * 256 * 2 * kRowsPerWg) ? 2 : 1;
-        if (!make_group(gs, count, kRowsPerWg * rt, [](const GemmArgs &g) { return decode_mfma_pass_kb(g); }, ga))
+        int rt = rows >= (gs[0].a_codes ? 256 * 2 * kRowsPerWg : 2 * 256 * 2 * kRowsPerWg) ? 2 : 1;
+        if (gs[0].a_codes) {
+            // at most two tokens from codes: that kernel variant fits three workgroups per CU
+            bool two = true;
+            for (int i = 0; i < count; ++i) two = two && gs[i].M <= 2;
+            if (two) rt = rows > 3 * 256 * kRowsPerWg ? 2 : 1;
+        }
+        if (gs[0].a_codes && variant == 104) rt = 1;  // four token tiles from codes: two row tiles do not fit the registers
+        if (!make_group(gs, count, kRowsPerWg * rt, [](const GemmArgs &g) { return g.nkb; }, ga))
             return hipErrorInvalidValue;
         return launch_decode_mfma(ga, rt, stream);
     }
@@ -763,7 +919,8 @@ hipError_t launch_gemm_decode_group(const GemmArgs *gs, int count, hipStream_t s
     }
 }
 
-hipError_t launch_gemm_decode(const GemmArgs &g, hipStream_t stream) { return launch_gemm_decode_group(&g, 1, stream); }
+hipError_t launch_gemm_decode(const GemmArgs &g, hipStream_t stream) { return launch_gemm_decode_group(&g, 1, stream, false); }
+hipError_t launch_gemm_decode_valu(const GemmArgs &g, hipStream_t stream) { return launch_gemm_decode_group(&g, 1, stream, true); }
 
 
 }  // namespace apmm

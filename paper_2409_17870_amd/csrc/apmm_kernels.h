@@ -35,12 +35,15 @@ KernelTiming take_kernel_timing();  // returns the pair and clears it
 void note_kernel(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
 const char *last_kernel();
 
-// Small-M weight-streaming kernels (M <= 16; M <= 64 on the matrix unit for p, q <= 2).
+// Small-M weight-streaming kernels: on the matrix unit for p, q <= 2 (M <= 64), XOR/popcount for wider codes (M <= 16).
 bool gemm_decode_supported(const GemmArgs &args);
 hipError_t launch_gemm_decode(const GemmArgs &args, hipStream_t stream);
+// The XOR/popcount small-M kernel whatever the code widths (M <= 16, q <= 4): design B at decode shapes.
+bool gemm_decode_valu_supported(const GemmArgs &args);
+hipError_t launch_gemm_decode_valu(const GemmArgs &args, hipStream_t stream);
 // Up to kMaxGroup small-M problems of equal p, q in one launch; they must all be covered by the same
 // kernel variant (gemm_decode_group_supported).
 bool gemm_decode_group_supported(const GemmArgs *args, int count);
-hipError_t launch_gemm_decode_group(const GemmArgs *args, int count, hipStream_t stream);
+hipError_t launch_gemm_decode_group(const GemmArgs *args, int count, hipStream_t stream, bool xor_only = false);
 
 }  // namespace apmm

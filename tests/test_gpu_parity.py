@@ -12,7 +12,7 @@ from paper_2409_17870_amd import inputs
 
 pytestmark = pytest.mark.gpu
 
-VALU, DECODE, FP4 = 1, 3, 4
+VALU, DECODE, FP4, DECODE_VALU = 1, 3, 4, 5
 
 
 @pytest.fixture(scope="module")
@@ -58,6 +58,8 @@ def algos_for(case):
     if (case["M"] <= 16 and case["q"] <= 4 and case["p"] not in (3, 4)) or \
             (case["M"] <= 64 and case["p"] <= 2 and case["q"] <= 2):
         algos.append(DECODE)
+    if case["M"] <= 16 and case["q"] <= 4 and case["p"] not in (3, 4):
+        algos.append(DECODE_VALU)
     return algos + [0]
 
 
@@ -162,9 +164,10 @@ def test_decode_kernel_all_token_counts(gpu, oracle, M, p, q):
     case = dict(M=M, N=203, K=1100, p=p, q=q, a_dist="bernoulli", scaled=True)
     data = inputs.make_case(case, 5000 + 100 * M + 10 * p + q)
     want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
-    c32, c16 = run_case(gpu, data, case, algo=DECODE)
-    assert np.array_equal(c32.astype(np.int64), want)
-    check_f16(c16, want, data, oracle)
+    for algo in (DECODE, DECODE_VALU):          # the matrix-unit kernel where it covers the widths, and XOR/popcount
+        c32, c16 = run_case(gpu, data, case, algo=algo)
+        assert np.array_equal(c32.astype(np.int64), want)
+        check_f16(c16, want, data, oracle)
 
 
 @pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (1, 2), (2, 2)])
@@ -277,9 +280,10 @@ def test_decode_kernels_with_k_beyond_one_pass(gpu, oracle, M, K, p, q):
     case = dict(M=M, N=77, K=K, p=p, q=q, a_dist="bernoulli", scaled=True)
     data = inputs.make_case(case, 7300 + M + p)
     want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
-    c32, c16 = run_case(gpu, data, case, algo=DECODE)
-    assert np.array_equal(c32.astype(np.int64), want)
-    check_f16(c16, want, data, oracle)
+    for algo in (DECODE, DECODE_VALU) if M <= 16 else (DECODE,):
+        c32, c16 = run_case(gpu, data, case, algo=algo)
+        assert np.array_equal(c32.astype(np.int64), want)
+        check_f16(c16, want, data, oracle)
     c32, c16 = run_from_codes(gpu, data, case)
     assert np.array_equal(c32.astype(np.int64), want)
     check_f16(c16, want, data, oracle)
