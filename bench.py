@@ -485,6 +485,31 @@ def paper_shapes(args):
         print("| %s | %d | %d | %d | %.1f | %.1f | %.0f | %.1f |" % (name, M, N, K, us, ug, 2.0 * M * N * K / min(us, ug) / 1e6, paper),
               flush=True)
 
+    # Ablation for the claim of paper Sec. 4.2, all three schemes as kernels of this library (apmm_gemm_ex algo ids):
+    # the fused kernel (recovery moved in front of the multiplier), the planes as +-1 operands on the matrix unit with
+    # an accumulator per plane pair and shift-and-add in registers, and the scheme the paper argues against: one
+    # plane pair per workgroup, its 32-bit product to global memory, then a shift-and-add pass over those products.
+    print()
+    print("| scheme (4096^3, int32 out) | fused kernel (us) | planes on the matrix unit, recovery in registers (us) | "
+          "plane pairs to global memory + recovery pass (us) | naive / fused |")
+    print("|---|---|---|---|---|")
+    M = N = K = 4096
+    for (p, q) in ((1, 1), (2, 1), (2, 2)):
+        a = torch.randint(0, 1 << p, (M, K), dtype=torch.uint8, device=dev)
+        w = torch.randint(0, 1 << q, (N, K), dtype=torch.uint8, device=dev)
+        ap, wp = binding.apmm_pack_activations(a, p), binding.apmm_pack_weights(w, q)
+        c = torch.empty((M, N), dtype=torch.int32, device=dev)
+        ws = torch.empty(p * q * M * N * 4, dtype=torch.uint8, device=dev)
+        times = []
+        for algo, workspace in ((binding.ALGO_AUTO, None), (binding.ALGO_PLANES_REGISTERS, None),
+                                (binding.ALGO_PLANE_PAIRS_GLOBAL, ws)):
+            def gemm(i):
+                binding.apmm_gemm(M, N, K, p, q, ap, wp, c_i32=c, workspace=workspace, algo=algo)
+            times.append(graph_us_per_call(torch, gemm, 10))
+        print("| W%dA%d | %.1f | %.1f | %.1f | %.1fx |" % (q, p, times[0], times[1], times[2], times[2] / times[0]), flush=True)
+        del ws
+        torch.cuda.empty_cache()
+
 
 def main():
     args = parse_args()

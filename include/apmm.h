@@ -50,8 +50,16 @@ typedef enum {
                                     p not 3 or 4 otherwise (XOR + popcount) */
     APMM_ALGO_MFMA_FP4 = 4,      /* plane groups recombined to E2M1 codes in registers, f8f6f4 MFMA, exact fp32 accumulate
                                     (p, q <= 4 and 4 * roundup(K,512) * (2^p-1)(2^q-1) < 2^24) */
-    APMM_ALGO_DECODE_VALU = 5    /* the XOR + popcount small-M kernel whatever the widths (M <= 16, q <= 4, p not 3 or 4):
+    APMM_ALGO_DECODE_VALU = 5,   /* the XOR + popcount small-M kernel whatever the widths (M <= 16, q <= 4, p not 3 or 4):
                                     design B at decode shapes, for comparison */
+    /* Ablation for the claim of paper Sec. 4.2 (p <= 2, q <= 4, same K bound as APMM_ALGO_MFMA_FP4); planes as +-1
+       operands on the matrix unit: */
+    APMM_ALGO_PLANE_PAIRS_GLOBAL = 6, /* the scheme the paper argues against: one plane pair per workgroup, its 32-bit
+                                    product D_ij to global memory, then a pass that shifts and adds them into C.
+                                    Needs `workspace` of p * q * M * N * 4 bytes (16-byte aligned), else
+                                    APMM_ERR_WORKSPACE */
+    APMM_ALGO_PLANES_REGISTERS = 7 /* one tile per workgroup, an accumulator per plane pair, shift-and-add in registers
+                                    (the paper's recovery-oriented scheme) */
 } apmm_algo;
 
 /* Bytes of the packed form of a rows x K operand of `bits`-bit codes (paper Sec. 4.1:
@@ -112,7 +120,8 @@ apmm_status apmm_unpack_activations(const void *a_packed, int64_t M, int64_t K, 
  *              becomes an infinity of its sign, as IEEE 754 rounding has it), or NULL
  *   w_scale  : device, N binary16 per-output-channel scales, or NULL (= 1)
  *   a_scale  : device, M binary16 per-token scales, or NULL (= 1)
- *   workspace: device scratch of at least apmm_workspace_bytes() bytes (may be NULL if 0)
+ *   workspace: device scratch of at least apmm_workspace_bytes() bytes (may be NULL if 0; only
+ *              APMM_ALGO_PLANE_PAIRS_GLOBAL of apmm_gemm_ex uses one)
  * At least one of c_i32 / c_f16 must be non-NULL.  M == 0 or N == 0 returns APMM_OK
  * without a launch.  Returns APMM_ERR_OVERFLOW if roundup(K,512)*(2^p-1)*(2^q-1) > INT32_MAX. */
 apmm_status apmm_gemm(int64_t M, int64_t N, int64_t K, int p, int q,

@@ -159,14 +159,15 @@ apmm_status check_gemm(int64_t M, int64_t N, int64_t K, int p, int q, const void
 
 constexpr int kMaxProblems = 256;  // entries of one apmm_gemm_grouped call
 
-apmm_status run_gemm(const apmm::GemmArgs &g, int algo, hipStream_t s)
+apmm_status run_gemm(const apmm::GemmArgs &g, int algo, hipStream_t s, void *workspace = nullptr, size_t workspace_bytes = 0)
 {
     if (algo == APMM_ALGO_AUTO) {
         if (apmm::gemm_decode_supported(g)) algo = APMM_ALGO_DECODE;
         else if (apmm::gemm_mfma_fp4_supported(g)) algo = APMM_ALGO_MFMA_FP4;
         else algo = APMM_ALGO_VALU_POPCOUNT;
     }
-    if (algo == APMM_ALGO_VALU_POPCOUNT) (void)apmm::take_kernel_timing();  // that kernel takes no timing events
+    if (algo == APMM_ALGO_VALU_POPCOUNT || algo == APMM_ALGO_PLANE_PAIRS_GLOBAL || algo == APMM_ALGO_PLANES_REGISTERS)
+        (void)apmm::take_kernel_timing();  // those kernels take no timing events
     hipError_t e;
     switch (algo) {
     case APMM_ALGO_VALU_POPCOUNT:
@@ -180,6 +181,20 @@ apmm_status run_gemm(const apmm::GemmArgs &g, int algo, hipStream_t s)
         if (!apmm::gemm_decode_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: decode kernel does not cover this request");
         e = apmm::launch_gemm_decode(g, s);
         break;
+    case APMM_ALGO_PLANE_PAIRS_GLOBAL:
+    case APMM_ALGO_PLANES_REGISTERS: {
+        if (!apmm::gemm_ablation_supported(g))
+            return fail(APMM_ERR_UNSUPPORTED, "gemm: the plane kernels cover p <= 2, q <= 4 while 4 K (2^p - 1)(2^q - 1) < 2^24");
+        int32_t *pairs = nullptr;
+        if (algo == APMM_ALGO_PLANE_PAIRS_GLOBAL) {
+            if (!workspace || workspace_bytes < apmm::gemm_ablation_pairs_bytes(g))
+                return fail(APMM_ERR_WORKSPACE, "gemm: the plane-pair scheme needs a workspace of p * q * M * N * 4 bytes");
+            if (!aligned16(workspace)) return fail(APMM_ERR_INVALID_ARG, "gemm: workspace must be 16-byte aligned");
+            pairs = static_cast<int32_t *>(workspace);
+        }
+        e = apmm::launch_gemm_ablation(g, pairs, s);
+        break;
+    }
     case APMM_ALGO_DECODE_VALU:
         if (!apmm::gemm_decode_valu_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: the XOR/popcount small-M kernel does not cover this request");
         e = apmm::launch_gemm_decode_valu(g, s);
@@ -200,16 +215,14 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
                          const uint16_t *a_scale, void *workspace, size_t workspace_bytes, void *stream,
                          int algo)
 {
-    (void)workspace;
-    (void)workspace_bytes;
     if (algo != APMM_ALGO_AUTO && algo != APMM_ALGO_VALU_POPCOUNT && algo != APMM_ALGO_DECODE && algo != APMM_ALGO_MFMA_FP4 &&
-        algo != APMM_ALGO_DECODE_VALU)
+        algo != APMM_ALGO_DECODE_VALU && algo != APMM_ALGO_PLANE_PAIRS_GLOBAL && algo != APMM_ALGO_PLANES_REGISTERS)
         return fail(APMM_ERR_INVALID_ARG, "gemm: unknown algo");
     apmm::GemmArgs g;
     bool empty;
     const apmm_status st = check_gemm(M, N, K, p, q, a_packed, w_packed, c_i32, c_f16, w_scale, a_scale, g, empty);
     if (st != APMM_OK || empty) return st;
-    return run_gemm(g, algo, static_cast<hipStream_t>(stream));
+    return run_gemm(g, algo, static_cast<hipStream_t>(stream), workspace, workspace_bytes);
 }
 
 apmm_status apmm_gemm_from_codes(int64_t M, int64_t N, int64_t K, int p, int q, const uint8_t *a_codes,

@@ -23,6 +23,13 @@ hipError_t launch_gemm_valu(const GemmArgs &args, hipStream_t stream);
 bool gemm_mfma_fp4_supported(const GemmArgs &args);
 hipError_t launch_gemm_mfma_fp4(const GemmArgs &args, hipStream_t stream);
 
+// Ablation kernels for the claim of paper Sec. 4.2 (apmm_gemm_ablation.hip): the planes as +-1 operands on the
+// matrix unit.  pairs != nullptr: every plane pair's product to global memory (p q M N int32 at `pairs`), then a
+// recovery pass; pairs == nullptr: one tile per workgroup, recovery in registers.
+bool gemm_ablation_supported(const GemmArgs &args);
+size_t gemm_ablation_pairs_bytes(const GemmArgs &args);
+hipError_t launch_gemm_ablation(const GemmArgs &args, int32_t *pairs, hipStream_t stream);
+
 // Measurement aid: a pair of events that the next GEMM launch of the calling thread (large-tile MFMA kernel or
 // small-M kernels) attaches to its kernel dispatch (hipExtLaunchKernel), so that they hold the kernel's own
 // begin and end.

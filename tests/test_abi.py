@@ -72,7 +72,7 @@ def test_argument_errors_come_before_any_launch(lib):
     assert _gemm(lib, 4, 4, 128, 1, 1, a=None) == INVALID
     assert _gemm(lib, 4, 4, 128, 1, 1, c=None) == INVALID          # no output requested
     assert _gemm(lib, 4, 4, 128, 1, 1, a=0x1004) == INVALID         # misaligned packed operand
-    assert _gemm(lib, 4, 4, 128, 1, 1, algo=7) == INVALID
+    assert _gemm(lib, 4, 4, 128, 1, 1, algo=9) == INVALID
     assert _gemm(lib, 64, 64, 128, 5, 1, algo=4) == UNSUPPORTED     # E2M1 path: p, q <= 4 ...
     assert _gemm(lib, 64, 64, 128, 2, 6, algo=4) == UNSUPPORTED
     assert _gemm(lib, 64, 64, 32768, 4, 4, algo=4) == UNSUPPORTED   # ... and 4 K (2^p-1)(2^q-1) < 2^24
@@ -82,6 +82,8 @@ def test_argument_errors_come_before_any_launch(lib):
     assert _gemm(lib, 4, 4, 32769, 8, 8) == OVERFLOW
     assert _gemm(lib, 4, 4, 40000, 8, 8) == OVERFLOW
     assert _gemm(lib, 64, 64, 128, 2, 2, algo=2) == INVALID         # an id no kernel of this build has
+    assert _gemm(lib, 64, 64, 128, 4, 2, algo=7) == UNSUPPORTED     # plane kernels: activations of 1 or 2 bits
+    assert _gemm(lib, 64, 64, 128, 2, 2, algo=6) == 4               # plane pairs to global memory: workspace missing
     assert lib.apmm_status_string(OVERFLOW) == b"result exceeds 32 bits"
     assert lib.apmm_pack_weights(None, 4, 128, 2, None, None) == INVALID
     assert lib.apmm_pack_activations(0x1000, 4, 128, 0, 0x2000, None) == INVALID

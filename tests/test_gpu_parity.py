@@ -132,6 +132,43 @@ def test_all_precisions_several_tiles_ragged(gpu, oracle, p, q):
             check_f16(c16, want, data, oracle)
 
 
+@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (2, 2), (1, 3), (2, 4), (1, 2)])
+def test_ablation_plane_schemes(gpu, oracle, p, q):
+    """Sec. 4.2 ablation kernels through apmm_gemm_ex: every plane pair's product to global memory plus a recovery
+    pass (algo 6, with its workspace), and the planes on the matrix unit with shift-and-add in registers (algo 7);
+    several tiles, ragged M, N and K, int32 and fp16 outputs against the oracle."""
+    torch, binding = gpu
+    for (M, N, K) in [(150, 300, 384), (300, 520, 130), (70, 45, 1100), (256, 128, 512)]:
+        case = dict(M=M, N=N, K=K, p=p, q=q, a_dist="bernoulli", scaled=True)
+        data = inputs.make_case(case, 1500 + 17 * p + q)
+        want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+        dev = torch.device("cuda:0")
+        ap = binding.apmm_pack_activations(torch.from_numpy(data["a_codes"]).to(dev), p)
+        wp = binding.apmm_pack_weights(torch.from_numpy(data["w_codes"]).to(dev), q)
+        sa, sw = torch.from_numpy(data["a_scale"]).to(dev), torch.from_numpy(data["w_scale"]).to(dev)
+        ws = torch.empty(p * q * M * N * 4, dtype=torch.uint8, device=dev)
+        for algo, workspace in ((binding.ALGO_PLANE_PAIRS_GLOBAL, ws), (binding.ALGO_PLANES_REGISTERS, None)):
+            c32, c16 = binding.apmm_gemm(M, N, K, p, q, ap, wp, want_i32=True, want_f16=True, w_scale=sw, a_scale=sa,
+                                         workspace=workspace, algo=algo)
+            torch.cuda.synchronize()
+            assert np.array_equal(c32.cpu().numpy().astype(np.int64), want), (algo, M, N, K)
+            check_f16(c16.cpu().numpy(), want, data, oracle)
+        with pytest.raises(binding.ApmmError) as err:                      # the naive scheme without its workspace
+            binding.apmm_gemm(M, N, K, p, q, ap, wp, algo=binding.ALGO_PLANE_PAIRS_GLOBAL, workspace=ws[:-16])
+        assert err.value.status == 4
+
+
+def test_ablation_kernels_decline_wide_activations(gpu):
+    torch, binding = gpu
+    dev = torch.device("cuda:0")
+    a = torch.zeros((64, 256), dtype=torch.uint8, device=dev)
+    ap, wp = binding.apmm_pack_activations(a, 4), binding.apmm_pack_weights(a, 2)
+    for algo in (binding.ALGO_PLANE_PAIRS_GLOBAL, binding.ALGO_PLANES_REGISTERS):
+        with pytest.raises(binding.ApmmError) as err:
+            binding.apmm_gemm(64, 64, 256, 4, 2, ap, wp, algo=algo)
+        assert err.value.status == 2
+
+
 @pytest.mark.parametrize("p,q", [(8, 8), (5, 7), (8, 1), (1, 6), (7, 3)])
 def test_wide_codes(gpu, oracle, p, q):
     case = dict(M=37, N=50, K=333, p=p, q=q, a_dist="bernoulli", scaled=False)
