@@ -74,6 +74,9 @@ def parse_args():
     ap.add_argument("--all-configs", action="store_true", help="time every workload configuration (markdown)")
     ap.add_argument("--configs", default="1,2,3,4,5", help="with --all-configs: which configurations")
     ap.add_argument("--paper-shapes", action="store_true", help="the paper's table shapes and the ablation (markdown)")
+    ap.add_argument("--decode-designs", action="store_true",
+                    help="the decode shape (M = 1, 11008 x 4096, W2A2, packed activations, cold weights) on both designs: "
+                         "matrix-unit small-M kernel and XOR/popcount small-M kernel (one JSON line)")
     return ap.parse_args()
 
 
@@ -178,6 +181,46 @@ def decode_leg(torch, binding, inputs):
     }
 
 
+def decode_designs(args):
+    """Design A against design B at the decode shape: apmm_gemm_ex with the two small-M algo ids on the same packed
+    operands, each walking over more than 512 MiB of packed weight copies; kernel time from events on the dispatch."""
+    import torch
+    from paper_2409_17870_amd import binding, inputs
+    dev = torch.device("cuda:0")
+    M, N, K, p, q = 1, 11008, 4096, 2, 2
+    case = dict(M=M, N=N, K=K, p=p, q=q, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, inputs.BASE_SEED + 3)
+    ap = binding.apmm_pack_activations(torch.from_numpy(data["a_codes"]).to(dev), p)
+    sa, sw = torch.from_numpy(data["a_scale"]).to(dev), torch.from_numpy(data["w_scale"]).to(dev)
+    wp0 = binding.apmm_pack_weights(torch.from_numpy(data["w_codes"]).to(dev), q)
+    w_bytes = N * K * q / 8.0
+    copies = int((512 << 20) // w_bytes) + 2
+    wps = [wp0] + [wp0.clone() for _ in range(copies - 1)]
+    h = torch.empty((M, N), dtype=torch.float16, device=dev)
+    nbytes = w_bytes + M * K * p / 8.0 + 2.0 * M * N + 2.0 * (M + N)
+    out = {"workload": "decode W2A2 M=1 N=11008 K=4096, packed activations, fp16 scale epilogue, %d packed weight copies "
+                       "in rotation" % copies, "algorithmic_bytes": nbytes, "designs": {}}
+    for name, algo in (("A: E2M1 MFMA 16x16x128", binding.ALGO_DECODE), ("B: XOR + popcount", binding.ALGO_DECODE_VALU)):
+        def call(i):
+            binding.apmm_gemm(M, N, K, p, q, ap, wps[i % copies], want_i32=False, want_f16=True, w_scale=sw, a_scale=sa,
+                              c_f16=h, algo=algo)
+        us_graph = graph_us_per_call(torch, call, copies)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(2 * copies)]
+        for e0, e1 in evs:
+            e0.record()
+            e1.record()
+        torch.cuda.synchronize()
+        for i, (e0, e1) in enumerate(evs):
+            binding.apmm_time_next_gemm(e0, e1)
+            call(i)
+        torch.cuda.synchronize()
+        k_us = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in evs[copies:])
+        out["designs"][name] = {"kernel": binding.apmm_last_gemm_kernel(), "us_per_call_in_graph": us_graph,
+                                "kernel_us_median": k_us[len(k_us) // 2], "GB/s": nbytes / us_graph / 1e3,
+                                "frac_of_hbm_peak": nbytes / us_graph / 1e3 / HBM_PEAK_GBS}
+    print(json.dumps(out))
+
+
 def headline(args):
     import torch
     from paper_2409_17870_amd import binding, inputs
@@ -246,6 +289,12 @@ def headline(args):
     mfma = kernel.startswith("gemm_mfma_direct_kernel")
     operand = "fp4" if mfma else "int8"
     traffic, traffic_source = profiled_traffic(kernel)
+    if mfma:
+        bound, peak = "mfma", PEAK[operand]
+    else:
+        # XOR/popcount kernel: one XOR, one popcount and one shift-and-add per output, plane pair and 16 elements on
+        # the vector ALU: 256 CUs x 64 lanes x 2.4 GHz integer operations per second
+        bound, peak = "alu", 2.0 * 16 / (3.0 * p * q) * 256 * 64 * 2.4e9 / 1e12
     out = {
         "metric": "effective TOPS (2*M*N*K/s), W1A2 bipolar-INT GEMM 4096^3 (activation pack + GEMM); "
                   "GB/s at M=1 decode in `decode`",
@@ -262,9 +311,9 @@ def headline(args):
                    "M": M, "N": N, "K": K, "weight_bits": q, "activation_bits": p,
                    "step": "apmm_pack_activations + apmm_gemm, weights pre-packed", "algo": args.algo},
         "gemm_ms": gemm_ms, "pack_ms": ms_per_step - gemm_ms,
-        "roofline": {"bound": "mfma", "kernel": kernel,
-                     "achieved": achieved, "peak": PEAK[operand], "unit": "TOP/s",
-                     "frac": achieved / PEAK[operand],
+        "roofline": {"bound": bound, "kernel": kernel,
+                     "achieved": achieved, "peak": peak, "unit": "TOP/s",
+                     "frac": achieved / peak,
                      "frac_of_int8_peak": achieved / PEAK["int8"],
                      "launches_timed": len(brackets),
                      "traffic": traffic, "traffic_source": traffic_source},
@@ -527,6 +576,8 @@ def main():
         all_configs(args)
     elif args.paper_shapes:
         paper_shapes(args)
+    elif args.decode_designs:
+        decode_designs(args)
     else:
         headline(args)
 

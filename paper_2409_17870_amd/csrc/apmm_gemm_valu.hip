@@ -7,12 +7,14 @@
 // popcounts and the true K appears in the constant.  The recovery (shift and add) is done
 // in registers; nothing but C touches global memory.
 //
-// This kernel is the general one: any p, q in 1..8, any M, N, K.  One thread per output
-// element, 16 x 16 outputs per workgroup; operands come straight from the packed tiles
-// (they are small and stay in L1/L2).  It is the fallback for codes the matrix-unit kernels do
-// not cover, written for clarity: every plane is brought to the same form, 16 elements per word
-// at the even bit positions (apmm_layout.h), and then any activation plane can be XOR-ed with any
-// weight plane.
+// This kernel is the general one: any p, q in 1..8, any M, N, K.  It is the fallback for codes the
+// matrix-unit kernels do not cover and the reference for design B at large M.  A workgroup of 256 threads
+// owns 64 x 64 outputs, a thread 4 x 4 of them (rows ty + 16 i, columns tx + 16 j).  Per k block the
+// workgroup brings every plane of its 64 + 64 rows to the same form, 16 elements per word at the even bit
+// positions (apmm_layout.h), once, into LDS; then any activation plane can be XOR-ed with any weight plane:
+// per output, plane pair and word one XOR, one popcount and one shift-and-add.  The vector ALU bounds it:
+// 3 p q operations per output and 16 elements, i.e. about 0.2 effective POP/s for W1A2 if every issue slot
+// of the chip did nothing else.
 #include "apmm_epilogue.h"
 #include "apmm_kernels.h"
 
@@ -51,44 +53,83 @@ __device__ __forceinline__ uint32_t field_plane_half_word(const uint32_t *tile_r
     return out;
 }
 
+constexpr int kOutTile = 64;                 // outputs per workgroup and dimension
+constexpr int kPerThread = kOutTile / kTile;  // outputs per thread and dimension
+
 __global__ __launch_bounds__(kTile * kTile) void gemm_valu_kernel(GemmArgs g, int64_t tiles_n)
 {
-    // one-dimensional grid (the y dimension would cap M at about a million rows)
-    const int64_t n = ((int64_t)blockIdx.x % tiles_n) * kTile + threadIdx.x;
-    const int64_t m = ((int64_t)blockIdx.x / tiles_n) * kTile + threadIdx.y;
-    if (m >= g.M || n >= g.N) return;
+    // one-dimensional grid (the y dimension would cap M at about four million rows)
+    const int64_t n0 = ((int64_t)blockIdx.x % tiles_n) * kOutTile, m0 = ((int64_t)blockIdx.x / tiles_n) * kOutTile;
+    const int tid = threadIdx.x, tx = tid % kTile, ty = tid / kTile;
     const int p = g.p, q = g.q;
+    const int64_t rows_a = round_up(g.M, kRowBlock), rows_b = round_up(g.N, kRowBlock);
+    // plane words of one k block: [plane][word 0..7][row 0..63]; consecutive lanes read consecutive rows
+    __shared__ uint32_t a_lds[8 * 8 * kOutTile], w_lds[8 * 8 * kOutTile];
 
-    uint32_t weighted = 0;  // sum_ij 2^(i+j) popcount, modulo 2^32 (the true C fits 32 bits)
+    uint32_t weighted[kPerThread][kPerThread];  // sum_ij 2^(i+j) popcount, modulo 2^32 (the true C fits 32 bits)
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i)
+#pragma unroll
+        for (int j = 0; j < kPerThread; ++j) weighted[i][j] = 0;
+
     for (int64_t kb = 0; kb < g.nkb; ++kb) {
-        const uint32_t *arow = g.a + tile_row_word(m, kb, g.nkb, activation_slots(p), 0);
-        const uint32_t *wrow = g.w + tile_row_word(n, kb, g.nkb, q, 0);
+        if (kb) __syncthreads();  // every thread is done with the previous k block
+        // fill: one word of one plane of one row per job; rows past the operand read its last padded row
+        for (int job = tid; job < (p + q) * 8 * kOutTile; job += kTile * kTile) {
+            const int r = job % kOutTile, w = (job / kOutTile) % 8, plane = job / (8 * kOutTile);
+            if (plane < p) {
+                int64_t row = m0 + r;
+                if (row >= rows_a) row = rows_a - 1;
+                const uint32_t *arow = g.a + tile_row_word(row, kb, g.nkb, activation_slots(p), 0);
+                a_lds[(plane * 8 + w) * kOutTile + r] =
+                    activation_field_form(p) ? field_plane_half_word(arow, plane, w) : plane_half_word(arow, p, plane, w);
+            } else {
+                int64_t row = n0 + r;
+                if (row >= rows_b) row = rows_b - 1;
+                const uint32_t *wrow = g.w + tile_row_word(row, kb, g.nkb, q, 0);
+                w_lds[((plane - p) * 8 + w) * kOutTile + r] = plane_half_word(wrow, q, plane - p, w);
+            }
+        }
+        __syncthreads();
         for (int w = 0; w < 8; ++w) {
-            uint32_t wp[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) wp[i] = i < q ? plane_half_word(wrow, q, i, w) : 0u;
             for (int j = 0; j < p; ++j) {
-                const uint32_t ap = activation_field_form(p) ? field_plane_half_word(arow, j, w)
-                                                              : plane_half_word(arow, p, j, w);
+                uint32_t av[kPerThread];
 #pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    if (i < q) weighted += (uint32_t)__popc(ap ^ wp[i]) << (i + j);
+                for (int i = 0; i < kPerThread; ++i) av[i] = a_lds[(j * 8 + w) * kOutTile + ty + kTile * i];
+                for (int i = 0; i < q; ++i) {
+#pragma unroll
+                    for (int jn = 0; jn < kPerThread; ++jn) {
+                        const uint32_t wv = w_lds[(i * 8 + w) * kOutTile + tx + kTile * jn];
+#pragma unroll
+                        for (int im = 0; im < kPerThread; ++im)
+                            weighted[im][jn] += (uint32_t)__popc(av[im] ^ wv) << (i + j);
+                    }
+                }
             }
         }
     }
     const uint32_t full = (uint32_t)g.K * (uint32_t)((1 << p) - 1) * (uint32_t)((1 << q) - 1);
-    const int32_t c = (int32_t)(full - 2u * weighted);
-    store_output(g, m, n, c, load_scale(g.a_scale, m), load_scale(g.w_scale, n));
+#pragma unroll
+    for (int im = 0; im < kPerThread; ++im) {
+        const int64_t m = m0 + ty + kTile * im;
+        if (m >= g.M) continue;
+        const float sa = load_scale(g.a_scale, m);
+#pragma unroll
+        for (int jn = 0; jn < kPerThread; ++jn) {
+            const int64_t n = n0 + tx + kTile * jn;
+            if (n < g.N) store_output(g, m, n, (int32_t)(full - 2u * weighted[im][jn]), sa, load_scale(g.w_scale, n));
+        }
+    }
 }
 
 }  // namespace
 
 hipError_t launch_gemm_valu(const GemmArgs &args, hipStream_t stream)
 {
-    const int64_t gx = (args.N + kTile - 1) / kTile, gy = (args.M + kTile - 1) / kTile;
+    const int64_t gx = (args.N + kOutTile - 1) / kOutTile, gy = (args.M + kOutTile - 1) / kOutTile;
     if (gx > 0x7fffffffLL / gy) return hipErrorInvalidValue;
     note_kernel("gemm_valu_kernel");
-    hipLaunchKernelGGL(gemm_valu_kernel, dim3((unsigned)(gx * gy)), dim3(kTile, kTile), 0, stream, args, gx);
+    hipLaunchKernelGGL(gemm_valu_kernel, dim3((unsigned)(gx * gy)), dim3(kTile * kTile), 0, stream, args, gx);
     return hipGetLastError();
 }
 
