@@ -65,9 +65,22 @@ constexpr int split_store_stages(int wm, int wn, int split)
     return split == 1 ? 0 : split_rows(wm, split, 0) * wn * 16 / (4 * split_rows(wm, split, 1) * wn / split_store_every(split));
 }
 
+// The arguments are plain scalars and pointers, the ones the first addresses depend on first: this file is built
+// with kernel-argument preloading, so the first 14 dwords are in scalar registers when a wave starts and the
+// prologue's first loads go out without a round trip to memory for the arguments.
 template <int P, int Q, int WM, int WN, int SPLIT>
-__global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g, int tiles_n, int tiles_total)
+__global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(const uint32_t *a_arg, const uint32_t *w_arg, int32_t *ci_arg,
+                                                               uint16_t *cf_arg, int m_arg, int n_arg, int k_arg, int nkb_arg,
+                                                               int tiles_n, int tiles_total, const uint16_t *ws_arg,
+                                                               const uint16_t *as_arg)
 {
+    GemmArgs g;
+    g.M = m_arg; g.N = n_arg; g.K = k_arg; g.nkb = nkb_arg;
+    g.p = P; g.q = Q;
+    g.a = a_arg; g.a_codes = nullptr; g.w = w_arg;
+    g.a_sum = reinterpret_cast<const int32_t *>(a_arg + row_sum_word(round_up(m_arg, kRowBlock), nkb_arg, activation_slots(P)));
+    g.w_sum = reinterpret_cast<const int32_t *>(w_arg + row_sum_word(round_up(n_arg, kRowBlock), nkb_arg, Q));
+    g.c_i32 = ci_arg; g.c_f16 = cf_arg; g.w_scale = ws_arg; g.a_scale = as_arg;
     static_assert(P >= 1 && P <= 4 && Q >= 1 && Q <= 4, "instantiated for codes of up to four bits");
     static_assert(SPLIT >= 1 && SPLIT <= 3, "one phase, two even phases, or two uneven phases");
     static_assert(SPLIT == 1 || WM % 2 == 0, "the row blocks of a wave are cut in two");
@@ -529,15 +542,17 @@ hipError_t launch_direct_variant(const GemmArgs &g, hipStream_t stream)
     constexpr int BM = 32 * WM * waves_m(WM), BN = 32 * WN * waves_n(WM);
     const int64_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int64_t tiles = tiles_m * tiles_n;
-    if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (tiles > 0x7fffffffLL || g.M > 0x7fffffffLL || g.N > 0x7fffffffLL || g.K > 0x7fffffffLL) return hipErrorInvalidValue;
     const KernelTiming timing = take_kernel_timing();
     note_kernel("gemm_mfma_direct_kernel<%d,%d,%d,%d,%d>", P, Q, WM, WN, SPLIT);
     if (timing.start || timing.stop)
         hipExtLaunchKernelGGL((gemm_mfma_direct_kernel<P, Q, WM, WN, SPLIT>), dim3((unsigned)tiles), dim3(256), 0,
-                              stream, timing.start, timing.stop, 0, g, (int)tiles_n, (int)tiles);
+                              stream, timing.start, timing.stop, 0, g.a, g.w, g.c_i32, g.c_f16, (int)g.M, (int)g.N, (int)g.K,
+                              (int)g.nkb, (int)tiles_n, (int)tiles, g.w_scale, g.a_scale);
     else
         hipLaunchKernelGGL((gemm_mfma_direct_kernel<P, Q, WM, WN, SPLIT>), dim3((unsigned)tiles), dim3(256), 0,
-                           stream, g, (int)tiles_n, (int)tiles);
+                           stream, g.a, g.w, g.c_i32, g.c_f16, (int)g.M, (int)g.N, (int)g.K, (int)g.nkb, (int)tiles_n,
+                           (int)tiles, g.w_scale, g.a_scale);
     return hipGetLastError();
 }
 
