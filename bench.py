@@ -77,6 +77,9 @@ def parse_args():
     ap.add_argument("--decode-designs", action="store_true",
                     help="the decode shape (M = 1, 11008 x 4096, W2A2, packed activations, cold weights) on both designs: "
                          "matrix-unit small-M kernel and XOR/popcount small-M kernel (one JSON line)")
+    ap.add_argument("--decode-layer", action="store_true",
+                    help="the seven linears of a Llama-2-7B decoder layer at 1, 8 and 16 tokens (W2A2, fp16 epilogue, cold "
+                         "weights): seven calls, and one grouped launch of seven independent problems (markdown)")
     return ap.parse_args()
 
 
@@ -219,6 +222,52 @@ def decode_designs(args):
                                 "kernel_us_median": k_us[len(k_us) // 2], "GB/s": nbytes / us_graph / 1e3,
                                 "frac_of_hbm_peak": nbytes / us_graph / 1e3 / HBM_PEAK_GBS}
     print(json.dumps(out))
+
+
+def decode_layer(args):
+    """Grouped launch (apmm_gemm_grouped) against one call per linear, weights of 14 layers in rotation (672 MiB)."""
+    import torch
+    from paper_2409_17870_amd import binding
+    dev = torch.device("cuda:0")
+    p = q = 2
+    H, F = 4096, 11008
+    shapes = [("q", H, H), ("k", H, H), ("v", H, H), ("o", H, H), ("gate", F, H), ("up", F, H), ("down", H, F)]
+    layers = 14
+    weights = [{n: binding.apmm_pack_weights(torch.randint(0, 4, (N, K), dtype=torch.uint8, device=dev), q)
+                for (n, N, K) in shapes} for _ in range(layers)]
+    w_bytes = sum(N * K * q / 8.0 for (_, N, K) in shapes)
+    print("| tokens | seven calls from codes (us per layer) | one grouped launch, packed activations (us) | one grouped "
+          "launch from codes (us) | grouped: GB/s of weights | of the HBM peak |")
+    print("|---|---|---|---|---|---|")
+    for M in (1, 8, 16):
+        x = {H: torch.randint(0, 4, (M, H), dtype=torch.uint8, device=dev),
+             F: torch.randint(0, 4, (M, F), dtype=torch.uint8, device=dev)}
+        xp = {K: binding.apmm_pack_activations(x[K], p) for K in x}
+        sa = (torch.rand(M, device=dev) * 0.09 + 0.01).half()
+        sw = {n: (torch.rand(N, device=dev) * 0.09 + 0.01).half() for (n, N, K) in shapes}
+        out = {n: torch.empty((M, N), dtype=torch.float16, device=dev) for (n, N, K) in shapes}
+
+        def calls(i):
+            for (n, N, K) in shapes:
+                binding.apmm_gemm_from_codes(x[K], N, p, q, weights[i % layers][n], want_i32=False, want_f16=True,
+                                             w_scale=sw[n], a_scale=sa, c_f16=out[n])
+
+        def grouped(codes):
+            def f(i):
+                probs = []
+                for (n, N, K) in shapes:
+                    d = dict(M=M, N=N, K=K, w_packed=weights[i % layers][n], c_f16=out[n], w_scale=sw[n], a_scale=sa)
+                    d["a_codes" if codes else "a_packed"] = x[K] if codes else xp[K]
+                    probs.append(d)
+                binding.apmm_gemm_grouped(probs, p, q)
+            return f
+
+        t_calls = graph_us_per_call(torch, calls, layers)
+        t_packed = graph_us_per_call(torch, grouped(False), layers)
+        t_codes = graph_us_per_call(torch, grouped(True), layers)
+        best = min(t_packed, t_codes)
+        print("| %d | %.1f | %.1f | %.1f | %.0f | %.0f %% |" % (M, t_calls, t_packed, t_codes, w_bytes / best / 1e3,
+                                                             100.0 * w_bytes / best / 1e3 / HBM_PEAK_GBS), flush=True)
 
 
 def headline(args):
@@ -578,6 +627,8 @@ def main():
         paper_shapes(args)
     elif args.decode_designs:
         decode_designs(args)
+    elif args.decode_layer:
+        decode_layer(args)
     else:
         headline(args)
 
