@@ -58,8 +58,11 @@ typedef enum {
                                     product D_ij to global memory, then a pass that shifts and adds them into C.
                                     Needs `workspace` of p * q * M * N * 4 bytes (16-byte aligned), else
                                     APMM_ERR_WORKSPACE */
-    APMM_ALGO_PLANES_REGISTERS = 7 /* one tile per workgroup, an accumulator per plane pair, shift-and-add in registers
+    APMM_ALGO_PLANES_REGISTERS = 7, /* one tile per workgroup, an accumulator per plane pair, shift-and-add in registers
                                     (the paper's recovery-oriented scheme) */
+    APMM_ALGO_MFMA_KSPLIT = 8    /* APMM_ALGO_MFMA_FP4 with the K partition of paper Sec. 4.2 taken across the four waves of
+                                    a workgroup as well: every wave holds the whole workgroup tile for a quarter of K, the
+                                    partial tiles are added in LDS (p = 3 or 4; chosen by AUTO for outputs of few tiles) */
 } apmm_algo;
 
 /* Bytes of the packed form of a rows x K operand of `bits`-bit codes (paper Sec. 4.1:

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libapmm.so")
 
 ALGO_AUTO, ALGO_VALU_POPCOUNT, ALGO_DECODE, ALGO_MFMA_FP4, ALGO_DECODE_VALU = 0, 1, 3, 4, 5
-ALGO_PLANE_PAIRS_GLOBAL, ALGO_PLANES_REGISTERS = 6, 7
+ALGO_PLANE_PAIRS_GLOBAL, ALGO_PLANES_REGISTERS, ALGO_MFMA_KSPLIT = 6, 7, 8
 
 EXPORTS = [
     "apmm_packed_bytes", "apmm_packed_activation_bytes", "apmm_workspace_bytes", "apmm_pack_weights", "apmm_pack_activations",

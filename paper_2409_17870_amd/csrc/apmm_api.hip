@@ -177,6 +177,10 @@ apmm_status run_gemm(const apmm::GemmArgs &g, int algo, hipStream_t s, void *wor
         if (!apmm::gemm_mfma_fp4_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: FP4 MFMA kernel covers p, q in 1..4 while 4 K (2^p - 1)(2^q - 1) < 2^24");
         e = apmm::launch_gemm_mfma_fp4(g, s);
         break;
+    case APMM_ALGO_MFMA_KSPLIT:
+        if (!apmm::gemm_mfma_ksplit_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: the K-split MFMA kernel covers p = 3, 4 and q in 1..4 while 4 K (2^p - 1)(2^q - 1) < 2^24");
+        e = apmm::launch_gemm_mfma_ksplit(g, s);
+        break;
     case APMM_ALGO_DECODE:
         if (!apmm::gemm_decode_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: decode kernel does not cover this request");
         e = apmm::launch_gemm_decode(g, s);
@@ -216,7 +220,8 @@ apmm_status apmm_gemm_ex(int64_t M, int64_t N, int64_t K, int p, int q, const vo
                          int algo)
 {
     if (algo != APMM_ALGO_AUTO && algo != APMM_ALGO_VALU_POPCOUNT && algo != APMM_ALGO_DECODE && algo != APMM_ALGO_MFMA_FP4 &&
-        algo != APMM_ALGO_DECODE_VALU && algo != APMM_ALGO_PLANE_PAIRS_GLOBAL && algo != APMM_ALGO_PLANES_REGISTERS)
+        algo != APMM_ALGO_DECODE_VALU && algo != APMM_ALGO_PLANE_PAIRS_GLOBAL && algo != APMM_ALGO_PLANES_REGISTERS &&
+        algo != APMM_ALGO_MFMA_KSPLIT)
         return fail(APMM_ERR_INVALID_ARG, "gemm: unknown algo");
     apmm::GemmArgs g;
     bool empty;

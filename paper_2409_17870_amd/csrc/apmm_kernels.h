@@ -23,6 +23,12 @@ hipError_t launch_gemm_valu(const GemmArgs &args, hipStream_t stream);
 bool gemm_mfma_fp4_supported(const GemmArgs &args);
 hipError_t launch_gemm_mfma_fp4(const GemmArgs &args, hipStream_t stream);
 
+// Design A with K split across the four waves of a workgroup (apmm_gemm_mfma_ksplit.h): for outputs of few large
+// tiles; activations in the field form (p = 3, 4), same exactness bound as above.
+bool gemm_mfma_ksplit_supported(const GemmArgs &args);
+bool gemm_mfma_ksplit_pays(const GemmArgs &args);  // the launch rule of launch_gemm_mfma_fp4 takes it for these
+hipError_t launch_gemm_mfma_ksplit(const GemmArgs &args, hipStream_t stream);
+
 // Ablation kernels for the claim of paper Sec. 4.2 (apmm_gemm_ablation.hip): the planes as +-1 operands on the
 // matrix unit.  pairs != nullptr: every plane pair's product to global memory (p q M N int32 at `pairs`), then a
 // recovery pass; pairs == nullptr: one tile per workgroup, recovery in registers.

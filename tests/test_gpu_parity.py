@@ -12,7 +12,7 @@ from paper_2409_17870_amd import inputs
 
 pytestmark = pytest.mark.gpu
 
-VALU, DECODE, FP4, DECODE_VALU = 1, 3, 4, 5
+VALU, DECODE, FP4, DECODE_VALU, KSPLIT = 1, 3, 4, 5, 8
 
 
 @pytest.fixture(scope="module")
@@ -667,6 +667,46 @@ def test_field_form_tile_arrangements(gpu, oracle, p, q, M, N, K):
     against the oracle."""
     case = dict(M=M, N=N, K=K, p=p, q=q, a_dist="normal" if p == 4 else "bernoulli", scaled=True)
     full_check(gpu, oracle, case, 7300 + 10 * p + q + M)
+
+
+@pytest.mark.parametrize("p,q", [(p, q) for p in (3, 4) for q in range(1, 5)])
+def test_k_split_across_waves_all_widths(gpu, oracle, p, q):
+    """The matrix-unit kernel whose four waves split K, asked for by its algo id: several tiles, ragged M, N and K,
+    K short enough that some waves get no stage, both outputs."""
+    for M, N, K in ((70, 170, 600), (130, 333, 1100 + 512 * q), (64, 160, 100)):
+        case = dict(M=M, N=N, K=K, p=p, q=q, a_dist="bernoulli", scaled=True)
+        data = inputs.make_case(case, 8100 + 16 * p + q + M)
+        want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+        c32, c16 = run_case(gpu, data, case, algo=KSPLIT, want_i32=True, want_f16=True)
+        assert np.array_equal(c32.astype(np.int64), want)
+        check_f16(c16, want, data, oracle)
+
+
+@pytest.mark.parametrize("M,N,K,want_i32,want_f16,scaled", [(512, 5120, 10240, False, True, True), (448, 1000, 12800, True, False, False),
+                                                            (200, 5001, 10300, True, True, True), (512, 6000, 10240, False, True, True),
+                                                            (512, 4096, 4096, True, True, True)])
+def test_k_split_across_waves_full_tiles(gpu, oracle, M, N, K, want_i32, want_f16, scaled):
+    """Shapes of one round of tiles and long K, where the launch rule itself takes the K-split kernel (the last
+    one by its algo id), one output or both, interior and border tiles, an odd output width, each of the three tile widths;
+    every output against the oracle."""
+    from paper_2409_17870_amd import binding
+    case = dict(M=M, N=N, K=K, p=4, q=2, a_dist="normal", scaled=scaled)
+    data = inputs.make_case(case, 8200 + M)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], 4, 2)
+    c32, c16 = run_case(gpu, data, case, algo=KSPLIT if K < 10240 else 0, want_i32=want_i32, want_f16=want_f16)
+    assert binding.apmm_last_gemm_kernel().startswith("gemm_mfma_ksplit_kernel")
+    if want_i32:
+        assert np.array_equal(c32.astype(np.int64), want)
+    if want_f16:
+        check_f16(c16, want, data, oracle)
+
+
+def test_k_split_kernel_declines_group_form_activations(gpu):
+    torch, binding = gpu
+    a = torch.zeros((64, 512), dtype=torch.uint8, device="cuda:0")
+    w = torch.zeros((64, 512), dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(binding.ApmmError):
+        binding.apmm_gemm(64, 64, 512, 2, 2, binding.apmm_pack_activations(a, 2), binding.apmm_pack_weights(w, 2), algo=KSPLIT)
 
 
 def test_config2_square_4096_w1a2(gpu, oracle):
