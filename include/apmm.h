@@ -49,7 +49,8 @@ typedef enum {
     APMM_ALGO_DECODE = 3,        /* small-M weight-streaming kernels: M <= 64 for p, q <= 2 (matrix unit), M <= 16 with q <= 4 and
                                     p not 3 or 4 otherwise (XOR + popcount) */
     APMM_ALGO_MFMA_FP4 = 4,      /* plane groups recombined to E2M1 codes in registers, f8f6f4 MFMA, exact fp32 accumulate
-                                    (p, q <= 4 and 4 * roundup(K,512) * (2^p-1)(2^q-1) < 2^24) */
+                                    (p, q <= 4 and 4 * roundup(K,512) * (2^p-1)(2^q-1) < 2^24); the large-tile kernel, every
+                                    wave sweeping all of K */
     APMM_ALGO_DECODE_VALU = 5,   /* the XOR + popcount small-M kernel whatever the widths (M <= 16, q <= 4, p not 3 or 4):
                                     design B at decode shapes, for comparison */
     /* Ablation for the claim of paper Sec. 4.2 (p <= 2, q <= 4, same K bound as APMM_ALGO_MFMA_FP4); planes as +-1
@@ -62,7 +63,7 @@ typedef enum {
                                     (the paper's recovery-oriented scheme) */
     APMM_ALGO_MFMA_KSPLIT = 8    /* APMM_ALGO_MFMA_FP4 with the K partition of paper Sec. 4.2 taken across the four waves of
                                     a workgroup as well: every wave holds the whole workgroup tile for a quarter of K, the
-                                    partial tiles are added in LDS (p = 3 or 4; chosen by AUTO for outputs of few tiles) */
+                                    partial tiles are added in LDS (chosen by AUTO for outputs of one round of tiles and long K) */
 } apmm_algo;
 
 /* Bytes of the packed form of a rows x K operand of `bits`-bit codes (paper Sec. 4.1:

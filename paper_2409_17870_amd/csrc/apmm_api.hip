@@ -163,7 +163,7 @@ apmm_status run_gemm(const apmm::GemmArgs &g, int algo, hipStream_t s, void *wor
 {
     if (algo == APMM_ALGO_AUTO) {
         if (apmm::gemm_decode_supported(g)) algo = APMM_ALGO_DECODE;
-        else if (apmm::gemm_mfma_fp4_supported(g)) algo = APMM_ALGO_MFMA_FP4;
+        else if (apmm::gemm_mfma_fp4_supported(g)) algo = apmm::gemm_mfma_ksplit_pays(g) ? APMM_ALGO_MFMA_KSPLIT : APMM_ALGO_MFMA_FP4;
         else algo = APMM_ALGO_VALU_POPCOUNT;
     }
     if (algo == APMM_ALGO_VALU_POPCOUNT || algo == APMM_ALGO_PLANE_PAIRS_GLOBAL || algo == APMM_ALGO_PLANES_REGISTERS)
@@ -178,7 +178,7 @@ apmm_status run_gemm(const apmm::GemmArgs &g, int algo, hipStream_t s, void *wor
         e = apmm::launch_gemm_mfma_fp4(g, s);
         break;
     case APMM_ALGO_MFMA_KSPLIT:
-        if (!apmm::gemm_mfma_ksplit_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: the K-split MFMA kernel covers p = 3, 4 and q in 1..4 while 4 K (2^p - 1)(2^q - 1) < 2^24");
+        if (!apmm::gemm_mfma_ksplit_supported(g)) return fail(APMM_ERR_UNSUPPORTED, "gemm: the K-split MFMA kernel covers p, q in 1..4 while 4 K (2^p - 1)(2^q - 1) < 2^24");
         e = apmm::launch_gemm_mfma_ksplit(g, s);
         break;
     case APMM_ALGO_DECODE:

@@ -43,7 +43,6 @@ bool gemm_mfma_fp4_supported(const GemmArgs &g)
 
 hipError_t launch_gemm_mfma_fp4(const GemmArgs &g, hipStream_t stream)
 {
-    if (gemm_mfma_ksplit_pays(g)) return launch_gemm_mfma_ksplit(g, stream);
     switch (g.p) {
     case 1: return launch_gemm_mfma_fp4_p1(g, stream);
     case 2: return launch_gemm_mfma_fp4_p2(g, stream);

@@ -1,39 +1,24 @@
-// Matrix-unit GEMM kernels whose four waves split K (apmm_gemm_mfma_ksplit.h): instantiations and launch rule.
-#include "apmm_gemm_mfma_ksplit.h"
+// Matrix-unit GEMM kernels whose four waves split K (apmm_gemm_mfma_ksplit.h): launch rule.  The kernels are
+// instantiated in apmm_gemm_mfma_ksplit_p<P>.hip, one translation unit per activation width.
+#include "apmm_kernels.h"
 
 namespace apmm {
 
+hipError_t launch_gemm_mfma_ksplit_p1(const GemmArgs &g, hipStream_t stream, int wn);
+hipError_t launch_gemm_mfma_ksplit_p2(const GemmArgs &g, hipStream_t stream, int wn);
+hipError_t launch_gemm_mfma_ksplit_p3(const GemmArgs &g, hipStream_t stream, int wn);
+hipError_t launch_gemm_mfma_ksplit_p4(const GemmArgs &g, hipStream_t stream, int wn);
+
 namespace {
 
-template <int P, int Q>
-hipError_t launch_ksplit_tiles(const GemmArgs &g, hipStream_t stream, int wn)
-{
-    switch (wn) {
-    case 4: return mfma::launch_ksplit_variant<P, Q, 2, 4>(g, stream);
-    case 5: return mfma::launch_ksplit_variant<P, Q, 2, 5>(g, stream);
-    default: return mfma::launch_ksplit_variant<P, Q, 2, 6>(g, stream);
-    }
-}
-
-template <int P>
-hipError_t launch_ksplit_p(const GemmArgs &g, hipStream_t stream, int wn)
-{
-    switch (g.q) {
-    case 1: return launch_ksplit_tiles<P, 1>(g, stream, wn);
-    case 2: return launch_ksplit_tiles<P, 2>(g, stream, wn);
-    case 3: return launch_ksplit_tiles<P, 3>(g, stream, wn);
-    case 4: return launch_ksplit_tiles<P, 4>(g, stream, wn);
-    }
-    return hipErrorInvalidValue;
-}
-
 // Tile width (column blocks of 32; the tile has two row blocks): the one that fills most of the 256 compute
-// units in a single round of tiles, or 0 when every width needs more than one round.
+// units in a single round of tiles, or 0 when every width needs more than one round.  Activations in the group
+// form (1 and 2 bits) have the 64 x 128 tile only.
 int one_round_width(const GemmArgs &g)
 {
     int best = 0;
     int64_t best_tiles = 0;
-    for (int wn = 4; wn <= 6; ++wn) {
+    for (int wn = 4; wn <= (activation_field_form(g.p) ? 6 : 4); ++wn) {
         const int64_t tiles = ((g.M + 63) / 64) * ((g.N + 32 * wn - 1) / (32 * wn));
         if (tiles <= 256 && tiles > best_tiles) {
             best = wn;
@@ -45,28 +30,34 @@ int one_round_width(const GemmArgs &g)
 
 }  // namespace
 
-bool gemm_mfma_ksplit_supported(const GemmArgs &g)
-{
-    return gemm_mfma_fp4_supported(g) && activation_field_form(g.p);
-}
+bool gemm_mfma_ksplit_supported(const GemmArgs &g) { return gemm_mfma_fp4_supported(g); }
 
-// Measured against the large-tile kernel (W2A4 and W1A4, 512 x 5120 outputs, fp16 output, inside a graph): equal at
-// K = 5120 and 8192 (14.5 / 21.6 us), 15 % faster at K = 13824 and 16384 (28.2 against 33.1 us): the exchange
-// through LDS and the colder start of waves that each begin at another place of K cost about 2 us per tile, the k
-// loop gains 0.5 us per 1024 elements of K.  With more than one round of tiles the large tiles win (their
-// fixed costs are paid once per larger tile).
+// Launch rule, measured against the large-tile kernel inside a graph; with more than one round of tiles the large
+// tiles win by 30 - 70 % (their fixed costs are paid once per larger tile), so one round is a condition throughout.
+//   Field form (3, 4 bits; W2A4 and W1A4, 512 x 5120 outputs, fp16 output): equal at K = 5120 and 8192 (14.5 / 21.6 us),
+//   15 % faster at K = 13824 and 16384 (28.2 against 33.1 us): the exchange through LDS and the colder start of
+//   waves that each begin at another place of K cost about 2 us per tile, the k loop gains 0.5 us per 1024
+//   elements of K.  Taken from K = 10240 on.
+//   Group form (1, 2 bits; W2A2 and W1A2, fp16 or int32 output), where the large-tile kernel has 128 x 128 tiles for
+//   these outputs: 512 x 4096 outputs 5.9 / 7.3 / 9.9 / 16.6 us against 6.7 / 7.5 / 8.6 / 11.6 us here at K = 1024 / 2048 /
+//   4096 / 8192; 512 x 4096 x 11008 22.0 against 13.8 us; 65 x 4096 and 96 x 11008 outputs faster at every K (10.7
+//   against 7.9 us at K = 4096).  Taken from K = 3072 on, and at every K up to 128 tokens.
 bool gemm_mfma_ksplit_pays(const GemmArgs &g)
 {
-    return gemm_mfma_ksplit_supported(g) && g.nkb >= 80 && one_round_width(g) != 0;
+    if (!gemm_mfma_ksplit_supported(g) || one_round_width(g) == 0) return false;
+    if (activation_field_form(g.p)) return g.nkb >= 80;
+    return g.nkb >= 24 || g.M <= 128;
 }
 
 hipError_t launch_gemm_mfma_ksplit(const GemmArgs &g, hipStream_t stream)
 {
     int wn = one_round_width(g);
-    if (wn == 0) wn = 5;  // explicit request for a shape of several rounds
+    if (wn == 0) wn = activation_field_form(g.p) ? 5 : 4;  // explicit request for a shape of several rounds
     switch (g.p) {
-    case 3: return launch_ksplit_p<3>(g, stream, wn);
-    case 4: return launch_ksplit_p<4>(g, stream, wn);
+    case 1: return launch_gemm_mfma_ksplit_p1(g, stream, wn);
+    case 2: return launch_gemm_mfma_ksplit_p2(g, stream, wn);
+    case 3: return launch_gemm_mfma_ksplit_p3(g, stream, wn);
+    case 4: return launch_gemm_mfma_ksplit_p4(g, stream, wn);
     }
     return hipErrorInvalidValue;
 }

@@ -23,8 +23,8 @@ hipError_t launch_gemm_valu(const GemmArgs &args, hipStream_t stream);
 bool gemm_mfma_fp4_supported(const GemmArgs &args);
 hipError_t launch_gemm_mfma_fp4(const GemmArgs &args, hipStream_t stream);
 
-// Design A with K split across the four waves of a workgroup (apmm_gemm_mfma_ksplit.h): for outputs of few large
-// tiles; activations in the field form (p = 3, 4), same exactness bound as above.
+// Design A with K split across the four waves of a workgroup (apmm_gemm_mfma_ksplit.h): for outputs of few
+// tiles; same widths and exactness bound as above.
 bool gemm_mfma_ksplit_supported(const GemmArgs &args);
 bool gemm_mfma_ksplit_pays(const GemmArgs &args);  // the launch rule of launch_gemm_mfma_fp4 takes it for these
 hipError_t launch_gemm_mfma_ksplit(const GemmArgs &args, hipStream_t stream);

@@ -83,7 +83,7 @@ def test_argument_errors_come_before_any_launch(lib):
     assert _gemm(lib, 4, 4, 40000, 8, 8) == OVERFLOW
     assert _gemm(lib, 64, 64, 128, 2, 2, algo=2) == INVALID         # an id no kernel of this build has
     assert _gemm(lib, 64, 64, 128, 4, 2, algo=7) == UNSUPPORTED     # plane kernels: activations of 1 or 2 bits
-    assert _gemm(lib, 64, 64, 128, 2, 2, algo=8) == UNSUPPORTED     # K split across waves: activations of 3 or 4 bits
+    assert _gemm(lib, 64, 64, 128, 5, 2, algo=8) == UNSUPPORTED     # K split across waves: p, q <= 4 like the E2M1 path
     assert _gemm(lib, 64, 64, 128, 2, 2, algo=6) == 4               # plane pairs to global memory: workspace missing
     assert lib.apmm_status_string(OVERFLOW) == b"result exceeds 32 bits"
     assert lib.apmm_pack_weights(None, 4, 128, 2, None, None) == INVALID

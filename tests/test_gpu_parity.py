@@ -669,7 +669,7 @@ def test_field_form_tile_arrangements(gpu, oracle, p, q, M, N, K):
     full_check(gpu, oracle, case, 7300 + 10 * p + q + M)
 
 
-@pytest.mark.parametrize("p,q", [(p, q) for p in (3, 4) for q in range(1, 5)])
+@pytest.mark.parametrize("p,q", [(p, q) for p in range(1, 5) for q in range(1, 5)])
 def test_k_split_across_waves_all_widths(gpu, oracle, p, q):
     """The matrix-unit kernel whose four waves split K, asked for by its algo id: several tiles, ragged M, N and K,
     K short enough that some waves get no stage, both outputs."""
@@ -687,13 +687,14 @@ def test_k_split_across_waves_all_widths(gpu, oracle, p, q):
                                                             (512, 4096, 4096, True, True, True)])
 def test_k_split_across_waves_full_tiles(gpu, oracle, M, N, K, want_i32, want_f16, scaled):
     """Shapes of one round of tiles and long K, where the launch rule itself takes the K-split kernel (the last
-    one by its algo id), one output or both, interior and border tiles, an odd output width, each of the three tile widths;
+    one with 2-bit activations), one output or both, interior and border tiles, an odd output width, each of the three tile widths;
     every output against the oracle."""
     from paper_2409_17870_amd import binding
-    case = dict(M=M, N=N, K=K, p=4, q=2, a_dist="normal", scaled=scaled)
+    p = 2 if N == 4096 else 4
+    case = dict(M=M, N=N, K=K, p=p, q=2, a_dist="normal" if p == 4 else "bernoulli", scaled=scaled)
     data = inputs.make_case(case, 8200 + M)
-    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], 4, 2)
-    c32, c16 = run_case(gpu, data, case, algo=KSPLIT if K < 10240 else 0, want_i32=want_i32, want_f16=want_f16)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, 2)
+    c32, c16 = run_case(gpu, data, case, want_i32=want_i32, want_f16=want_f16)
     assert binding.apmm_last_gemm_kernel().startswith("gemm_mfma_ksplit_kernel")
     if want_i32:
         assert np.array_equal(c32.astype(np.int64), want)
@@ -701,12 +702,26 @@ def test_k_split_across_waves_full_tiles(gpu, oracle, M, N, K, want_i32, want_f1
         check_f16(c16, want, data, oracle)
 
 
-def test_k_split_kernel_declines_group_form_activations(gpu):
+def test_k_split_kernel_declines_wide_codes(gpu):
     torch, binding = gpu
     a = torch.zeros((64, 512), dtype=torch.uint8, device="cuda:0")
     w = torch.zeros((64, 512), dtype=torch.uint8, device="cuda:0")
     with pytest.raises(binding.ApmmError):
-        binding.apmm_gemm(64, 64, 512, 2, 2, binding.apmm_pack_activations(a, 2), binding.apmm_pack_weights(w, 2), algo=KSPLIT)
+        binding.apmm_gemm(64, 64, 512, 5, 2, binding.apmm_pack_activations(a, 5), binding.apmm_pack_weights(w, 2), algo=KSPLIT)
+
+
+@pytest.mark.parametrize("M,N,K,p,q", [(65, 4096, 700, 2, 2), (128, 1000, 512, 1, 1), (300, 4000, 3100, 2, 1), (512, 4096, 3072, 1, 2)])
+def test_k_split_rule_for_group_form_activations(gpu, oracle, M, N, K, p, q):
+    """1- and 2-bit activations on outputs of one round of 64 x 128 tiles: the launch rule takes the K-split kernel up
+    to 128 tokens at any K and from K = 3072 on; int32 and fp16 outputs against the oracle."""
+    from paper_2409_17870_amd import binding
+    case = dict(M=M, N=N, K=K, p=p, q=q, a_dist="bernoulli", scaled=True)
+    data = inputs.make_case(case, 8300 + M)
+    want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
+    c32, c16 = run_case(gpu, data, case, want_i32=True, want_f16=True)
+    assert binding.apmm_last_gemm_kernel().startswith("gemm_mfma_ksplit_kernel")
+    assert np.array_equal(c32.astype(np.int64), want)
+    check_f16(c16, want, data, oracle)
 
 
 def test_config2_square_4096_w1a2(gpu, oracle):
