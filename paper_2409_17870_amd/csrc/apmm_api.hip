@@ -162,7 +162,10 @@ constexpr int kMaxProblems = 256;  // entries of one apmm_gemm_grouped call
 apmm_status run_gemm(const apmm::GemmArgs &g, int algo, hipStream_t s, void *workspace = nullptr, size_t workspace_bytes = 0)
 {
     if (algo == APMM_ALGO_AUTO) {
-        if (apmm::gemm_decode_supported(g)) algo = APMM_ALGO_DECODE;
+        // (33 - 64 tokens at more than 8192 channels: the small-M kernel needs a second round of its one-per-CU workgroups
+        // there, 10.0 us at 11008 x 4096, and the K-split kernel's 86 tiles take 7.9 - 8.6 us)
+        if (apmm::gemm_decode_supported(g) && !(g.M > 32 && g.N > 8192 && !g.a_codes && apmm::gemm_mfma_ksplit_pays(g)))
+            algo = APMM_ALGO_DECODE;
         else if (apmm::gemm_mfma_fp4_supported(g)) algo = apmm::gemm_mfma_ksplit_pays(g) ? APMM_ALGO_MFMA_KSPLIT : APMM_ALGO_MFMA_FP4;
         else algo = APMM_ALGO_VALU_POPCOUNT;
     }

@@ -912,6 +912,9 @@ hipError_t launch_gemm_decode_group(const GemmArgs *problems, int count, hipStre
             for (int i = 0; i < count; ++i) two = two && gs[i].M <= 2;
             if (two) rt = rows > 3 * 256 * kRowsPerWg ? 2 : 1;
         }
+        // four token tiles (33 - 64 tokens) with packed operands: that variant fits one workgroup per CU, so two row
+        // tiles as soon as single ones would need a second round of workgroups (8192 x 4096, 64 tokens: 5.9 us)
+        if (!gs[0].a_codes && variant == 104 && rows > 256 * kRowsPerWg) rt = 2;
         if (gs[0].a_codes && variant == 104) rt = 1;  // four token tiles from codes: two row tiles do not fit the registers
         if (!make_group(gs, count, kRowsPerWg * rt, [](const GemmArgs &g) { return g.nkb; }, ga))
             return hipErrorInvalidValue;
