@@ -20,6 +20,10 @@ outside the timed region, as an inference engine would do.  Prints ONE JSON line
 
 Other modes (markdown tables, not the default line):
   --all-configs [--configs 1,2,3,4,5]   every workload configuration against its roofline
+  --tile-designs                        large tiles against the K split across the waves of a workgroup, on outputs
+                                        of one round of tiles
+  --decode-designs                      design A (matrix unit) against design B (XOR + popcount) at the decode shape
+  --decode-layer                        the seven linears of a decoder layer as seven calls and as one grouped launch
   --paper-shapes                        the shapes of the paper's Tables 1 and 2, GEMM only, and the
                                         Sec. 4.2 ablation (plane pairs to global memory + recovery pass, planes
                                         on the matrix unit with recovery in registers) against the fused kernel
@@ -77,6 +81,8 @@ def parse_args():
     ap.add_argument("--decode-designs", action="store_true",
                     help="the decode shape (M = 1, 11008 x 4096, W2A2, packed activations, cold weights) on both designs: "
                          "matrix-unit small-M kernel and XOR/popcount small-M kernel (one JSON line)")
+    ap.add_argument("--tile-designs", action="store_true",
+                    help="large tiles against the K split across waves on outputs of one round of tiles (markdown)")
     ap.add_argument("--decode-layer", action="store_true",
                     help="the seven linears of a Llama-2-7B decoder layer at 1, 8 and 16 tokens (W2A2, fp16 epilogue, cold "
                          "weights): seven calls, and one grouped launch of seven independent problems (markdown)")
@@ -268,6 +274,37 @@ def decode_layer(args):
         best = min(t_packed, t_codes)
         print("| %d | %.1f | %.1f | %.1f | %.0f | %.0f %% |" % (M, t_calls, t_packed, t_codes, w_bytes / best / 1e3,
                                                              100.0 * w_bytes / best / 1e3 / HBM_PEAK_GBS), flush=True)
+
+
+def tile_designs(args):
+    """The two tile designs of the matrix-unit GEMM on outputs of one round of tiles: large tiles whose waves own parts
+    of the output and sweep all of K (APMM_ALGO_MFMA_FP4), and one tile per workgroup whose four waves split K
+    (APMM_ALGO_MFMA_KSPLIT).  GEMM only, fp16 output, inside a captured graph.  Under rocprofv3 the two kernels
+    appear under their own names (kernel trace, L1 / L2 request counters)."""
+    import torch
+    from paper_2409_17870_amd import binding
+    dev = torch.device("cuda:0")
+    print("| M | N | K | scheme | large tiles (us) | kernel | K split across waves (us) | kernel | AUTO takes |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    for (M, N, K, p, q) in ((512, 5120, 5120, 4, 2), (512, 5120, 13824, 4, 2), (512, 4096, 4096, 2, 2), (512, 4096, 11008, 2, 2),
+                            (128, 4096, 4096, 2, 2), (256, 4096, 11008, 2, 1)):
+        a = torch.randint(0, 1 << p, (M, K), dtype=torch.uint8, device=dev)
+        w = torch.randint(0, 1 << q, (N, K), dtype=torch.uint8, device=dev)
+        ap, wp = binding.apmm_pack_activations(a, p), binding.apmm_pack_weights(w, q)
+        sa = (torch.rand(M, device=dev) * 0.09 + 0.01).half()
+        sw = (torch.rand(N, device=dev) * 0.09 + 0.01).half()
+        h = torch.empty((M, N), dtype=torch.float16, device=dev)
+        cells = []
+        for algo in (binding.ALGO_MFMA_FP4, binding.ALGO_MFMA_KSPLIT, binding.ALGO_AUTO):
+            def call(i):
+                binding.apmm_gemm(M, N, K, p, q, ap, wp, want_i32=False, want_f16=True, w_scale=sw, a_scale=sa, c_f16=h,
+                                  algo=algo)
+            for i in range(200):   # settle the clocks on this kernel
+                call(i)
+            us = graph_us_per_call(torch, call, 20)
+            cells.append((us, binding.apmm_last_gemm_kernel()))
+        print("| %d | %d | %d | W%dA%d | %.1f | %s | %.1f | %s | %s |" % (M, N, K, q, p, cells[0][0], cells[0][1], cells[1][0],
+                                                                  cells[1][1], cells[2][1]))
 
 
 def headline(args):
@@ -627,6 +664,8 @@ def main():
         paper_shapes(args)
     elif args.decode_designs:
         decode_designs(args)
+    elif args.tile_designs:
+        tile_designs(args)
     elif args.decode_layer:
         decode_layer(args)
     else:

@@ -34,10 +34,11 @@ bool gemm_mfma_ksplit_supported(const GemmArgs &g) { return gemm_mfma_fp4_suppor
 
 // Launch rule, measured against the large-tile kernel inside a graph; with more than one round of tiles the large
 // tiles win by 30 - 70 % (their fixed costs are paid once per larger tile), so one round is a condition throughout.
-//   Field form (3, 4 bits; W2A4 and W1A4, 512 x 5120 outputs, fp16 output): equal at K = 5120 and 8192 (14.5 / 21.6 us),
-//   15 % faster at K = 13824 and 16384 (28.2 against 33.1 us): the exchange through LDS and the colder start of
-//   waves that each begin at another place of K cost about 2 us per tile, the k loop gains 0.5 us per 1024
-//   elements of K.  Taken from K = 10240 on.
+//   Field form (3, 4 bits; W2A4 and W1A4, 512 x 5120 outputs, fp16 output): slower below K = 4096 (the exchange
+//   through LDS and the colder start of waves that each begin at another place of K cost about 2 us per tile),
+//   equal to 10 % faster at K = 5120 (14.2 against 14.5 us on one box, 12.1 against 13.4 us on another), 15 - 26 %
+//   faster at K = 13824 (28.2 against 33.1, 22.5 against 30.4 us): the k loop gains 0.5 us per 1024 elements of K.
+//   Taken from K = 5120 on.
 //   Group form (1, 2 bits; W2A2 and W1A2, fp16 or int32 output), where the large-tile kernel has 128 x 128 tiles for
 //   these outputs: 512 x 4096 outputs 5.9 / 7.3 / 9.9 / 16.6 us against 6.7 / 7.5 / 8.6 / 11.6 us here at K = 1024 / 2048 /
 //   4096 / 8192; 512 x 4096 x 11008 22.0 against 13.8 us; 65 x 4096 and 96 x 11008 outputs faster at every K (10.7
@@ -45,7 +46,7 @@ bool gemm_mfma_ksplit_supported(const GemmArgs &g) { return gemm_mfma_fp4_suppor
 bool gemm_mfma_ksplit_pays(const GemmArgs &g)
 {
     if (!gemm_mfma_ksplit_supported(g) || one_round_width(g) == 0) return false;
-    if (activation_field_form(g.p)) return g.nkb >= 80;
+    if (activation_field_form(g.p)) return g.nkb >= 40;
     return g.nkb >= 24 || g.M <= 128;
 }
 
