@@ -38,7 +38,9 @@ bool gemm_mfma_ksplit_supported(const GemmArgs &g) { return gemm_mfma_fp4_suppor
 //   through LDS and the colder start of waves that each begin at another place of K cost about 2 us per tile),
 //   equal to 10 % faster at K = 5120 (14.2 against 14.5 us on one box, 12.1 against 13.4 us on another), 15 - 26 %
 //   faster at K = 13824 (28.2 against 33.1, 22.5 against 30.4 us): the k loop gains 0.5 us per 1024 elements of K.
-//   Taken from K = 5120 on.
+//   Taken from K = 5120 on; with the 64 x 128 tile (outputs of up to 256 of them, e.g. up to 512 tokens at 4096
+//   channels or 128 at 11008) already from K = 3072 on: 1 - 256 tokens at 4096 x 4096 9.4 - 9.8 against 11.2 - 12.6 us,
+//   at 4096 x 11008 15.5 - 16.2 against 22.7 - 24.1 us, equal at K = 1024.
 //   Group form (1, 2 bits; W2A2 and W1A2, fp16 or int32 output), where the large-tile kernel has 128 x 128 tiles for
 //   these outputs: 512 x 4096 outputs 5.9 / 7.3 / 9.9 / 16.6 us against 6.7 / 7.5 / 8.6 / 11.6 us here at K = 1024 / 2048 /
 //   4096 / 8192; 512 x 4096 x 11008 22.0 against 13.8 us; 65 x 4096 and 96 x 11008 outputs faster at every K (10.7
@@ -46,7 +48,7 @@ bool gemm_mfma_ksplit_supported(const GemmArgs &g) { return gemm_mfma_fp4_suppor
 bool gemm_mfma_ksplit_pays(const GemmArgs &g)
 {
     if (!gemm_mfma_ksplit_supported(g) || one_round_width(g) == 0) return false;
-    if (activation_field_form(g.p)) return g.nkb >= 40;
+    if (activation_field_form(g.p)) return g.nkb >= 40 || (one_round_width(g) == 4 && g.nkb >= 24);
     return g.nkb >= 24 || g.M <= 128;
 }
 
