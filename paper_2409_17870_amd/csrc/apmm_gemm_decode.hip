@@ -451,7 +451,10 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
                              uint32_t misc_arg /* M | problems << 8 */, int reserved_arg, uint16_t *cf_arg, int32_t *ci_arg,
                              const uint16_t *ws_arg, const uint16_t *as_arg, GroupArgs ga)
 {
-    static_assert(P <= 2 && Q <= 2, "one plane group per operand");
+    static_assert((P <= 2 || (activation_field_form(P) && CODES == 0)) && Q <= 2,
+                  "one plane group per operand, or packed activations in the field form (ready-made E2M3 operands)");
+    constexpr bool AF = activation_field_form(P);
+    constexpr int SA = activation_slots(P);  // slots of an activation row and k block
     static_assert(NJ == 8 || (NJ == 1 && CODES == 1 && TT == 1), "NJ = 1: codes of at most two tokens");
     (void)reserved_arg;
     DecodeProblem pr = {w_arg, a_arg, n_arg, k_arg, (int64_t)(misc_arg & 0xffu), cf_arg, ci_arg, ws_arg, as_arg};
@@ -477,7 +480,7 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
         wsrc[rt] = reinterpret_cast<const uint4 *>(pr.w + tile_row_word(n, 4 * wave + kq, nkb, Q, 0));
     }
     constexpr int kIterVecW = 4 * kWaves * Q * kSlotVec;     // uint4 between this lane's k blocks of consecutive iterations
-    constexpr int kIterVecA = 4 * kWaves * P * kSlotVec;
+    constexpr int kIterVecA = 4 * kWaves * SA * kSlotVec;
     const uint4 *asrc[TT];
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
@@ -486,11 +489,11 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
             // tokens past M: the padded rows of the last row block hold zero words (read, never stored)
             const int64_t t = tt * 16 + r16, t_ld = t < rows_a ? t : rows_a - 1;
             asrc[tt] = reinterpret_cast<const uint4 *>(static_cast<const uint32_t *>(pr.a) +
-                                                       tile_row_word(t_ld, 4 * wave + kq, nkb, P, 0));
+                                                       tile_row_word(t_ld, 4 * wave + kq, nkb, SA, 0));
         }
     }
 
-    uint4 wnext[RT][2], anext[TT][2];
+    uint4 wnext[RT][2], anext[TT][AF ? 6 : 2];
     auto load_packed = [&](int it) __attribute__((always_inline)) {
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt)
@@ -500,7 +503,7 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-                for (int s = 0; s < P; ++s) anext[tt][s] = asrc[tt][(int64_t)it * kIterVecA + s * kSlotVec];
+                for (int s = 0; s < SA; ++s) anext[tt][s] = asrc[tt][(int64_t)it * kIterVecA + s * kSlotVec];
         }
     };
     // CODES.  The codes of one token tile and one group of four k blocks are 16 runs of 512 contiguous bytes
@@ -626,7 +629,7 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
         const int32_t *w_sum = reinterpret_cast<const int32_t *>(pr.w + row_sum_word(rows_b, nkb, Q));
         const int32_t *a_sum = CODES ? nullptr
                                      : reinterpret_cast<const int32_t *>(static_cast<const uint32_t *>(pr.a) +
-                                                                         row_sum_word(rows_a, nkb, P));
+                                                                         row_sum_word(rows_a, nkb, SA));
         const uint16_t *dummy = reinterpret_cast<const uint16_t *>(pr.w);
 #pragma unroll
         for (int o = 0; o < OUTS; ++o) {
@@ -658,7 +661,7 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
     for (int tt = 0; tt < TT; ++tt) acc_pa[tt] = mfma::v4f{0.f, 0.f, 0.f, 0.f};
 
     for (int it = 0; it < iters; ++it) {
-        uint4 wq[RT][2], aq[TT][2];
+        uint4 wq[RT][2], aq[TT][AF ? 6 : 2];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
@@ -667,7 +670,7 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-                for (int s = 0; s < P; ++s) aq[tt][s] = anext[tt][s];
+                for (int s = 0; s < SA; ++s) aq[tt][s] = anext[tt][s];
         }
         if constexpr (CODES && TT == 1) {
             if (it + 1 < iters) load_packed(it + 1);
@@ -701,18 +704,32 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
                 }
 #pragma unroll
                 for (int tt = 0; tt < TT; ++tt) {
-                    if constexpr (P == 1) b8[tt][d] = (int)mfma::fp4_single_dword<ks, d>(aq[tt][0]);
-                    else b8[tt][d] = (int)mfma::fp4_pair_dword<ks, d>(aq[tt][0], aq[tt][1]);
+                    if constexpr (AF) {
+                    } else if constexpr (P == 1) {
+                        b8[tt][d] = (int)mfma::fp4_single_dword<ks, d>(aq[tt][0]);
+                    } else {
+                        b8[tt][d] = (int)mfma::fp4_pair_dword<ks, d>(aq[tt][0], aq[tt][1]);
+                    }
                 }
             });
-            // E8M0 exponents: 2^2 per operand turns (ua/2)(uw/2) into 4 ua uw
+            if constexpr (AF) {
+                // field form: words 6 ks .. 6 ks + 5 of the lane's 24 are the E2M3 operand of this k step as they stand
+                mfma::static_for<6>([&](auto w_c) __attribute__((always_inline)) {
+                    constexpr int w = 6 * ks + decltype(w_c)::value;
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) b8[tt][decltype(w_c)::value] = (int)mfma::vec_word<w & 3>(aq[tt][w >> 2]);
+                });
+            }
+            // E8M0 exponents: 2^2 per operand turns (ua/2)(uw/2) into 4 ua uw; field form: (ua/8)(uw/2) 2^6.
+            // Operand formats: 4 = E2M1, 2 = E2M3.
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
                 for (int tt = 0; tt < TT; ++tt)
                     acc[rt][tt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                        a8[rt], b8[tt], acc[rt][tt], 4, 4, 0, 129 + (Q == 1 ? mfma::fp4_single_exponent(ks) : 0), 0,
-                        129 + (P == 1 ? mfma::fp4_single_exponent(ks) : 0));
+                        a8[rt], b8[tt], acc[rt][tt], 4, AF ? 2 : 4, 0,
+                        (AF ? 130 : 129) + (Q == 1 ? mfma::fp4_single_exponent(ks) : 0), 0,
+                        AF ? 130 : 129 + (P == 1 ? mfma::fp4_single_exponent(ks) : 0));
             if constexpr (CODES) {
                 const mfma::v8i ones = {0x11111111, 0x11111111, 0x11111111, 0x11111111, 0, 0, 0, 0};  // E2M1 0.5 = the code 1
 #pragma unroll
@@ -776,10 +793,13 @@ size_t decode_mfma_lds_bytes(const GemmArgs &g, int rt)
     return (size_t)kWaves * rt * tt * 256 * 4 + (size_t)kWaves * tt * 16 * 4 + (g.a_codes ? (size_t)kWaves * (g.p == 1 ? 4096 : 2048) : 0);
 }
 
+// 1- and 2-bit codes up to 64 tokens; packed 3- and 4-bit activations (field form) with 1- and 2-bit weights up to 32
+// tokens (two token tiles: their 24 words per row and k block leave no registers for four)
 bool decode_mfma_supported(const GemmArgs &g)
 {
-    return g.M >= kMfmaMinTokens && g.M <= 64 && g.p <= 2 && g.q <= 2 && g.K <= 0x7fffffffLL && g.N <= 0x7fffffffLL &&
-           4 * g.nkb * kKBlock * 9 < (1 << 24);
+    const bool widths = g.q <= 2 && (g.p <= 2 || (activation_field_form(g.p) && !g.a_codes && g.M <= 32));
+    return g.M >= kMfmaMinTokens && g.M <= 64 && widths && g.K <= 0x7fffffffLL && g.N <= 0x7fffffffLL &&
+           4 * g.nkb * kKBlock * ((1 << g.p) - 1) * ((1 << g.q) - 1) < (1 << 24);
 }
 
 template <class Kernel>
@@ -813,6 +833,10 @@ hipError_t launch_decode_mfma_v(const GroupArgs &ga, hipStream_t stream)
         lds = lds > decode_mfma_lds_bytes(ga.g[i], RT) ? lds : decode_mfma_lds_bytes(ga.g[i], RT);
     static bool attr_set[4] = {false, false, false, false};
     note_kernel("gemm_decode_mfma_kernel<%d,%d,%d,%d,%s>", P, Q, TT, RT, ga.g[0].a_codes ? "codes" : "packed");
+    if constexpr (activation_field_form(P)) {  // packed operands only
+        if (ga.g[0].a_codes) return hipErrorInvalidValue;
+        return launch_group_scalars(gemm_decode_mfma_kernel<P, Q, TT, RT, 0>, attr_set[0], ga, lds, stream);
+    } else
     if (ga.g[0].a_codes) {
         // (four token tiles from codes with two row tiles would not fit the registers: the launcher never asks for it)
         if constexpr (TT == 4 && RT == 2) {
@@ -839,6 +863,11 @@ hipError_t launch_decode_mfma_v(const GroupArgs &ga, hipStream_t stream)
 template <int P, int Q>
 hipError_t launch_decode_mfma_pq(const GroupArgs &ga, int tt, int rt, hipStream_t stream)
 {
+    if constexpr (activation_field_form(P)) {  // one or two token tiles
+        if (tt > 2) return hipErrorInvalidValue;
+        if (rt == 2) return tt == 1 ? launch_decode_mfma_v<P, Q, 1, 2>(ga, stream) : launch_decode_mfma_v<P, Q, 2, 2>(ga, stream);
+        return tt == 1 ? launch_decode_mfma_v<P, Q, 1, 1>(ga, stream) : launch_decode_mfma_v<P, Q, 2, 1>(ga, stream);
+    } else
     if (rt == 2) {
         if (tt == 1) return launch_decode_mfma_v<P, Q, 1, 2>(ga, stream);
         if (tt == 2) return launch_decode_mfma_v<P, Q, 2, 2>(ga, stream);
@@ -855,7 +884,11 @@ hipError_t launch_decode_mfma(const GroupArgs &ga, int rt, hipStream_t stream)
     if (p == 1 && q == 1) return launch_decode_mfma_pq<1, 1>(ga, tt, rt, stream);
     if (p == 1 && q == 2) return launch_decode_mfma_pq<1, 2>(ga, tt, rt, stream);
     if (p == 2 && q == 1) return launch_decode_mfma_pq<2, 1>(ga, tt, rt, stream);
-    return launch_decode_mfma_pq<2, 2>(ga, tt, rt, stream);
+    if (p == 2 && q == 2) return launch_decode_mfma_pq<2, 2>(ga, tt, rt, stream);
+    if (p == 3 && q == 1) return launch_decode_mfma_pq<3, 1>(ga, tt, rt, stream);
+    if (p == 3 && q == 2) return launch_decode_mfma_pq<3, 2>(ga, tt, rt, stream);
+    if (p == 4 && q == 1) return launch_decode_mfma_pq<4, 1>(ga, tt, rt, stream);
+    return launch_decode_mfma_pq<4, 2>(ga, tt, rt, stream);
 }
 
 // kernel variant that serves a problem: 0 = none, 100 + token tiles = matrix unit, else the token tile of the
@@ -863,8 +896,8 @@ hipError_t launch_decode_mfma(const GroupArgs &ga, int rt, hipStream_t stream)
 int decode_variant(const GemmArgs &g, bool xor_only = false)
 {
     if (g.M < 1 || g.M > 64 || g.q < 1 || g.q > 4) return 0;
-    if (activation_field_form(g.p)) return 0;  // 3- and 4-bit activations are laid out for the large-tile MFMA kernel
     if (!xor_only && decode_mfma_supported(g)) return 100 + decode_token_tiles(g.M);
+    if (activation_field_form(g.p)) return 0;  // the XOR/popcount kernel reads the group form only
     if (g.M > 16) return 0;
     return decode_pass_kb(g, decode_mt(g.M)) > 0 ? decode_mt(g.M) : 0;
 }
