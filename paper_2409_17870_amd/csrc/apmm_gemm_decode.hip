@@ -427,7 +427,7 @@ struct DecodeProblem {
 __device__ __forceinline__ int pick_problem(DecodeProblem &pr, uint32_t misc, const GroupArgs &ga)
 {
     int block = (int)blockIdx.x;
-    const int count = (int)(misc >> 8);
+    const int count = (int)((misc >> 12) & 0xffu);
     if (count > 1) {
         int idx = 0;
         for (int i = 0; i + 1 < count; ++i)
@@ -448,7 +448,7 @@ __device__ __forceinline__ int pick_problem(DecodeProblem &pr, uint32_t misc, co
 template <int P, int Q, int TT, int RT, int CODES, int NJ = 8>
 __global__ __launch_bounds__(kThreads, (CODES == 1 && TT == 1) ? (NJ == 1 && RT == 1 ? 6 : 4) : 2)  // waves per SIMD aimed at
 void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg, int k_arg,
-                             uint32_t misc_arg /* M | problems << 8 */, int reserved_arg, uint16_t *cf_arg, int32_t *ci_arg,
+                             uint32_t misc_arg /* M | problems << 12 | token groups << 24 */, int reserved_arg, uint16_t *cf_arg, int32_t *ci_arg,
                              const uint16_t *ws_arg, const uint16_t *as_arg, GroupArgs ga)
 {
     static_assert((P <= 2 || (activation_field_form(P) && CODES == 0)) && Q <= 2,
@@ -457,9 +457,20 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
     constexpr int SA = activation_slots(P);  // slots of an activation row and k block
     static_assert(NJ == 8 || (NJ == 1 && CODES == 1 && TT == 1), "NJ = 1: codes of at most two tokens");
     (void)reserved_arg;
-    DecodeProblem pr = {w_arg, a_arg, n_arg, k_arg, (int64_t)(misc_arg & 0xffu), cf_arg, ci_arg, ws_arg, as_arg};
-    const int block = pick_problem(pr, misc_arg, ga);
+    DecodeProblem pr = {w_arg, a_arg, n_arg, k_arg, (int64_t)(misc_arg & 0xfffu), cf_arg, ci_arg, ws_arg, as_arg};
+    int block = pick_problem(pr, misc_arg, ga);
     constexpr int ROWS = kRowsPerWg * RT;
+    // Token groups (packed operands, one problem per launch): with more tokens than the TT tiles of a workgroup hold,
+    // the grid is repeated per group of 16 TT tokens; a workgroup re-reads its 16 or 32 packed weight rows (from L2,
+    // a few KiB) and works on tokens tok0 ... of the same packed operands and outputs.
+    int tok0 = 0;
+    if constexpr (!CODES) {
+        if ((misc_arg >> 24) > 1) {
+            const int per_group = (int)((pr.N + ROWS - 1) / ROWS);
+            tok0 = (block / per_group) * 16 * TT;
+            block %= per_group;
+        }
+    }
     constexpr int OUTS = (TT * RT * 256 + kThreads - 1) / kThreads;  // outputs per thread
     constexpr uint32_t ca = (1u << P) - 1, cw = (1u << Q) - 1;
     constexpr int kSlotVec = kPlaneWords / 4;
@@ -487,7 +498,7 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
         asrc[tt] = nullptr;
         if constexpr (!CODES) {
             // tokens past M: the padded rows of the last row block hold zero words (read, never stored)
-            const int64_t t = tt * 16 + r16, t_ld = t < rows_a ? t : rows_a - 1;
+            const int64_t t = tok0 + tt * 16 + r16, t_ld = t < rows_a ? t : rows_a - 1;
             asrc[tt] = reinterpret_cast<const uint4 *>(static_cast<const uint32_t *>(pr.a) +
                                                        tile_row_word(t_ld, 4 * wave + kq, nkb, SA, 0));
         }
@@ -637,7 +648,7 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
             // t = rt * TT + tt; 16x16 accumulator layout: lane l, register v holds row 4*(l/16) + v (weight row),
             // column l%16 (token)
             const int e = tid + o * kThreads, t = e >> 8, v = (e >> 6) & 3, l = e & 63;
-            out_m[o] = (t % TT) * 16 + (l & 15);
+            out_m[o] = tok0 + (t % TT) * 16 + (l & 15);
             out_n[o] = n0 + (t / TT) * 16 + 4 * (l >> 4) + v;
             out_ok[o] = t < TT * RT && out_m[o] < pr.M && out_n[o] < pr.N;
             const int64_t m_c = out_m[o] < rows_a ? out_m[o] : rows_a - 1, n_c = out_n[o] < rows_b ? out_n[o] : rows_b - 1;
@@ -784,21 +795,29 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
     }
 }
 
-int decode_token_tiles(int64_t M) { return M <= 16 ? 1 : M <= 32 ? 2 : 4; }
+// token tiles of 16 per workgroup, and groups of that many tokens per launch (packed operands only)
+int decode_token_tiles(const GemmArgs &g) { return g.M <= 16 ? 1 : (g.M <= 32 || activation_field_form(g.p)) ? 2 : 4; }
+int decode_token_groups(const GemmArgs &g) { return (int)((g.M + 16 * decode_token_tiles(g) - 1) / (16 * decode_token_tiles(g))); }
+// (measured, W2A2 / W2A4 against the K-split kernel at 4096 x 4096: two groups of 64 tokens 7.5 - 8.0 against 7.8 - 8.5 us,
+// three and four groups 11.3 - 14.7 against 7.9 - 8.1 us; two groups of 32 tokens with 4-bit activations 6.4 - 6.6 against
+// 9.4 - 10.2 us: only the last is offered)
+constexpr int kMaxTokenGroups = 2;
 
 size_t decode_mfma_lds_bytes(const GemmArgs &g, int rt)
 {
-    const int tt = decode_token_tiles(g.M);
+    const int tt = decode_token_tiles(g);
     // accumulator partials + code sums + (codes) the waves' exchange areas
     return (size_t)kWaves * rt * tt * 256 * 4 + (size_t)kWaves * tt * 16 * 4 + (g.a_codes ? (size_t)kWaves * (g.p == 1 ? 4096 : 2048) : 0);
 }
 
-// 1- and 2-bit codes up to 64 tokens; packed 3- and 4-bit activations (field form) with 1- and 2-bit weights up to 32
-// tokens (two token tiles: their 24 words per row and k block leave no registers for four)
+// 1- and 2-bit codes, up to 64 tokens; packed 3- and 4-bit activations (field form) with 1- and 2-bit weights, 32
+// tokens per workgroup (two token tiles: their 24 words per row and k block leave no registers for four) and up to
+// two such token groups per launch
 bool decode_mfma_supported(const GemmArgs &g)
 {
-    const bool widths = g.q <= 2 && (g.p <= 2 || (activation_field_form(g.p) && !g.a_codes && g.M <= 32));
-    return g.M >= kMfmaMinTokens && g.M <= 64 && widths && g.K <= 0x7fffffffLL && g.N <= 0x7fffffffLL &&
+    const bool widths = g.q <= 2 && (g.p <= 2 || (activation_field_form(g.p) && !g.a_codes));
+    const int64_t per_wg = activation_field_form(g.p) ? 32 : 64;
+    return g.M >= kMfmaMinTokens && g.M <= (activation_field_form(g.p) ? kMaxTokenGroups * per_wg : per_wg) && widths && g.K <= 0x7fffffffLL && g.N <= 0x7fffffffLL &&
            4 * g.nkb * kKBlock * ((1 << g.p) - 1) * ((1 << g.q) - 1) < (1 << 24);
 }
 
@@ -813,8 +832,10 @@ hipError_t launch_group_scalars(Kernel kernel, bool &attr_set, const GroupArgs &
     }
     const GemmArgs &g = ga.g[0];
     const void *a = g.a_codes ? static_cast<const void *>(g.a_codes) : static_cast<const void *>(g.a);
-    const uint32_t misc = (uint32_t)g.M | ((uint32_t)ga.count << 8);
-    const dim3 grid((unsigned)ga.wg_end[ga.count - 1]), block(kThreads);
+    const int groups = ga.count == 1 && !g.a_codes ? decode_token_groups(g) : 1;
+    const uint32_t misc = (uint32_t)g.M | ((uint32_t)ga.count << 12) | ((uint32_t)groups << 24);
+    if ((int64_t)ga.wg_end[ga.count - 1] * groups > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(ga.wg_end[ga.count - 1] * groups)), block(kThreads);
     const KernelTiming timing = take_kernel_timing();
     if (timing.start || timing.stop)
         hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, timing.start, timing.stop, 0, g.w, a, (int)g.N, (int)g.K,
@@ -880,7 +901,7 @@ hipError_t launch_decode_mfma_pq(const GroupArgs &ga, int tt, int rt, hipStream_
 
 hipError_t launch_decode_mfma(const GroupArgs &ga, int rt, hipStream_t stream)
 {
-    const int p = ga.g[0].p, q = ga.g[0].q, tt = decode_token_tiles(ga.g[0].M);
+    const int p = ga.g[0].p, q = ga.g[0].q, tt = decode_token_tiles(ga.g[0]);
     if (p == 1 && q == 1) return launch_decode_mfma_pq<1, 1>(ga, tt, rt, stream);
     if (p == 1 && q == 2) return launch_decode_mfma_pq<1, 2>(ga, tt, rt, stream);
     if (p == 2 && q == 1) return launch_decode_mfma_pq<2, 1>(ga, tt, rt, stream);
@@ -896,7 +917,7 @@ hipError_t launch_decode_mfma(const GroupArgs &ga, int rt, hipStream_t stream)
 int decode_variant(const GemmArgs &g, bool xor_only = false)
 {
     if (g.M < 1 || g.M > 64 || g.q < 1 || g.q > 4) return 0;
-    if (!xor_only && decode_mfma_supported(g)) return 100 + decode_token_tiles(g.M);
+    if (!xor_only && decode_mfma_supported(g)) return 100 + decode_token_tiles(g);
     if (activation_field_form(g.p)) return 0;  // the XOR/popcount kernel reads the group form only
     if (g.M > 16) return 0;
     return decode_pass_kb(g, decode_mt(g.M)) > 0 ? decode_mt(g.M) : 0;
@@ -914,7 +935,8 @@ bool gemm_decode_group_supported(const GemmArgs *gs, int count)
     const int v = decode_variant(gs[0]);
     for (int i = 0; i < count; ++i)
         if (decode_variant(gs[i]) != v || gs[i].p != gs[0].p || gs[i].q != gs[0].q ||
-            (gs[i].a_codes != nullptr) != (gs[0].a_codes != nullptr))
+            (gs[i].a_codes != nullptr) != (gs[0].a_codes != nullptr) ||
+            (count > 1 && v > 100 && decode_token_groups(gs[i]) > 1))  // token groups: single-problem launches only
             return false;
     return v != 0;
 }

@@ -48,7 +48,7 @@ KernelTiming take_kernel_timing();  // returns the pair and clears it
 void note_kernel(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
 const char *last_kernel();
 
-// Small-M weight-streaming kernels: on the matrix unit for q <= 2 with p <= 2 (M <= 64) or packed p = 3, 4 (M <= 32),
+// Small-M weight-streaming kernels: on the matrix unit for q <= 2 with p <= 2 (M <= 64) or packed p = 3, 4 (M <= 64),
 // XOR/popcount for wider codes (M <= 16, p not 3 or 4).
 bool gemm_decode_supported(const GemmArgs &args);
 hipError_t launch_gemm_decode(const GemmArgs &args, hipStream_t stream);
