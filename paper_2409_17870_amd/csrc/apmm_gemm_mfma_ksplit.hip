@@ -11,14 +11,15 @@ hipError_t launch_gemm_mfma_ksplit_p4(const GemmArgs &g, hipStream_t stream, int
 
 namespace {
 
-// Tile width (column blocks of 32; the tile has two row blocks): the one that fills most of the 256 compute
-// units in a single round of tiles, or 0 when every width needs more than one round.  Activations in the group
-// form (1 and 2 bits) have the 64 x 128 tile only.
+// Tile width (column blocks of 32: 2, 4, 5 or 6; the tile has two row blocks): the one that fills most of the 256
+// compute units in a single round of tiles, i.e. the narrowest with at most 256 tiles, or 0 when every width needs
+// more than one round.  Activations in the group form (1 and 2 bits) have the 64 x 64 and 64 x 128 tiles only.
 int one_round_width(const GemmArgs &g)
 {
     int best = 0;
     int64_t best_tiles = 0;
-    for (int wn = 4; wn <= (activation_field_form(g.p) ? 6 : 4); ++wn) {
+    for (int wn = 2; wn <= (activation_field_form(g.p) ? 6 : 4); ++wn) {
+        if (wn == 3) continue;
         const int64_t tiles = ((g.M + 63) / 64) * ((g.N + 32 * wn - 1) / (32 * wn));
         if (tiles <= 256 && tiles > best_tiles) {
             best = wn;
@@ -45,9 +46,14 @@ bool gemm_mfma_ksplit_supported(const GemmArgs &g) { return gemm_mfma_fp4_suppor
 //   these outputs: 512 x 4096 outputs 5.9 / 7.3 / 9.9 / 16.6 us against 6.7 / 7.5 / 8.6 / 11.6 us here at K = 1024 / 2048 /
 //   4096 / 8192; 512 x 4096 x 11008 22.0 against 13.8 us; 65 x 4096 and 96 x 11008 outputs faster at every K (10.7
 //   against 7.9 us at K = 4096).  Taken from K = 3072 on, and at every K up to 128 tokens.
+//   The 64 x 64 tile (outputs of up to 256 of them: up to 256 tokens at 4096 channels, 128 at 8192), every width:
+//   65 - 256 tokens at 4096 x 4096 5.3 - 5.9 us (W1A1, W2A2), 6.9 - 7.4 us (W2A4) against 7.5 - 8.5 and 9.6 - 9.9 us with the
+//   64 x 128 tile and 9.3 - 11.5 us on the large tiles; at 4096 x 11008 7.4 - 8.5 and 10.7 - 11.9 against 11.0 - 12.1 and
+//   15.8 - 16.5 us; at K = 1024 4.4 - 5.0 against 5.5 - 6.6 us on the large tiles.  Taken at every K.
 bool gemm_mfma_ksplit_pays(const GemmArgs &g)
 {
     if (!gemm_mfma_ksplit_supported(g) || one_round_width(g) == 0) return false;
+    if (one_round_width(g) == 2) return true;
     if (activation_field_form(g.p)) return g.nkb >= 40 || (one_round_width(g) == 4 && g.nkb >= 24);
     return g.nkb >= 24 || g.M <= 128;
 }

@@ -7,7 +7,8 @@ namespace {
 template <int Q>
 hipError_t launch_q(const GemmArgs &g, hipStream_t stream, int wn)
 {
-    (void)wn;  // activations in the group form: the 64 x 128 tile only (the wider ones measured slower)
+    // activations in the group form: the 64 x 64 and 64 x 128 tiles (the wider ones measured slower)
+    if (wn == 2) return mfma::launch_ksplit_variant<1, Q, 2, 2>(g, stream);
     return mfma::launch_ksplit_variant<1, Q, 2, 4>(g, stream);
 }
 }  // namespace

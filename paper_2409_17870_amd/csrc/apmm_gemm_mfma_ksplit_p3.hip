@@ -8,6 +8,7 @@ template <int Q>
 hipError_t launch_q(const GemmArgs &g, hipStream_t stream, int wn)
 {
     switch (wn) {
+    case 2: return mfma::launch_ksplit_variant<3, Q, 2, 2>(g, stream);
     case 4: return mfma::launch_ksplit_variant<3, Q, 2, 4>(g, stream);
     case 5: return mfma::launch_ksplit_variant<3, Q, 2, 5>(g, stream);
     default: return mfma::launch_ksplit_variant<3, Q, 2, 6>(g, stream);

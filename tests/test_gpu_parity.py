@@ -700,7 +700,8 @@ def test_field_form_tile_arrangements(gpu, oracle, p, q, M, N, K):
 def test_k_split_across_waves_all_widths(gpu, oracle, p, q):
     """The matrix-unit kernel whose four waves split K, asked for by its algo id: several tiles, ragged M, N and K,
     K short enough that some waves get no stage, both outputs."""
-    for M, N, K in ((70, 170, 600), (130, 333, 1100 + 512 * q), (64, 160, 100)):
+    # (the last shape is one round of 64 x 128 tiles but more than 256 of 64 x 64: the wider tile; the others the 64 x 64 one)
+    for M, N, K in ((70, 170, 600), (130, 333, 1100 + 512 * q), (64, 160, 100), (300, 3400, 700)):
         case = dict(M=M, N=N, K=K, p=p, q=q, a_dist="bernoulli", scaled=True)
         data = inputs.make_case(case, 8100 + 16 * p + q + M)
         want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
@@ -711,11 +712,13 @@ def test_k_split_across_waves_all_widths(gpu, oracle, p, q):
 
 @pytest.mark.parametrize("M,N,K,want_i32,want_f16,scaled", [(512, 5120, 10240, False, True, True), (448, 1000, 12800, True, False, False),
                                                             (200, 5001, 10300, True, True, True), (512, 6000, 10240, False, True, True),
-                                                            (512, 4096, 4096, True, True, True)])
+                                                            (512, 4096, 4096, True, True, True), (512, 4000, 5120, True, True, True),
+                                                            (128, 8192, 1024, False, True, True)])
 def test_k_split_across_waves_full_tiles(gpu, oracle, M, N, K, want_i32, want_f16, scaled):
     """Shapes of one round of tiles and long K, where the launch rule itself takes the K-split kernel (the last
-    one with 2-bit activations), one output or both, interior and border tiles, an odd output width, each of the three tile widths;
-    every output against the oracle."""
+    one with 2-bit activations), one output or both, interior and border tiles, an odd output width, each of the four tile
+    widths (64 x 64 at 448 x 1001 and 128 x 8192, 64 x 128 at 512 x 4096 / 4000, 64 x 160 at 512 x 5120 and 200 x 5001, 64 x 192 at
+    512 x 6000); every output against the oracle."""
     from paper_2409_17870_amd import binding
     p = 2 if N == 4096 else 4
     case = dict(M=M, N=N, K=K, p=p, q=2, a_dist="normal" if p == 4 else "bernoulli", scaled=scaled)
