@@ -451,8 +451,11 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
                              uint32_t misc_arg /* M | problems << 12 | token groups << 24 */, int reserved_arg, uint16_t *cf_arg, int32_t *ci_arg,
                              const uint16_t *ws_arg, const uint16_t *as_arg, GroupArgs ga)
 {
-    static_assert((P <= 2 || (activation_field_form(P) && CODES == 0)) && Q <= 2,
-                  "one plane group per operand, or packed activations in the field form (ready-made E2M3 operands)");
+    static_assert((P <= 2 || (activation_field_form(P) && CODES == 0)) && (Q <= 2 || (Q <= 4 && CODES == 0)),
+                  "one plane group per activation, or packed activations in the field form (ready-made E2M3 operands); "
+                  "weights of one plane group, or of two with packed activations");
+    constexpr int WS = Q > 2 ? Q : 2;        // weight slots held per channel tile
+    constexpr int NG = pair_groups(Q) + (has_single_group(Q) ? 1 : 0);  // plane groups of the weights
     constexpr bool AF = activation_field_form(P);
     constexpr int SA = activation_slots(P);  // slots of an activation row and k block
     static_assert(NJ == 8 || (NJ == 1 && CODES == 1 && TT == 1), "NJ = 1: codes of at most two tokens");
@@ -504,7 +507,7 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
         }
     }
 
-    uint4 wnext[RT][2], anext[TT][AF ? 6 : 2];
+    uint4 wnext[RT][WS], anext[TT][AF ? 6 : 2];
     auto load_packed = [&](int it) __attribute__((always_inline)) {
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt)
@@ -672,7 +675,7 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
     for (int tt = 0; tt < TT; ++tt) acc_pa[tt] = mfma::v4f{0.f, 0.f, 0.f, 0.f};
 
     for (int it = 0; it < iters; ++it) {
-        uint4 wq[RT][2], aq[TT][AF ? 6 : 2];
+        uint4 wq[RT][WS], aq[TT][AF ? 6 : 2];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
@@ -701,18 +704,11 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
         }
         mfma::static_for<4>([&](auto ks_c) __attribute__((always_inline)) {
             constexpr int ks = decltype(ks_c)::value;
-            mfma::v8i a8[RT], b8[TT];
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt) a8[rt] = mfma::v8i{0, 0, 0, 0, 0, 0, 0, 0};
+            mfma::v8i b8[TT];
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) b8[tt] = mfma::v8i{0, 0, 0, 0, 0, 0, 0, 0};
             mfma::static_for<4>([&](auto d_c) __attribute__((always_inline)) {
                 constexpr int d = decltype(d_c)::value;
-#pragma unroll
-                for (int rt = 0; rt < RT; ++rt) {
-                    if constexpr (Q == 1) a8[rt][d] = (int)mfma::fp4_single_dword<ks, d>(wq[rt][0]);
-                    else a8[rt][d] = (int)mfma::fp4_pair_dword<ks, d>(wq[rt][0], wq[rt][1]);
-                }
 #pragma unroll
                 for (int tt = 0; tt < TT; ++tt) {
                     if constexpr (AF) {
@@ -731,16 +727,34 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
                     for (int tt = 0; tt < TT; ++tt) b8[tt][decltype(w_c)::value] = (int)mfma::vec_word<w & 3>(aq[tt][w >> 2]);
                 });
             }
+            // One MFMA per plane group of the weights (pair groups at code bits 2 g, a single group at bit Q - 1), all into
+            // the same accumulator: the group's bit position goes into the weights' power-of-two operand scale.
             // E8M0 exponents: 2^2 per operand turns (ua/2)(uw/2) into 4 ua uw; field form: (ua/8)(uw/2) 2^6.
             // Operand formats: 4 = E2M1, 2 = E2M3.
+            mfma::static_for<NG>([&](auto g_c) __attribute__((always_inline)) {
+                constexpr int grp = decltype(g_c)::value;
+                constexpr bool SINGLE = grp >= pair_groups(Q);
+                constexpr int slot = SINGLE ? Q - 1 : 2 * grp;
+                mfma::v8i a8[RT];
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt)
+                for (int rt = 0; rt < RT; ++rt) a8[rt] = mfma::v8i{0, 0, 0, 0, 0, 0, 0, 0};
+                mfma::static_for<4>([&](auto d_c) __attribute__((always_inline)) {
+                    constexpr int d = decltype(d_c)::value;
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
-                    acc[rt][tt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                        a8[rt], b8[tt], acc[rt][tt], 4, AF ? 2 : 4, 0,
-                        (AF ? 130 : 129) + (Q == 1 ? mfma::fp4_single_exponent(ks) : 0), 0,
-                        AF ? 130 : 129 + (P == 1 ? mfma::fp4_single_exponent(ks) : 0));
+                    for (int rt = 0; rt < RT; ++rt) {
+                        if constexpr (SINGLE) a8[rt][d] = (int)mfma::fp4_single_dword<ks, d>(wq[rt][slot]);
+                        else a8[rt][d] = (int)mfma::fp4_pair_dword<ks, d>(wq[rt][slot], wq[rt][slot + 1]);
+                    }
+                });
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+                        acc[rt][tt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                            a8[rt], b8[tt], acc[rt][tt], 4, AF ? 2 : 4, 0,
+                            (AF ? 130 : 129) + slot + (SINGLE ? mfma::fp4_single_exponent(ks) : 0), 0,
+                            AF ? 130 : 129 + (P == 1 ? mfma::fp4_single_exponent(ks) : 0));
+            });
             if constexpr (CODES) {
                 const mfma::v8i ones = {0x11111111, 0x11111111, 0x11111111, 0x11111111, 0, 0, 0, 0};  // E2M1 0.5 = the code 1
 #pragma unroll
@@ -815,7 +829,7 @@ size_t decode_mfma_lds_bytes(const GemmArgs &g, int rt)
 // two such token groups per launch
 bool decode_mfma_supported(const GemmArgs &g)
 {
-    const bool widths = g.q <= 2 && (g.p <= 2 || (activation_field_form(g.p) && !g.a_codes));
+    const bool widths = (g.q <= 2 || (g.q <= 4 && !g.a_codes)) && (g.p <= 2 || (activation_field_form(g.p) && !g.a_codes));
     const int64_t per_wg = activation_field_form(g.p) ? 32 : 64;
     return g.M >= kMfmaMinTokens && g.M <= (activation_field_form(g.p) ? kMaxTokenGroups * per_wg : per_wg) && widths && g.K <= 0x7fffffffLL && g.N <= 0x7fffffffLL &&
            4 * g.nkb * kKBlock * ((1 << g.p) - 1) * ((1 << g.q) - 1) < (1 << 24);
@@ -854,7 +868,7 @@ hipError_t launch_decode_mfma_v(const GroupArgs &ga, hipStream_t stream)
         lds = lds > decode_mfma_lds_bytes(ga.g[i], RT) ? lds : decode_mfma_lds_bytes(ga.g[i], RT);
     static bool attr_set[4] = {false, false, false, false};
     note_kernel("gemm_decode_mfma_kernel<%d,%d,%d,%d,%s>", P, Q, TT, RT, ga.g[0].a_codes ? "codes" : "packed");
-    if constexpr (activation_field_form(P)) {  // packed operands only
+    if constexpr (activation_field_form(P) || Q > 2) {  // packed operands only
         if (ga.g[0].a_codes) return hipErrorInvalidValue;
         return launch_group_scalars(gemm_decode_mfma_kernel<P, Q, TT, RT, 0>, attr_set[0], ga, lds, stream);
     } else
@@ -909,7 +923,12 @@ hipError_t launch_decode_mfma(const GroupArgs &ga, int rt, hipStream_t stream)
     if (p == 3 && q == 1) return launch_decode_mfma_pq<3, 1>(ga, tt, rt, stream);
     if (p == 3 && q == 2) return launch_decode_mfma_pq<3, 2>(ga, tt, rt, stream);
     if (p == 4 && q == 1) return launch_decode_mfma_pq<4, 1>(ga, tt, rt, stream);
-    return launch_decode_mfma_pq<4, 2>(ga, tt, rt, stream);
+    if (p == 4 && q == 2) return launch_decode_mfma_pq<4, 2>(ga, tt, rt, stream);
+    // weights of two plane groups (packed activations only)
+    if (q == 3) return p == 1 ? launch_decode_mfma_pq<1, 3>(ga, tt, rt, stream) : p == 2 ? launch_decode_mfma_pq<2, 3>(ga, tt, rt, stream)
+                     : p == 3 ? launch_decode_mfma_pq<3, 3>(ga, tt, rt, stream) : launch_decode_mfma_pq<4, 3>(ga, tt, rt, stream);
+    return p == 1 ? launch_decode_mfma_pq<1, 4>(ga, tt, rt, stream) : p == 2 ? launch_decode_mfma_pq<2, 4>(ga, tt, rt, stream)
+         : p == 3 ? launch_decode_mfma_pq<3, 4>(ga, tt, rt, stream) : launch_decode_mfma_pq<4, 4>(ga, tt, rt, stream);
 }
 
 // kernel variant that serves a problem: 0 = none, 100 + token tiles = matrix unit, else the token tile of the

@@ -181,14 +181,14 @@ def test_wide_codes(gpu, oracle, p, q):
 @pytest.mark.parametrize("p,q", [(3, 3), (4, 4), (4, 1), (3, 2), (4, 2), (3, 1)])
 @pytest.mark.parametrize("M", [1, 7, 16, 17, 32, 33, 50, 64, 65])
 def test_few_tokens_with_field_form_activations(gpu, oracle, M, p, q):
-    """3- and 4-bit activations (field form).  With 1- and 2-bit weights the small-M matrix-unit kernel takes the packed
-    6-bit fields as its E2M3 operand for up to 64 tokens (two groups of 32 from 33 on); wider weights, more tokens
+    """3- and 4-bit activations (field form).  The small-M matrix-unit kernel takes the packed 6-bit fields as its E2M3
+    operand for up to 64 tokens (two groups of 32 from 33 on), with weights of one or two plane groups; more tokens
     and the XOR/popcount small-M kernel decline, and automatic selection serves every case."""
     torch, binding = gpu
     case = dict(M=M, N=203, K=1100, p=p, q=q, a_dist="bernoulli", scaled=True)
     data = inputs.make_case(case, 5500 + 100 * M + 10 * p + q)
     want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
-    if q <= 2 and M <= 64:
+    if M <= 64:
         c32, c16 = run_case(gpu, data, case, algo=DECODE)
         assert binding.apmm_last_gemm_kernel().startswith("gemm_decode_mfma_kernel<%d,%d" % (p, q))
         assert np.array_equal(c32.astype(np.int64), want)
