@@ -248,10 +248,7 @@ apmm_status apmm_gemm_from_codes(int64_t M, int64_t N, int64_t K, int p, int q, 
     // Every workgroup of the small-M kernels loads all M x K codes for itself: that beats a packing launch
     // (2.5 - 3 us) up to 16 tokens at every width measured (16 tokens x 11008 channels: 7.3 us in one launch, 7.2 us
     // in two), and for more tokens while M x N is small.
-    // With weights of 3 or 4 bits (and 1 - 2-bit activations) the one-launch form is the XOR/popcount kernel, whose time
-    // grows with tokens x plane pairs (W4A2 at 4096 x 4096: 3.7 / 6.0 / 9.2 us for 1 / 4 / 8 tokens), while packing
-    // (2.5 - 3 us) plus the matrix-unit small-M kernel on packed operands takes about 6 us at any token count.
-    const bool fused_pays = q > 2 && p <= 2 ? M * p * q <= 32 : (M <= 16 || M * N <= 65536);
+    const bool fused_pays = M <= 16 || M * N <= 65536;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (fused_ok && (fused_pays || !room)) {
         const hipError_t e = apmm::launch_gemm_decode(g, s);

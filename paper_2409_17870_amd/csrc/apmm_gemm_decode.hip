@@ -446,14 +446,14 @@ __device__ __forceinline__ int pick_problem(DecodeProblem &pr, uint32_t misc, co
 }
 
 template <int P, int Q, int TT, int RT, int CODES, int NJ = 8>
-__global__ __launch_bounds__(kThreads, (CODES == 1 && TT == 1) ? (NJ == 1 && RT == 1 ? 6 : 4) : 2)  // waves per SIMD aimed at
+__global__ __launch_bounds__(kThreads, (CODES == 1 && TT == 1) ? (NJ == 1 && RT == 1 ? 6 : 4) - (Q > 2 ? 1 : 0) : 2)  // waves per SIMD aimed at (weights of two plane groups hold twice the raw words)
 void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg, int k_arg,
                              uint32_t misc_arg /* M | problems << 12 | token groups << 24 */, int reserved_arg, uint16_t *cf_arg, int32_t *ci_arg,
                              const uint16_t *ws_arg, const uint16_t *as_arg, GroupArgs ga)
 {
-    static_assert((P <= 2 || (activation_field_form(P) && CODES == 0)) && (Q <= 2 || (Q <= 4 && CODES == 0)),
+    static_assert((P <= 2 || (activation_field_form(P) && CODES == 0)) && Q <= 4,
                   "one plane group per activation, or packed activations in the field form (ready-made E2M3 operands); "
-                  "weights of one plane group, or of two with packed activations");
+                  "weights of one or two plane groups");
     constexpr int WS = Q > 2 ? Q : 2;        // weight slots held per channel tile
     constexpr int NG = pair_groups(Q) + (has_single_group(Q) ? 1 : 0);  // plane groups of the weights
     constexpr bool AF = activation_field_form(P);
@@ -829,7 +829,7 @@ size_t decode_mfma_lds_bytes(const GemmArgs &g, int rt)
 // two such token groups per launch
 bool decode_mfma_supported(const GemmArgs &g)
 {
-    const bool widths = (g.q <= 2 || (g.q <= 4 && !g.a_codes)) && (g.p <= 2 || (activation_field_form(g.p) && !g.a_codes));
+    const bool widths = g.q <= 4 && (g.p <= 2 || (activation_field_form(g.p) && !g.a_codes));
     const int64_t per_wg = activation_field_form(g.p) ? 32 : 64;
     return g.M >= kMfmaMinTokens && g.M <= (activation_field_form(g.p) ? kMaxTokenGroups * per_wg : per_wg) && widths && g.K <= 0x7fffffffLL && g.N <= 0x7fffffffLL &&
            4 * g.nkb * kKBlock * ((1 << g.p) - 1) * ((1 << g.q) - 1) < (1 << 24);
@@ -868,7 +868,7 @@ hipError_t launch_decode_mfma_v(const GroupArgs &ga, hipStream_t stream)
         lds = lds > decode_mfma_lds_bytes(ga.g[i], RT) ? lds : decode_mfma_lds_bytes(ga.g[i], RT);
     static bool attr_set[4] = {false, false, false, false};
     note_kernel("gemm_decode_mfma_kernel<%d,%d,%d,%d,%s>", P, Q, TT, RT, ga.g[0].a_codes ? "codes" : "packed");
-    if constexpr (activation_field_form(P) || Q > 2) {  // packed operands only
+    if constexpr (activation_field_form(P)) {  // packed operands only
         if (ga.g[0].a_codes) return hipErrorInvalidValue;
         return launch_group_scalars(gemm_decode_mfma_kernel<P, Q, TT, RT, 0>, attr_set[0], ga, lds, stream);
     } else
@@ -902,15 +902,16 @@ hipError_t launch_decode_mfma_pq(const GroupArgs &ga, int tt, int rt, hipStream_
         if (tt > 2) return hipErrorInvalidValue;
         if (rt == 2) return tt == 1 ? launch_decode_mfma_v<P, Q, 1, 2>(ga, stream) : launch_decode_mfma_v<P, Q, 2, 2>(ga, stream);
         return tt == 1 ? launch_decode_mfma_v<P, Q, 1, 1>(ga, stream) : launch_decode_mfma_v<P, Q, 2, 1>(ga, stream);
-    } else
-    if (rt == 2) {
-        if (tt == 1) return launch_decode_mfma_v<P, Q, 1, 2>(ga, stream);
-        if (tt == 2) return launch_decode_mfma_v<P, Q, 2, 2>(ga, stream);
-        return launch_decode_mfma_v<P, Q, 4, 2>(ga, stream);
+    } else {
+        if (rt == 2) {
+            if (tt == 1) return launch_decode_mfma_v<P, Q, 1, 2>(ga, stream);
+            if (tt == 2) return launch_decode_mfma_v<P, Q, 2, 2>(ga, stream);
+            return launch_decode_mfma_v<P, Q, 4, 2>(ga, stream);
+        }
+        if (tt == 1) return launch_decode_mfma_v<P, Q, 1, 1>(ga, stream);
+        if (tt == 2) return launch_decode_mfma_v<P, Q, 2, 1>(ga, stream);
+        return launch_decode_mfma_v<P, Q, 4, 1>(ga, stream);
     }
-    if (tt == 1) return launch_decode_mfma_v<P, Q, 1, 1>(ga, stream);
-    if (tt == 2) return launch_decode_mfma_v<P, Q, 2, 1>(ga, stream);
-    return launch_decode_mfma_v<P, Q, 4, 1>(ga, stream);
 }
 
 hipError_t launch_decode_mfma(const GroupArgs &ga, int rt, hipStream_t stream)
@@ -990,6 +991,9 @@ hipError_t launch_gemm_decode_group(const GemmArgs *problems, int count, hipStre
         // tiles as soon as single ones would need a second round of workgroups (8192 x 4096, 64 tokens: 5.9 us)
         if (!gs[0].a_codes && variant == 104 && rows > 256 * kRowsPerWg) rt = 2;
         if (gs[0].a_codes && variant == 104) rt = 1;  // four token tiles from codes: two row tiles do not fit the registers
+        // weights of two plane groups from codes: the two-tile variant fits three waves per SIMD only (11008 x 4096, 4 / 16
+        // tokens: 7.8 / 9.4 us against 6.3 / 7.9 us with single tiles)
+        if (gs[0].a_codes && gs[0].q > 2) rt = 1;
         if (!make_group(gs, count, kRowsPerWg * rt, [](const GemmArgs &g) { return g.nkb; }, ga))
             return hipErrorInvalidValue;
         return launch_decode_mfma(ga, rt, stream);

@@ -292,8 +292,8 @@ def test_gemm_from_codes_few_tokens(gpu, oracle, M, p, q):
     check_f16(c16, want, data, oracle)
 
 
-@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (1, 2), (2, 2)])
-@pytest.mark.parametrize("M,N,K", [(17, 203, 1100), (32, 64, 4096), (50, 203, 1111), (64, 16421, 300), (5, 16421, 300)])
+@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (1, 2), (2, 2), (2, 4), (1, 3), (2, 3), (1, 4)])
+@pytest.mark.parametrize("M,N,K", [(17, 203, 1100), (32, 64, 4096), (50, 203, 1111), (64, 16421, 300), (5, 16421, 300), (2, 300, 4096)])
 def test_gemm_from_codes_token_tiles(gpu, oracle, M, N, K, p, q):
     """The same on the matrix-unit small-M kernel with one, two and four token tiles and both row-tile counts."""
     case = dict(M=M, N=N, K=K, p=p, q=q, a_dist="bernoulli", scaled=True)
