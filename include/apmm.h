@@ -47,7 +47,7 @@ typedef enum {
     APMM_ALGO_AUTO = 0,
     APMM_ALGO_VALU_POPCOUNT = 1, /* plane pairs by XOR + popcount on the vector ALU, D_ij = K - 2*popc */
     APMM_ALGO_DECODE = 3,        /* small-M weight-streaming kernels: on the matrix unit for p, q <= 4 and M <= 64 (unpacked
-                                    activation codes: p <= 2); else XOR + popcount for M <= 16, q <= 4 and p not 3 or 4 */
+                                    activation codes of 3 and 4 bits: M <= 32); else XOR + popcount for M <= 16, q <= 4 and p not 3 or 4 */
     APMM_ALGO_MFMA_FP4 = 4,      /* plane groups recombined to E2M1 codes in registers, f8f6f4 MFMA, exact fp32 accumulate
                                     (p, q <= 4 and 4 * roundup(K,512) * (2^p-1)(2^q-1) < 2^24); the large-tile kernel, every
                                     wave sweeping all of K */

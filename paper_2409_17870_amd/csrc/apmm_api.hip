@@ -248,7 +248,9 @@ apmm_status apmm_gemm_from_codes(int64_t M, int64_t N, int64_t K, int p, int q, 
     // Every workgroup of the small-M kernels loads all M x K codes for itself: that beats a packing launch
     // (2.5 - 3 us) up to 16 tokens at every width measured (16 tokens x 11008 channels: 7.3 us in one launch, 7.2 us
     // in two), and for more tokens while M x N is small.
-    const bool fused_pays = M <= 16 || M * N <= 65536;
+    // (3- and 4-bit activations: turning codes into 6-bit fields costs more, the one-launch form wins up to 8 tokens:
+    // W2A4 at 11008 x 4096 6.0 / 7.5 / 9.6 us for 1 / 8 / 16 tokens against about 8 - 8.8 us in two launches)
+    const bool fused_pays = apmm::activation_field_form(p) ? (M <= 8 || M * N <= 65536) : (M <= 16 || M * N <= 65536);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (fused_ok && (fused_pays || !room)) {
         const hipError_t e = apmm::launch_gemm_decode(g, s);

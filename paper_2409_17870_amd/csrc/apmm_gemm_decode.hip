@@ -451,8 +451,8 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
                              uint32_t misc_arg /* M | problems << 12 | token groups << 24 */, int reserved_arg, uint16_t *cf_arg, int32_t *ci_arg,
                              const uint16_t *ws_arg, const uint16_t *as_arg, GroupArgs ga)
 {
-    static_assert((P <= 2 || (activation_field_form(P) && CODES == 0)) && Q <= 4,
-                  "one plane group per activation, or packed activations in the field form (ready-made E2M3 operands); "
+    static_assert((P <= 2 || (activation_field_form(P) && NJ == 8)) && Q <= 4,
+                  "one plane group per activation, or activations in the field form (ready-made E2M3 operands); "
                   "weights of one or two plane groups");
     constexpr int WS = Q > 2 ? Q : 2;        // weight slots held per channel tile
     constexpr int NG = pair_groups(Q) + (has_single_group(Q) ? 1 : 0);  // plane groups of the weights
@@ -527,7 +527,8 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
     // each chunk into that word with seven operations and the words change lanes through a piece of LDS that
     // belongs to the wave alone (no workgroup barrier): lane (r16, kq) reads back the eight words of token r16 in
     // k block kq, its MFMA fragment.
-    constexpr int kXposeWords = P == 1 ? 1024 : 512;  // per wave: [token 16][k block 4][word 8] (single group: two partial words each)
+    // per wave: [token 16][k block 4][word 8] (single group: two partial words each; field form: 24 words)
+    constexpr int kXposeWords = AF ? 1536 : P == 1 ? 1024 : 512;
     uint32_t *xpose = reinterpret_cast<uint32_t *>(lds_raw) + kWaves * RT * TT * 256 + kWaves * TT * 16 + wave * kXposeWords;
     // CODES == 1: K is a multiple of 16 and the matrix starts at a multiple of 16 bytes, so every chunk is one
     // aligned 16-byte load and lies wholly inside the row or wholly in the padding.  The loads are issued without
@@ -575,7 +576,7 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
             }
         }
     };
-    auto chunks_to_fragment = [&](int tt, int it, const uint4 (&v)[NJ], uint4 (&aq)[2]) __attribute__((always_inline)) {
+    auto chunks_to_fragment = [&](int tt, int it, const uint4 (&v)[NJ], uint4 (&aq)[AF ? 6 : 2]) __attribute__((always_inline)) {
         constexpr uint32_t code_mask = 0x01010101u * ca;
         // the wave's previous fragment has been read by every lane before anything is overwritten
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -599,7 +600,19 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
             // dword i = 2 t2 + jh of the chunk holds the elements (t = 2 tp + t2, jh, c = 0..3) of the word
             const uint32_t d0 = (v[jj].x & m_and) | m_or, d1 = (v[jj].y & m_and) | m_or, d2 = (v[jj].z & m_and) | m_or,
                            d3 = (v[jj].w & m_and) | m_or;
-            if constexpr (P == 2) {
+            if constexpr (AF) {
+                // Field form: the chunk's 16 codes are the fields 16 tp ... 16 tp + 15 of k step w / 2 (tp = w % 2), i.e. words
+                // 6 (w / 2) + 3 tp ... + 2 of the row's 24: byte c of dword i goes to field 8 (i / 2) + 2 c + i % 2, six bits each.
+                auto spread12 = [](uint32_t x) __attribute__((always_inline)) {  // byte c -> bits 12 c ... 12 c + 7
+                    return (uint64_t)((x & 0xffu) | ((x & 0xff00u) << 4) | ((x & 0xff0000u) << 8)) | ((uint64_t)(x >> 24) << 36);
+                };
+                const uint64_t lo = spread12(d0) | (spread12(d1) << 6), hi = spread12(d2) | (spread12(d3) << 6);  // 48 bits each
+                const int token = 2 * jj + (lane >> 5), kb = (lane & 31) >> 3;
+                uint32_t *dst = xpose + (token * 4 + kb) * 24 + 6 * (w >> 1) + 3 * (w & 1);
+                dst[0] = (uint32_t)lo;
+                dst[1] = (uint32_t)(lo >> 32) | ((uint32_t)hi << 16);
+                dst[2] = (uint32_t)(hi >> 16);
+            } else if constexpr (P == 2) {
                 // S[w]: bit b of element (t2, jh, c) at 8c + 4jh + 2 t2 + b
                 xpose[64 * jj + slot] = d0 | (d1 << 4) | (d2 << 2) | (d3 << 6);
             } else {
@@ -612,7 +625,10 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         const int mine = (r16 * 4 + kq) * 8;
-        if constexpr (P == 2) {
+        if constexpr (AF) {
+#pragma unroll
+            for (int i = 0; i < 6; ++i) aq[i] = *reinterpret_cast<const uint4 *>(xpose + 3 * mine + 4 * i);
+        } else if constexpr (P == 2) {
             aq[0] = *reinterpret_cast<const uint4 *>(xpose + mine);
             aq[1] = *reinterpret_cast<const uint4 *>(xpose + mine + 4);
         } else {
@@ -760,7 +776,8 @@ void gemm_decode_mfma_kernel(const uint32_t *w_arg, const void *a_arg, int n_arg
 #pragma unroll
                 for (int tt = 0; tt < TT; ++tt)
                     acc_pa[tt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                        ones, b8[tt], acc_pa[tt], 4, 4, 0, 129, 0, 129 + (P == 1 ? mfma::fp4_single_exponent(ks) : 0));
+                        ones, b8[tt], acc_pa[tt], 4, AF ? 2 : 4, 0, AF ? 130 : 129, 0,
+                        AF ? 130 : 129 + (P == 1 ? mfma::fp4_single_exponent(ks) : 0));
             }
         });
     }
@@ -821,7 +838,7 @@ size_t decode_mfma_lds_bytes(const GemmArgs &g, int rt)
 {
     const int tt = decode_token_tiles(g);
     // accumulator partials + code sums + (codes) the waves' exchange areas
-    return (size_t)kWaves * rt * tt * 256 * 4 + (size_t)kWaves * tt * 16 * 4 + (g.a_codes ? (size_t)kWaves * (g.p == 1 ? 4096 : 2048) : 0);
+    return (size_t)kWaves * rt * tt * 256 * 4 + (size_t)kWaves * tt * 16 * 4 + (g.a_codes ? (size_t)kWaves * (activation_field_form(g.p) ? 6144 : g.p == 1 ? 4096 : 2048) : 0);
 }
 
 // 1- and 2-bit codes, up to 64 tokens; packed 3- and 4-bit activations (field form) with 1- and 2-bit weights, 32
@@ -829,9 +846,9 @@ size_t decode_mfma_lds_bytes(const GemmArgs &g, int rt)
 // two such token groups per launch
 bool decode_mfma_supported(const GemmArgs &g)
 {
-    const bool widths = g.q <= 4 && (g.p <= 2 || (activation_field_form(g.p) && !g.a_codes));
+    const bool widths = g.q <= 4 && (g.p <= 2 || activation_field_form(g.p));
     const int64_t per_wg = activation_field_form(g.p) ? 32 : 64;
-    return g.M >= kMfmaMinTokens && g.M <= (activation_field_form(g.p) ? kMaxTokenGroups * per_wg : per_wg) && widths && g.K <= 0x7fffffffLL && g.N <= 0x7fffffffLL &&
+    return g.M >= kMfmaMinTokens && g.M <= (activation_field_form(g.p) && !g.a_codes ? kMaxTokenGroups * per_wg : per_wg) && widths && g.K <= 0x7fffffffLL && g.N <= 0x7fffffffLL &&
            4 * g.nkb * kKBlock * ((1 << g.p) - 1) * ((1 << g.q) - 1) < (1 << 24);
 }
 
@@ -868,8 +885,18 @@ hipError_t launch_decode_mfma_v(const GroupArgs &ga, hipStream_t stream)
         lds = lds > decode_mfma_lds_bytes(ga.g[i], RT) ? lds : decode_mfma_lds_bytes(ga.g[i], RT);
     static bool attr_set[4] = {false, false, false, false};
     note_kernel("gemm_decode_mfma_kernel<%d,%d,%d,%d,%s>", P, Q, TT, RT, ga.g[0].a_codes ? "codes" : "packed");
-    if constexpr (activation_field_form(P)) {  // packed operands only
-        if (ga.g[0].a_codes) return hipErrorInvalidValue;
+    if constexpr (activation_field_form(P)) {  // from codes: single channel tiles only
+        if (ga.g[0].a_codes) {
+            if constexpr (RT == 1) {
+                bool vec_ok = true;
+                for (int i = 0; i < ga.count; ++i)
+                    vec_ok = vec_ok && (ga.g[i].K & 15) == 0 && (reinterpret_cast<uintptr_t>(ga.g[i].a_codes) & 15) == 0;
+                if (vec_ok) return launch_group_scalars(gemm_decode_mfma_kernel<P, Q, TT, RT, 1>, attr_set[1], ga, lds, stream);
+                return launch_group_scalars(gemm_decode_mfma_kernel<P, Q, TT, RT, 2>, attr_set[2], ga, lds, stream);
+            } else {
+                return hipErrorInvalidValue;
+            }
+        }
         return launch_group_scalars(gemm_decode_mfma_kernel<P, Q, TT, RT, 0>, attr_set[0], ga, lds, stream);
     } else
     if (ga.g[0].a_codes) {
@@ -993,7 +1020,7 @@ hipError_t launch_gemm_decode_group(const GemmArgs *problems, int count, hipStre
         if (gs[0].a_codes && variant == 104) rt = 1;  // four token tiles from codes: two row tiles do not fit the registers
         // weights of two plane groups from codes: the two-tile variant fits three waves per SIMD only (11008 x 4096, 4 / 16
         // tokens: 7.8 / 9.4 us against 6.3 / 7.9 us with single tiles)
-        if (gs[0].a_codes && gs[0].q > 2) rt = 1;
+        if (gs[0].a_codes && (gs[0].q > 2 || activation_field_form(gs[0].p))) rt = 1;  // (field-form codes: single tiles only)
         if (!make_group(gs, count, kRowsPerWg * rt, [](const GemmArgs &g) { return g.nkb; }, ga))
             return hipErrorInvalidValue;
         return launch_decode_mfma(ga, rt, stream);

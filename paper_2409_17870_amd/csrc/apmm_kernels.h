@@ -48,7 +48,7 @@ KernelTiming take_kernel_timing();  // returns the pair and clears it
 void note_kernel(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
 const char *last_kernel();
 
-// Small-M weight-streaming kernels: on the matrix unit for p, q <= 4 (M <= 64; activations of 3 and 4 bits with packed operands only), XOR/popcount for wider codes (M <= 16, p not 3 or 4).
+// Small-M weight-streaming kernels: on the matrix unit for p, q <= 4 (M <= 64; unpacked activation codes of 3 and 4 bits: M <= 32), XOR/popcount for wider codes (M <= 16, p not 3 or 4).
 bool gemm_decode_supported(const GemmArgs &args);
 hipError_t launch_gemm_decode(const GemmArgs &args, hipStream_t stream);
 // The XOR/popcount small-M kernel whatever the code widths (M <= 16, q <= 4): design B at decode shapes.

@@ -279,7 +279,7 @@ def run_from_codes(gpu, data, case, dirty_high_bits=False, workspace=False):
     return c32.cpu().numpy(), c16.cpu().numpy()
 
 
-@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (1, 2), (2, 2), (5, 3), (2, 4), (8, 2), (1, 4), (6, 4)])
+@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (1, 2), (2, 2), (5, 3), (2, 4), (8, 2), (1, 4), (6, 4), (4, 2), (3, 1), (4, 4), (3, 3)])
 @pytest.mark.parametrize("M", [1, 2, 3, 5, 8, 13, 16])
 def test_gemm_from_codes_few_tokens(gpu, oracle, M, p, q):
     """GEMM straight from the activation codes, both small-M kernels, ragged N and K (K = 1100 is neither a
@@ -292,14 +292,15 @@ def test_gemm_from_codes_few_tokens(gpu, oracle, M, p, q):
     check_f16(c16, want, data, oracle)
 
 
-@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (1, 2), (2, 2), (2, 4), (1, 3), (2, 3), (1, 4)])
+@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (1, 2), (2, 2), (2, 4), (1, 3), (2, 3), (1, 4), (4, 2), (3, 4), (4, 1)])
 @pytest.mark.parametrize("M,N,K", [(17, 203, 1100), (32, 64, 4096), (50, 203, 1111), (64, 16421, 300), (5, 16421, 300), (2, 300, 4096)])
 def test_gemm_from_codes_token_tiles(gpu, oracle, M, N, K, p, q):
     """The same on the matrix-unit small-M kernel with one, two and four token tiles and both row-tile counts."""
     case = dict(M=M, N=N, K=K, p=p, q=q, a_dist="bernoulli", scaled=True)
     data = inputs.make_case(case, 6900 + M + 10 * p + q)
     want = oracle.gemm_i64(data["a_codes"], data["w_codes"], p, q)
-    c32, c16 = run_from_codes(gpu, data, case)
+    # (3- and 4-bit activations have the one-launch form up to 32 tokens; beyond, the call needs its workspace)
+    c32, c16 = run_from_codes(gpu, data, case, workspace=(p in (3, 4) and M > 32))
     assert np.array_equal(c32.astype(np.int64), want)
     check_f16(c16, want, data, oracle)
 
@@ -315,7 +316,7 @@ def test_gemm_from_codes_unaligned_rows_and_refusals(gpu, oracle):
     assert np.array_equal(c32.astype(np.int64), want)
     check_f16(c16, want, data, oracle)
     dev = torch.device("cuda:0")
-    for (M, p, q) in ((65, 2, 2), (17, 5, 2), (4, 4, 2), (4, 2, 5)):
+    for (M, p, q) in ((65, 2, 2), (17, 5, 2), (33, 4, 2), (4, 2, 5)):
         a = torch.zeros((M, 256), dtype=torch.uint8, device=dev)
         wp = binding.apmm_pack_weights(torch.zeros((32, 256), dtype=torch.uint8, device=dev), q)
         with pytest.raises(binding.ApmmError) as err:
