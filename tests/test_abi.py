@@ -116,7 +116,7 @@ def test_new_entry_points_check_their_arguments(lib):
     WORKSPACE = 4
     assert fc(65, 8, 128, 2, 2, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE
     assert fc(17, 8, 128, 5, 2, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE
-    assert fc(4, 8, 128, 4, 2, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE
+    assert fc(33, 8, 128, 4, 2, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE     # 4-bit activations: one launch up to 32 tokens
     assert fc(4, 8, 128, 2, 5, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE
     assert fc(40, 8, 1 << 20, 2, 2, 0x1001, 0x2000, 0x3000, None, None, None, None, 0, None) == WORKSPACE   # K beyond the exact fp32 range
     need = lib.apmm_packed_activation_bytes(65, 128, 2)
