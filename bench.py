@@ -22,6 +22,8 @@ Other modes (markdown tables, not the default line):
   --all-configs [--configs 1,2,3,4,5]   every workload configuration against its roofline
   --tile-designs                        large tiles against the K split across the waves of a workgroup, on outputs
                                         of one round of tiles
+  --small-m                             1 - 64 tokens over code widths (packed and from codes) and one token over growing
+                                        weight matrices
   --decode-designs                      design A (matrix unit) against design B (XOR + popcount) at the decode shape
   --decode-layer                        the seven linears of a decoder layer as seven calls and as one grouped launch
   --paper-shapes                        the shapes of the paper's Tables 1 and 2, GEMM only, and the
@@ -83,6 +85,8 @@ def parse_args():
                          "matrix-unit small-M kernel and XOR/popcount small-M kernel (one JSON line)")
     ap.add_argument("--tile-designs", action="store_true",
                     help="large tiles against the K split across waves on outputs of one round of tiles (markdown)")
+    ap.add_argument("--small-m", action="store_true",
+                    help="the small-M path over code widths and weight sizes (markdown)")
     ap.add_argument("--decode-layer", action="store_true",
                     help="the seven linears of a Llama-2-7B decoder layer at 1, 8 and 16 tokens (W2A2, fp16 epilogue, cold "
                          "weights): seven calls, and one grouped launch of seven independent problems (markdown)")
@@ -305,6 +309,54 @@ def tile_designs(args):
             cells.append((us, binding.apmm_last_gemm_kernel()))
         print("| %d | %d | %d | W%dA%d | %.1f | %s | %.1f | %s | %s |" % (M, N, K, q, p, cells[0][0], cells[0][1], cells[1][0],
                                                                   cells[1][1], cells[2][1]))
+
+
+def small_m(args):
+    """The small-M path over code widths and weight sizes.  First table: 1 / 16 / 64 tokens at 4096 x 4096 and
+    11008 x 4096 for several schemes, packed activations and from codes, whatever kernel AUTO takes.  Second table: one
+    token at W2A2 from codes over growing weight matrices.  Weights rotate over more than 512 MiB of packed copies;
+    microseconds per call inside a captured graph."""
+    import torch
+    from paper_2409_17870_amd import binding
+    dev = torch.device("cuda:0")
+
+    def timed(M, N, K, p, q, codes):
+        a = torch.randint(0, 1 << p, (M, K), dtype=torch.uint8, device=dev)
+        wp0 = binding.apmm_pack_weights(torch.randint(0, 1 << q, (N, K), dtype=torch.uint8, device=dev), q)
+        copies = int((512 << 20) // (N * K * q / 8.0)) + 2
+        wps = [wp0] + [wp0.clone() for _ in range(copies - 1)]
+        ap = binding.apmm_pack_activations(a, p)
+        ws = torch.empty(binding.apmm_packed_activation_bytes(M, K, p), dtype=torch.uint8, device=dev)
+        sa = (torch.rand(M, device=dev) * 0.09 + 0.01).half()
+        sw = (torch.rand(N, device=dev) * 0.09 + 0.01).half()
+        h = torch.empty((M, N), dtype=torch.float16, device=dev)
+
+        def call(i):
+            if codes:
+                binding.apmm_gemm_from_codes(a, N, p, q, wps[i % copies], want_i32=False, want_f16=True, w_scale=sw,
+                                             a_scale=sa, c_f16=h, workspace=ws)
+            else:
+                binding.apmm_gemm(M, N, K, p, q, ap, wps[i % copies], want_i32=False, want_f16=True, w_scale=sw,
+                                  a_scale=sa, c_f16=h)
+        for i in range(copies):
+            call(i)
+        return graph_us_per_call(torch, call, copies), binding.apmm_last_gemm_kernel()
+
+    print("| scheme | N | K | tokens | packed (us) | kernel | from codes (us) | kernel (the last one, when a packing launch precedes it) |")
+    print("|---|---|---|---|---|---|---|---|")
+    for (p, q) in ((2, 2), (2, 4), (4, 2), (4, 4), (1, 1)):
+        for (N, K) in ((4096, 4096), (11008, 4096)):
+            for M in (1, 16, 64):
+                tp, kp = timed(M, N, K, p, q, False)
+                tc, kc = timed(M, N, K, p, q, True)
+                print("| W%dA%d | %d | %d | %d | %.1f | %s | %.1f | %s |" % (q, p, N, K, M, tp, kp, tc, kc))
+    print()
+    print("| N | K | packed weights (MiB) | one token, W2A2, from codes (us) | TB/s of weights | of the HBM peak |")
+    print("|---|---|---|---|---|---|")
+    for (N, K) in ((4096, 4096), (11008, 4096), (32000, 4096), (28672, 8192), (8192, 28672), (128256, 4096)):
+        t, _ = timed(1, N, K, 2, 2, True)
+        b = N * K * 2 / 8.0
+        print("| %d | %d | %.1f | %.1f | %.2f | %.0f %% |" % (N, K, b / 2 ** 20, t, b / t / 1e6, 100 * b / t / 1e6 / 8.0))
 
 
 def headline(args):
@@ -666,6 +718,8 @@ def main():
         decode_designs(args)
     elif args.tile_designs:
         tile_designs(args)
+    elif args.small_m:
+        small_m(args)
     elif args.decode_layer:
         decode_layer(args)
     else:

@@ -1017,6 +1017,10 @@ hipError_t launch_gemm_decode_group(const GemmArgs *problems, int count, hipStre
         // four token tiles (33 - 64 tokens) with packed operands: that variant fits one workgroup per CU, so two row
         // tiles as soon as single ones would need a second round of workgroups (8192 x 4096, 64 tokens: 5.9 us)
         if (!gs[0].a_codes && variant == 104 && rows > 256 * kRowsPerWg) rt = 2;
+        // packed 3- and 4-bit activations: 88 registers leave two workgroups per CU, so two channel tiles as soon as single
+        // ones would need a second round of workgroups (W2A4, one token at 11008 x 4096, cold weights: 7.4 us with single tiles)
+        // (with weights of two plane groups the two-tile variant holds too many raw words: 8.8 against 8.2 us for W4A4)
+        if (!gs[0].a_codes && activation_field_form(gs[0].p) && gs[0].q <= 2 && rows > 2 * 256 * kRowsPerWg) rt = 2;
         if (gs[0].a_codes && variant == 104) rt = 1;  // four token tiles from codes: two row tiles do not fit the registers
         // weights of two plane groups from codes: the two-tile variant fits three waves per SIMD only (11008 x 4096, 4 / 16
         // tokens: 7.8 / 9.4 us against 6.3 / 7.9 us with single tiles)
